@@ -1,0 +1,208 @@
+#!/usr/bin/env python3
+"""Benchmark of the LQ-SGD compressor on one MI355X.
+
+A step is one whole iteration of the hot path (error-feedback add, both
+power-iteration products, Gram-Schmidt, both quantised exchanges with the
+on-device mean over W workers, reconstruction, residual update, and the plain
+mean of the 1-D tensors) over one batch of synthetic gradients that is already
+resident in HBM.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload resnet18]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
+# algorithmic HBM bytes per gradient element of one worker, per streaming sweep
+SWEEP_BYTES = {"add_project_kernel": 12.0, "back_project_kernel": 4.0, "residual_kernel": 8.0}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="resnet18", choices=["fc_256x128", "small_cnn", "resnet18", "llm_stack", "sweep_8192"])
+    ap.add_argument("--rank", type=int, default=None)
+    ap.add_argument("--bits", type=int, default=None)
+    ap.add_argument("--workers", type=int, default=None)
+    ap.add_argument("--llm-layers", type=int, default=32)
+    ap.add_argument("--no-ghat", action="store_true", help="do not write G-hat (state update only)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-timing", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (W simulated workers share it; "
+              "no collectives are built) -- run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2506_17974_amd import binding as B
+    from paper_2506_17974_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the compressor has no CPU path", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+
+    mk = {"fc_256x128": wl.fc_256x128, "small_cnn": wl.small_cnn, "resnet18": wl.resnet18,
+          "llm_stack": lambda: wl.llm_stack(args.llm_layers), "sweep_8192": wl.sweep_8192}[args.workload]
+    w = mk()
+    over = {}
+    if args.rank is not None:
+        over["rank"] = args.rank
+    if args.bits is not None:
+        over["bits"] = args.bits
+    if args.workers is not None:
+        over["workers"] = args.workers
+    if over:
+        w = wl.scaled(w, **over)
+    L, V, W = len(w.layers), len(w.vectors), w.workers
+
+    # ---- synthetic inputs, resident in HBM before anything is timed -----
+    grads = []
+    for k in range(W):
+        row = [wl.device_gradient(w, 0, l, k) for l in range(L)]
+        row += [torch.from_numpy(wl.vector_gradient(w, 0, v, k)).cuda() for v in range(V)]
+        grads.append(row)
+    ghat = None
+    if not args.no_ghat:
+        ghat = [torch.empty(s, device="cuda") for s in w.layers] + [torch.empty(n, device="cuda") for n in w.vectors]
+    comp = B.Compressor(B.layer_list(w.layers, w.vectors), w.rank, w.bits, w.bits, W, w.alpha)
+    q0 = [wl.initial_q(w, l) for l in range(L)]
+    for l in range(L):
+        comp.set_q(l, q0[l])
+    tab = comp.pointer_table(grads)
+    import ctypes as C
+    gt = None
+    if ghat is not None:
+        gt = (C.c_void_p * (L + V))()
+        for i, t in enumerate(ghat):
+            gt[i] = t.data_ptr()
+
+    def run(n):
+        for _ in range(n):
+            comp.step_raw(tab, gt)
+
+    run(args.warmup)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run(args.steps)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    grad_bytes = w.gradient_bytes
+    value = grad_bytes / (ms_per_step * 1e-3) / 1e9
+
+    # ---- per-kernel durations: HIP events on the library's own stream ----
+    roofline = None
+    kernels = {}
+    if not args.no_kernel_timing:
+        comp.timing_enable(True)
+        run(args.steps)
+        ms, cnt = comp.timing_read()
+        comp.timing_enable(False)
+        elems = W * w.elements_per_worker
+        for k in range(B.KERNEL_COUNT):
+            if cnt[k]:
+                name = B.kernel_name(k) + ("_q" if k == B.KERNEL_EXCHANGE_Q else "_p" if k == B.KERNEL_EXCHANGE_P else "")
+                kernels[name] = {"avg_us": 1e3 * ms[k] / cnt[k], "launches": cnt[k]}
+        dom = max((k for k in kernels), key=lambda n: kernels[n]["avg_us"])
+        per_elem = SWEEP_BYTES.get(dom)
+        if per_elem is not None:
+            alg = per_elem * elems
+            if dom == "residual_kernel" and ghat is not None:
+                alg += 4.0 * w.elements_per_worker          # G-hat, once per layer
+            achieved = alg / (kernels[dom]["avg_us"] * 1e-6) / 1e9
+            roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                        "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                        "traffic": _measured_traffic(dom, w.name),
+                        "algorithmic_bytes_per_launch": alg,
+                        "avg_launch_us": round(kernels[dom]["avg_us"], 2)}
+        for n, d in kernels.items():
+            if n in SWEEP_BYTES:
+                alg = SWEEP_BYTES[n] * elems + (4.0 * w.elements_per_worker if (n == "residual_kernel" and ghat is not None) else 0.0)
+                d["hbm_frac"] = round(alg / (d["avg_us"] * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)
+            d["avg_us"] = round(d["avg_us"], 2)
+
+    # ---- the oracle on the host cores, same inputs, bounded sample -------
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = _cpu_baseline(w, grads, q0)
+
+    step_bytes = 24.0 * W * w.elements_per_worker + (4.0 * w.elements_per_worker if ghat is not None else 0.0)
+    out = {
+        "metric": "compressed gradient GB/s per LQ-SGD step (ResNet-18 set, r=4) and % HBM peak",
+        "value": round(value, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "%s: %d matrices + %d vectors, %d elements/worker, r=%d, b=%d, W=%d, alpha=%g, %s gradients, G-hat %s"
+                   % (w.name, L, V, w.elements_per_worker, w.rank, w.bits, W, w.alpha, w.dist,
+                      "written" if ghat is not None else "not written"),
+                   "rank": w.rank, "bits": w.bits, "workers": W, "gradient_bytes_per_step": grad_bytes},
+        "step_hbm_frac": round(step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+        "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels,
+        "wire_bytes_per_worker_step": comp.wire_bytes(),
+    }
+    comp.close()
+    print(json.dumps(out))
+
+
+def _measured_traffic(kernel, workload):
+    """HBM bytes per launch from the committed rocprofv3 counter summary, if one
+    exists for this kernel and workload (a line `<kernel> <workload> hbm_bytes_per_launch <number>`)."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+    try:
+        with open(path) as fh:
+            for line in fh:
+                p = line.split()
+                if len(p) == 4 and p[0] == kernel and p[1] == workload and p[2] == "hbm_bytes_per_launch":
+                    return float(p[3])
+    except OSError:
+        pass
+    return None
+
+
+def _cpu_baseline(w, grads, q0):
+    """The oracle as it stands, on the host cores, on a bounded sample of the
+    same inputs: layers are taken in order until about 25 s have been spent."""
+    import numpy as np
+    import oracle.lqsgd_oracle as orc
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    L, W = len(w.layers), w.workers
+    budget_s = 25.0
+    done_elems = 0
+    done_layers = 0
+    t_spent = 0.0
+    order = sorted(range(L), key=lambda l: w.layers[l][0] * w.layers[l][1])
+    for l in order:
+        G = [grads[k][l].cpu().numpy() for k in range(W)]
+        E = [np.zeros(w.layers[l], np.float32) for _ in range(W)]
+        t0 = time.perf_counter()
+        orc.layer_step(G, E, q0[l], w.rank, w.bits, w.bits, w.alpha)
+        t_spent += time.perf_counter() - t0
+        done_elems += W * w.layers[l][0] * w.layers[l][1]
+        done_layers += 1
+        if t_spent > budget_s:
+            break
+    return {"value": round(4.0 * done_elems / t_spent / 1e9, 4), "unit": "GB/s", "cores": int(threads),
+            "kind": "oracle",
+            "sample": "%d of %d layers (smallest first), all %d workers, one step: %d gradient elements in %.1f s"
+                      % (done_layers, L, W, done_elems, t_spent)}
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,624 @@
+// C ABI of the LQ-SGD compressor: context, device state, phase sequencing,
+// taps and timing.  All arithmetic of the method runs in the kernels; this
+// file only moves bytes and launches.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "lqsgd.h"
+#include "lqsgd_kernels.h"
+#include "lqsgd_plan.h"
+
+using namespace lqsgd;
+
+namespace {
+
+thread_local std::string g_create_error;
+
+enum State { kIdle = 0, kPCompressed = 1, kPDone = 2, kQCompressed = 3 };
+
+struct EventPair {
+  hipEvent_t a, b;
+  int kernel;
+};
+
+}  // namespace
+
+struct lqsgd_ctx {
+  Plan plan;
+  hipStream_t stream = nullptr;
+  int device = 0;
+  State state = kIdle;
+  std::string err;
+  std::vector<void*> allocs;
+  DevArgs args{};
+  // device copies of the work lists
+  Tile* d_tilesA = nullptr; Tile* d_tilesB = nullptr;
+  XTile* d_tilesXP = nullptr; XTile* d_tilesXQ = nullptr;
+  RTile* d_tilesRQ = nullptr; VTile* d_tilesV = nullptr;
+  // pointer tables
+  const float** d_grads = nullptr; float** d_ghat = nullptr;
+  std::vector<const float*> h_grads; std::vector<float*> h_ghat;
+  bool grads_valid = false, ghat_valid = false;
+  // timing
+  bool timing = false;
+  std::vector<EventPair> events;
+  size_t events_used = 0;
+};
+
+namespace {
+
+int fail(lqsgd_ctx* c, int code, const std::string& msg) {
+  if (c) c->err = msg; else g_create_error = msg;
+  return code;
+}
+
+int fail_hip(lqsgd_ctx* c, hipError_t e, const char* what) {
+  // Clear the sticky error so that a later call does not report it again.
+  (void)hipGetLastError();
+  return fail(c, LQSGD_EHIP, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+#define HIP_TRY(ctx, expr)                                   \
+  do {                                                       \
+    hipError_t e_ = (expr);                                  \
+    if (e_ != hipSuccess) return fail_hip(ctx, e_, #expr);   \
+  } while (0)
+
+template <typename T>
+int dev_alloc(lqsgd_ctx* c, T** out, size_t count, bool zero) {
+  *out = nullptr;
+  if (count == 0) count = 1;
+  void* p = nullptr;
+  hipError_t e = hipMalloc(&p, count * sizeof(T));
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    char buf[160];
+    std::snprintf(buf, sizeof buf, "hipMalloc of %zu bytes failed: %s", count * sizeof(T), hipGetErrorString(e));
+    return fail(c, LQSGD_ENOMEM, buf);
+  }
+  c->allocs.push_back(p);
+  if (zero) HIP_TRY(c, hipMemsetAsync(p, 0, count * sizeof(T), c->stream));
+  *out = static_cast<T*>(p);
+  return LQSGD_OK;
+}
+
+template <typename T>
+int dev_upload(lqsgd_ctx* c, T** out, const std::vector<T>& v) {
+  int rc = dev_alloc(c, out, v.size(), false);
+  if (rc) return rc;
+  if (!v.empty()) HIP_TRY(c, hipMemcpy(*out, v.data(), v.size() * sizeof(T), hipMemcpyHostToDevice));
+  return LQSGD_OK;
+}
+
+struct Timed {
+  lqsgd_ctx* c;
+  EventPair* ep = nullptr;
+  Timed(lqsgd_ctx* ctx, int kernel) : c(ctx) {
+    if (!c->timing) return;
+    if (c->events_used == c->events.size()) {
+      EventPair p{};
+      if (hipEventCreate(&p.a) != hipSuccess || hipEventCreate(&p.b) != hipSuccess) { (void)hipGetLastError(); return; }
+      c->events.push_back(p);
+    }
+    ep = &c->events[c->events_used++];
+    ep->kernel = kernel;
+    (void)hipEventRecord(ep->a, c->stream);
+  }
+  ~Timed() {
+    if (ep) (void)hipEventRecord(ep->b, c->stream);
+  }
+};
+
+int check_matrix_layer(lqsgd_ctx* c, int32_t layer, const LayerDesc** out) {
+  if (layer < 0 || layer >= c->plan.n_all) return fail(c, LQSGD_ESHAPE, "layer index out of range");
+  const int k = c->plan.kind_of[layer];
+  if (k < 0) return fail(c, LQSGD_ESHAPE, "layer is a VECTOR layer");
+  *out = &c->plan.layers[k];
+  return LQSGD_OK;
+}
+
+int check_worker(lqsgd_ctx* c, int32_t worker) {
+  if (worker < 0 || worker >= c->plan.W) return fail(c, LQSGD_ESHAPE, "worker index out of range");
+  return LQSGD_OK;
+}
+
+// Copies the caller's pointer list to the device table when it changed.
+int bind_grads(lqsgd_ctx* c, const float* const* grads) {
+  const size_t n = (size_t)c->plan.W * c->plan.n_all;
+  for (size_t i = 0; i < n; ++i) {
+    if (!grads[i]) return fail(c, LQSGD_EINVAL, "NULL gradient pointer");
+    if (reinterpret_cast<uintptr_t>(grads[i]) & 15u) return fail(c, LQSGD_EINVAL, "gradient pointer not 16-byte aligned");
+  }
+  if (c->grads_valid && std::memcmp(c->h_grads.data(), grads, n * sizeof(float*)) == 0) return LQSGD_OK;
+  HIP_TRY(c, hipStreamSynchronize(c->stream));   // the old table may still be in use
+  c->h_grads.assign(grads, grads + n);
+  HIP_TRY(c, hipMemcpy(c->d_grads, c->h_grads.data(), n * sizeof(float*), hipMemcpyHostToDevice));
+  c->grads_valid = true;
+  return LQSGD_OK;
+}
+
+int bind_ghat(lqsgd_ctx* c, float* const* ghat) {
+  if (!ghat) { c->args.ghat = nullptr; return LQSGD_OK; }
+  const size_t n = (size_t)c->plan.n_all;
+  for (size_t i = 0; i < n; ++i)
+    if (ghat[i] && (reinterpret_cast<uintptr_t>(ghat[i]) & 15u))
+      return fail(c, LQSGD_EINVAL, "G-hat pointer not 16-byte aligned");
+  if (!(c->ghat_valid && std::memcmp(c->h_ghat.data(), ghat, n * sizeof(float*)) == 0)) {
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    c->h_ghat.assign(ghat, ghat + n);
+    HIP_TRY(c, hipMemcpy(c->d_ghat, c->h_ghat.data(), n * sizeof(float*), hipMemcpyHostToDevice));
+    c->ghat_valid = true;
+  }
+  c->args.ghat = c->d_ghat;
+  return LQSGD_OK;
+}
+
+// ---- the phases -------------------------------------------------------------
+int run_sweep0(lqsgd_ctx* c) {
+  { Timed t(c, LQSGD_KERNEL_ADD_PROJECT);
+    HIP_TRY(c, launch_add_project(c->plan.RP, c->args, c->d_tilesA, (int)c->plan.tilesA.size(), c->stream)); }
+  { Timed t(c, LQSGD_KERNEL_ORTH);
+    HIP_TRY(c, launch_orth(c->plan.RP, c->args, c->stream)); }
+  return LQSGD_OK;
+}
+int run_exchange(lqsgd_ctx* c, int mode, int phase) {
+  Timed t(c, phase ? LQSGD_KERNEL_EXCHANGE_Q : LQSGD_KERNEL_EXCHANGE_P);
+  const auto& tl = phase ? c->plan.tilesXQ : c->plan.tilesXP;
+  HIP_TRY(c, launch_exchange(mode, phase, c->args, phase ? c->d_tilesXQ : c->d_tilesXP, (int)tl.size(), c->stream));
+  return LQSGD_OK;
+}
+int run_sweep1(lqsgd_ctx* c) {
+  { Timed t(c, LQSGD_KERNEL_BACK_PROJECT);
+    HIP_TRY(c, launch_back_project(c->plan.RP, c->args, c->d_tilesB, (int)c->plan.tilesB.size(), c->stream)); }
+  { Timed t(c, LQSGD_KERNEL_REDUCE_Q);
+    HIP_TRY(c, launch_reduce_q(c->args, c->d_tilesRQ, (int)c->plan.tilesRQ.size(), c->stream)); }
+  return LQSGD_OK;
+}
+int run_sweep2(lqsgd_ctx* c, int write_ghat) {
+  Timed t(c, LQSGD_KERNEL_RESIDUAL);
+  HIP_TRY(c, launch_residual(c->plan.RP, c->args, c->d_tilesB, (int)c->plan.tilesB.size(), write_ghat, c->stream));
+  return LQSGD_OK;
+}
+
+struct PacketLoc {
+  uint8_t* mag; uint8_t* sgn; float* scale;
+  int64_t n_el, groups, mag_len, sign_len;
+  int bits;
+};
+
+int locate_packet(lqsgd_ctx* c, int32_t phase, int32_t layer, int32_t worker, PacketLoc* out) {
+  if (phase != LQSGD_PHASE_P && phase != LQSGD_PHASE_Q) return fail(c, LQSGD_EINVAL, "phase must be LQSGD_PHASE_P or LQSGD_PHASE_Q");
+  const LayerDesc* ld = nullptr;
+  int rc = check_matrix_layer(c, layer, &ld);
+  if (rc) return rc;
+  if ((rc = check_worker(c, worker))) return rc;
+  const int li = c->plan.kind_of[layer];
+  const DevArgs& a = c->args;
+  out->bits = phase ? a.bits_q : a.bits_p;
+  if (out->bits == 0) return fail(c, LQSGD_EUNSUPPORTED, "quantisation is off for this phase: the packet is the fp32 factor");
+  out->n_el = phase ? ld->nq_el : ld->np_el;
+  out->groups = (out->n_el + kXGroup - 1) / kXGroup;
+  out->mag_len = out->groups * out->bits;
+  out->sign_len = out->groups;
+  if (phase) {
+    out->mag = a.magQ + (size_t)worker * a.magq_stride + ld->magq_off;
+    out->sgn = a.sgnQ + (size_t)worker * a.sgnq_stride + ld->sgnq_off;
+    out->scale = a.scaleQ + (size_t)worker * a.L + li;
+  } else {
+    out->mag = a.magP + (size_t)worker * a.magp_stride + ld->magp_off;
+    out->sgn = a.sgnP + (size_t)worker * a.sgnp_stride + ld->sgnp_off;
+    out->scale = a.scaleP + (size_t)worker * a.L + li;
+  }
+  return LQSGD_OK;
+}
+
+}  // namespace
+
+// =============================================================================
+extern "C" {
+
+int lqsgd_plan_query(const lqsgd_config* cfg, const lqsgd_layer* layers, int32_t n_layers, lqsgd_plan_info* out) {
+  if (!out) return fail(nullptr, LQSGD_EINVAL, "NULL output");
+  Plan p;
+  const int rc = p.build(cfg, layers, n_layers);
+  if (rc) return fail(nullptr, rc, p.err);
+  out->device_bytes = p.device_bytes;
+  out->wire_bytes = p.wire_bytes;
+  out->matrix_elements = p.matrix_elements;
+  out->n_matrix = p.L;
+  out->n_vector = p.V;
+  out->rank_pad = p.RP;
+  out->tiles[0] = (int32_t)p.tilesA.size();
+  out->tiles[1] = (int32_t)p.tilesB.size();
+  out->tiles[2] = (int32_t)p.tilesB.size();
+  return LQSGD_OK;
+}
+
+int64_t lqsgd_plan_tiles(const lqsgd_config* cfg, const lqsgd_layer* layers, int32_t n_layers, int32_t sweep,
+                         int32_t* out, int64_t cap) {
+  if (sweep < 0 || sweep > 2) return fail(nullptr, LQSGD_EINVAL, "sweep must be 0, 1 or 2");
+  Plan p;
+  const int rc = p.build(cfg, layers, n_layers);
+  if (rc) return fail(nullptr, rc, p.err);
+  const std::vector<Tile>& tl = sweep == 0 ? p.tilesA : p.tilesB;
+  if (out) {
+    const int64_t n = std::min<int64_t>(cap, (int64_t)tl.size());
+    for (int64_t i = 0; i < n; ++i) {
+      const Tile& t = tl[i];
+      const int li = t.lw / p.W;
+      const LayerDesc& d = p.layers[li];
+      int32_t* o = out + 6 * i;
+      o[0] = d.gidx;
+      o[1] = t.lw - li * p.W;
+      o[2] = t.row0;
+      o[3] = t.nrows;
+      if (sweep == 0) {
+        o[4] = t.aux * d.segw;
+        o[5] = std::min(d.cols, o[4] + d.segw) - o[4];
+      } else {
+        o[4] = t.aux * kWave * d.vec;
+        o[5] = std::min(d.cols, o[4] + kWave * d.vec) - o[4];
+      }
+    }
+  }
+  return (int64_t)tl.size();
+}
+
+int lqsgd_create(const lqsgd_config* cfg, const lqsgd_layer* layers, int32_t n_layers, void* hip_stream,
+                 lqsgd_ctx** out) {
+  if (!out) return fail(nullptr, LQSGD_EINVAL, "NULL output pointer");
+  *out = nullptr;
+  lqsgd_ctx* c = new (std::nothrow) lqsgd_ctx();
+  if (!c) return fail(nullptr, LQSGD_ENOMEM, "out of host memory");
+  int rc = c->plan.build(cfg, layers, n_layers);
+  if (rc) {
+    g_create_error = c->plan.err;
+    delete c;
+    return rc;
+  }
+  c->stream = static_cast<hipStream_t>(hip_stream);
+  auto bail = [&](int code) {
+    g_create_error = c->err;
+    for (void* p : c->allocs) (void)hipFree(p);
+    delete c;
+    return code;
+  };
+  {
+    hipError_t e = hipGetDevice(&c->device);
+    if (e != hipSuccess) { fail_hip(c, e, "hipGetDevice"); return bail(LQSGD_EHIP); }
+  }
+  const Plan& p = c->plan;
+  DevArgs& a = c->args;
+  a.W = p.W; a.L = p.L; a.n_all = p.n_all; a.bits_p = p.cfg.bits_p; a.bits_q = p.cfg.bits_q;
+  a.m_stride = p.m_stride; a.p_stride = p.p_stride; a.q_stride = p.q_stride;
+  a.ppart_stride = p.ppart_stride; a.qpart_stride = p.qpart_stride;
+  a.magp_stride = p.magp_stride; a.sgnp_stride = p.sgnp_stride;
+  a.magq_stride = p.magq_stride; a.sgnq_stride = p.sgnq_stride;
+  const size_t W = (size_t)p.W;
+  LayerDesc* d_layers = nullptr; VecDesc* d_vecs = nullptr;
+  float *thrP = nullptr, *levP = nullptr, *thrQ = nullptr, *levQ = nullptr;
+  std::vector<float> tP, lP, tQ, lQ;
+  quantiser_tables(p.cfg.bits_p, (double)p.cfg.alpha, tP, lP);
+  quantiser_tables(p.cfg.bits_q, (double)p.cfg.alpha, tQ, lQ);
+#define TRY_(x) do { if ((rc = (x))) return bail(rc); } while (0)
+  TRY_(dev_alloc(c, &a.E, W * p.m_stride, true));
+  TRY_(dev_alloc(c, &a.Ppart, W * p.ppart_stride, true));
+  TRY_(dev_alloc(c, &a.Ppre, W * p.p_stride, true));
+  TRY_(dev_alloc(c, &a.Porth, W * p.p_stride, true));
+  TRY_(dev_alloc(c, &a.Pbar, (size_t)p.p_stride, true));
+  TRY_(dev_alloc(c, &a.Qpart, W * p.qpart_stride, true));
+  TRY_(dev_alloc(c, &a.Qw, W * p.q_stride, true));
+  TRY_(dev_alloc(c, &a.Qbar, (size_t)p.q_stride, true));
+  TRY_(dev_alloc(c, &a.magP, W * p.magp_stride, true));
+  TRY_(dev_alloc(c, &a.sgnP, W * p.sgnp_stride, true));
+  TRY_(dev_alloc(c, &a.scaleP, W * (size_t)std::max(p.L, 1), true));
+  TRY_(dev_alloc(c, &a.magQ, W * p.magq_stride, true));
+  TRY_(dev_alloc(c, &a.sgnQ, W * p.sgnq_stride, true));
+  TRY_(dev_alloc(c, &a.scaleQ, W * (size_t)std::max(p.L, 1), true));
+  TRY_(dev_alloc(c, &a.vmean, (size_t)p.v_total, true));
+  TRY_(dev_upload(c, &d_layers, p.layers));
+  TRY_(dev_upload(c, &d_vecs, p.vecs));
+  TRY_(dev_upload(c, &thrP, tP)); TRY_(dev_upload(c, &levP, lP));
+  TRY_(dev_upload(c, &thrQ, tQ)); TRY_(dev_upload(c, &levQ, lQ));
+  TRY_(dev_upload(c, &c->d_tilesA, p.tilesA));
+  TRY_(dev_upload(c, &c->d_tilesB, p.tilesB));
+  TRY_(dev_upload(c, &c->d_tilesXP, p.tilesXP));
+  TRY_(dev_upload(c, &c->d_tilesXQ, p.tilesXQ));
+  TRY_(dev_upload(c, &c->d_tilesRQ, p.tilesRQ));
+  TRY_(dev_upload(c, &c->d_tilesV, p.tilesV));
+  TRY_(dev_alloc(c, &c->d_grads, W * p.n_all, true));
+  TRY_(dev_alloc(c, &c->d_ghat, (size_t)p.n_all, true));
+#undef TRY_
+  a.layers = d_layers; a.vecs = d_vecs;
+  a.thrP = thrP; a.levP = levP; a.thrQ = thrQ; a.levQ = levQ;
+  a.grads = c->d_grads; a.ghat = nullptr;
+  {
+    hipError_t e = hipStreamSynchronize(c->stream);
+    if (e != hipSuccess) { fail_hip(c, e, "hipStreamSynchronize"); return bail(LQSGD_EHIP); }
+  }
+  *out = c;
+  return LQSGD_OK;
+}
+
+int lqsgd_destroy(lqsgd_ctx* c) {
+  if (!c) return LQSGD_OK;
+  (void)hipStreamSynchronize(c->stream);
+  for (EventPair& e : c->events) { (void)hipEventDestroy(e.a); (void)hipEventDestroy(e.b); }
+  for (void* p : c->allocs) (void)hipFree(p);
+  (void)hipGetLastError();
+  delete c;
+  return LQSGD_OK;
+}
+
+int lqsgd_synchronize(lqsgd_ctx* c) {
+  if (!c) return fail(nullptr, LQSGD_EINVAL, "NULL context");
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  return LQSGD_OK;
+}
+
+const char* lqsgd_last_error(const lqsgd_ctx* c) { return c ? c->err.c_str() : g_create_error.c_str(); }
+
+int lqsgd_set_q(lqsgd_ctx* c, int32_t layer, const float* host_q) {
+  if (!c) return fail(nullptr, LQSGD_EINVAL, "NULL context");
+  if (!host_q) return fail(c, LQSGD_EINVAL, "NULL host_q");
+  return lqsgd_set_state(c, layer, 0, nullptr, host_q);
+}
+
+int lqsgd_get_state(lqsgd_ctx* c, int32_t layer, int32_t worker, float* host_e, float* host_q) {
+  if (!c) return fail(nullptr, LQSGD_EINVAL, "NULL context");
+  const LayerDesc* ld = nullptr;
+  int rc = check_matrix_layer(c, layer, &ld);
+  if (rc) return rc;
+  if ((rc = check_worker(c, worker))) return rc;
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  if (host_e)
+    HIP_TRY(c, hipMemcpy(host_e, c->args.E + (size_t)worker * c->args.m_stride + ld->m_off,
+                         (size_t)ld->rows * ld->cols * sizeof(float), hipMemcpyDeviceToHost));
+  if (host_q)
+    HIP_TRY(c, hipMemcpy(host_q, c->args.Qbar + ld->q_off, (size_t)ld->nq_el * sizeof(float), hipMemcpyDeviceToHost));
+  return LQSGD_OK;
+}
+
+int lqsgd_set_state(lqsgd_ctx* c, int32_t layer, int32_t worker, const float* host_e, const float* host_q) {
+  if (!c) return fail(nullptr, LQSGD_EINVAL, "NULL context");
+  const LayerDesc* ld = nullptr;
+  int rc = check_matrix_layer(c, layer, &ld);
+  if (rc) return rc;
+  if ((rc = check_worker(c, worker))) return rc;
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  if (host_e)
+    HIP_TRY(c, hipMemcpy(c->args.E + (size_t)worker * c->args.m_stride + ld->m_off, host_e,
+                         (size_t)ld->rows * ld->cols * sizeof(float), hipMemcpyHostToDevice));
+  if (host_q)
+    HIP_TRY(c, hipMemcpy(c->args.Qbar + ld->q_off, host_q, (size_t)ld->nq_el * sizeof(float), hipMemcpyHostToDevice));
+  return LQSGD_OK;
+}
+
+int lqsgd_compress(lqsgd_ctx* c, int32_t phase, const float* const* grads) {
+  if (!c) return fail(nullptr, LQSGD_EINVAL, "NULL context");
+  int rc;
+  if (phase == LQSGD_PHASE_P) {
+    if (c->state != kIdle) return fail(c, LQSGD_ESTATE, "compress(P) must start an iteration");
+    if (!grads) return fail(c, LQSGD_EINVAL, "NULL gradient list");
+    if ((rc = bind_grads(c, grads))) return rc;
+    if ((rc = run_sweep0(c))) return rc;
+    if ((rc = run_exchange(c, kQuantOnly, 0))) return rc;
+    c->state = kPCompressed;
+    return LQSGD_OK;
+  }
+  if (phase == LQSGD_PHASE_Q) {
+    if (c->state != kPDone) return fail(c, LQSGD_ESTATE, "compress(Q) must follow decompress(P)");
+    if ((rc = run_sweep1(c))) return rc;
+    if ((rc = run_exchange(c, kQuantOnly, 1))) return rc;
+    c->state = kQCompressed;
+    return LQSGD_OK;
+  }
+  return fail(c, LQSGD_EINVAL, "phase must be LQSGD_PHASE_P or LQSGD_PHASE_Q");
+}
+
+int lqsgd_decompress(lqsgd_ctx* c, int32_t phase) {
+  if (!c) return fail(nullptr, LQSGD_EINVAL, "NULL context");
+  int rc;
+  if (phase == LQSGD_PHASE_P) {
+    if (c->state != kPCompressed) return fail(c, LQSGD_ESTATE, "decompress(P) must follow compress(P)");
+    if ((rc = run_exchange(c, kMeanOnly, 0))) return rc;
+    c->state = kPDone;
+    return LQSGD_OK;
+  }
+  if (phase == LQSGD_PHASE_Q) {
+    if (c->state != kQCompressed) return fail(c, LQSGD_ESTATE, "decompress(Q) must follow compress(Q)");
+    if ((rc = run_exchange(c, kMeanOnly, 1))) return rc;
+    c->args.ghat = nullptr;
+    if ((rc = run_sweep2(c, 0))) return rc;
+    c->state = kIdle;
+    return LQSGD_OK;
+  }
+  return fail(c, LQSGD_EINVAL, "phase must be LQSGD_PHASE_P or LQSGD_PHASE_Q");
+}
+
+int lqsgd_step(lqsgd_ctx* c, const float* const* grads, float* const* ghat) {
+  if (!c) return fail(nullptr, LQSGD_EINVAL, "NULL context");
+  if (c->state != kIdle) return fail(c, LQSGD_ESTATE, "a staged iteration is in progress");
+  if (!grads) return fail(c, LQSGD_EINVAL, "NULL gradient list");
+  int rc;
+  if ((rc = bind_grads(c, grads))) return rc;
+  if ((rc = bind_ghat(c, ghat))) return rc;
+  if (ghat) {
+    const size_t n = (size_t)c->plan.W * c->plan.n_all;
+    for (int i = 0; i < c->plan.n_all; ++i)
+      if (ghat[i])
+        for (size_t j = 0; j < n; ++j)
+          if (grads[j] == ghat[i]) return fail(c, LQSGD_EINVAL, "a G-hat pointer aliases a gradient");
+  }
+  if ((rc = run_sweep0(c))) return rc;
+  if ((rc = run_exchange(c, kFused, 0))) return rc;
+  if ((rc = run_sweep1(c))) return rc;
+  if ((rc = run_exchange(c, kFused, 1))) return rc;
+  if ((rc = run_sweep2(c, ghat != nullptr))) return rc;
+  if (c->plan.V > 0) {
+    Timed t(c, LQSGD_KERNEL_VECTOR_MEAN);
+    HIP_TRY(c, launch_vector_mean(c->args, c->d_tilesV, (int)c->plan.tilesV.size(), c->stream));
+  }
+  return LQSGD_OK;
+}
+
+int lqsgd_get_packet_raw(lqsgd_ctx* c, int32_t phase, int32_t layer, int32_t worker, uint8_t* mag_plane,
+                         int64_t* mag_len, uint8_t* sign_plane, int64_t* sign_len) {
+  if (!c) return fail(nullptr, LQSGD_EINVAL, "NULL context");
+  PacketLoc loc{};
+  int rc = locate_packet(c, phase, layer, worker, &loc);
+  if (rc) return rc;
+  if (mag_len) *mag_len = loc.mag_len;
+  if (sign_len) *sign_len = loc.sign_len;
+  if (!mag_plane && !sign_plane) return LQSGD_OK;
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  if (mag_plane) HIP_TRY(c, hipMemcpy(mag_plane, loc.mag, (size_t)loc.mag_len, hipMemcpyDeviceToHost));
+  if (sign_plane) HIP_TRY(c, hipMemcpy(sign_plane, loc.sgn, (size_t)loc.sign_len, hipMemcpyDeviceToHost));
+  return LQSGD_OK;
+}
+
+int lqsgd_get_packet(lqsgd_ctx* c, int32_t phase, int32_t layer, int32_t worker, uint8_t* mag_codes,
+                     uint8_t* sign_bits, float* scale) {
+  if (!c) return fail(nullptr, LQSGD_EINVAL, "NULL context");
+  PacketLoc loc{};
+  int rc = locate_packet(c, phase, layer, worker, &loc);
+  if (rc) return rc;
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  if (scale) HIP_TRY(c, hipMemcpy(scale, loc.scale, sizeof(float), hipMemcpyDeviceToHost));
+  if (mag_codes) {
+    std::vector<uint8_t> raw((size_t)loc.mag_len);
+    HIP_TRY(c, hipMemcpy(raw.data(), loc.mag, raw.size(), hipMemcpyDeviceToHost));
+    const unsigned mask = (1u << loc.bits) - 1u;
+    for (int64_t e = 0; e < loc.n_el; ++e) {
+      const int64_t bit = e * loc.bits;
+      unsigned v = raw[(size_t)(bit >> 3)] >> (bit & 7);
+      if ((bit & 7) + loc.bits > 8) v |= (unsigned)raw[(size_t)(bit >> 3) + 1] << (8 - (bit & 7));
+      mag_codes[e] = (uint8_t)(v & mask);
+    }
+  }
+  if (sign_bits) {
+    std::vector<uint8_t> raw((size_t)loc.sign_len);
+    HIP_TRY(c, hipMemcpy(raw.data(), loc.sgn, raw.size(), hipMemcpyDeviceToHost));
+    for (int64_t e = 0; e < loc.n_el; ++e) sign_bits[e] = (raw[(size_t)(e >> 3)] >> (e & 7)) & 1u;
+  }
+  return LQSGD_OK;
+}
+
+int lqsgd_set_packet(lqsgd_ctx* c, int32_t phase, int32_t layer, int32_t worker, const uint8_t* mag_codes,
+                     const uint8_t* sign_bits, float scale) {
+  if (!c) return fail(nullptr, LQSGD_EINVAL, "NULL context");
+  if (!mag_codes || !sign_bits) return fail(c, LQSGD_EINVAL, "NULL code array");
+  PacketLoc loc{};
+  int rc = locate_packet(c, phase, layer, worker, &loc);
+  if (rc) return rc;
+  const unsigned mask = (1u << loc.bits) - 1u;
+  std::vector<uint8_t> mag((size_t)loc.mag_len, 0), sgn((size_t)loc.sign_len, 0);
+  for (int64_t e = 0; e < loc.n_el; ++e) {
+    if (mag_codes[e] > mask) return fail(c, LQSGD_EINVAL, "magnitude code exceeds 2^b - 1");
+    const int64_t bit = e * loc.bits;
+    const unsigned v = (unsigned)mag_codes[e] << (bit & 7);
+    mag[(size_t)(bit >> 3)] |= (uint8_t)v;
+    if ((bit & 7) + loc.bits > 8) mag[(size_t)(bit >> 3) + 1] |= (uint8_t)(v >> 8);
+    if (sign_bits[e] & 1u) sgn[(size_t)(e >> 3)] |= (uint8_t)(1u << (e & 7));
+  }
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  HIP_TRY(c, hipMemcpy(loc.mag, mag.data(), mag.size(), hipMemcpyHostToDevice));
+  HIP_TRY(c, hipMemcpy(loc.sgn, sgn.data(), sgn.size(), hipMemcpyHostToDevice));
+  HIP_TRY(c, hipMemcpy(loc.scale, &scale, sizeof(float), hipMemcpyHostToDevice));
+  return LQSGD_OK;
+}
+
+int lqsgd_get_factor(lqsgd_ctx* c, int32_t which, int32_t layer, int32_t worker, float* host) {
+  if (!c) return fail(nullptr, LQSGD_EINVAL, "NULL context");
+  if (!host) return fail(c, LQSGD_EINVAL, "NULL host buffer");
+  const DevArgs& a = c->args;
+  if (which == LQSGD_FACTOR_VMEAN) {
+    if (layer < 0 || layer >= c->plan.n_all) return fail(c, LQSGD_ESHAPE, "layer index out of range");
+    const int k = c->plan.kind_of[layer];
+    if (k >= 0) return fail(c, LQSGD_ESHAPE, "layer is not a VECTOR layer");
+    const VecDesc& vd = c->plan.vecs[-k - 1];
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    HIP_TRY(c, hipMemcpy(host, a.vmean + vd.off, (size_t)vd.len * sizeof(float), hipMemcpyDeviceToHost));
+    return LQSGD_OK;
+  }
+  const LayerDesc* ld = nullptr;
+  int rc = check_matrix_layer(c, layer, &ld);
+  if (rc) return rc;
+  const float* src = nullptr;
+  size_t n = 0;
+  const bool per_worker = which == LQSGD_FACTOR_P_PRE || which == LQSGD_FACTOR_P_ORTH || which == LQSGD_FACTOR_Q_W;
+  if (per_worker && (rc = check_worker(c, worker))) return rc;
+  switch (which) {
+    case LQSGD_FACTOR_P_PRE: src = a.Ppre + (size_t)worker * a.p_stride + ld->p_off; n = ld->np_el; break;
+    case LQSGD_FACTOR_P_ORTH: src = a.Porth + (size_t)worker * a.p_stride + ld->p_off; n = ld->np_el; break;
+    case LQSGD_FACTOR_P_BAR: src = a.Pbar + ld->p_off; n = ld->np_el; break;
+    case LQSGD_FACTOR_Q_W: src = a.Qw + (size_t)worker * a.q_stride + ld->q_off; n = ld->nq_el; break;
+    case LQSGD_FACTOR_Q_BAR: src = a.Qbar + ld->q_off; n = ld->nq_el; break;
+    default: return fail(c, LQSGD_EINVAL, "unknown factor id");
+  }
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  HIP_TRY(c, hipMemcpy(host, src, n * sizeof(float), hipMemcpyDeviceToHost));
+  return LQSGD_OK;
+}
+
+int lqsgd_set_factor(lqsgd_ctx* c, int32_t which, int32_t layer, const float* host) {
+  if (!c) return fail(nullptr, LQSGD_EINVAL, "NULL context");
+  if (!host) return fail(c, LQSGD_EINVAL, "NULL host buffer");
+  const LayerDesc* ld = nullptr;
+  int rc = check_matrix_layer(c, layer, &ld);
+  if (rc) return rc;
+  float* dst = nullptr;
+  size_t n = 0;
+  if (which == LQSGD_FACTOR_P_BAR) { dst = c->args.Pbar + ld->p_off; n = ld->np_el; }
+  else if (which == LQSGD_FACTOR_Q_BAR) { dst = c->args.Qbar + ld->q_off; n = ld->nq_el; }
+  else return fail(c, LQSGD_EINVAL, "only P-bar and Q-bar can be set");
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  HIP_TRY(c, hipMemcpy(dst, host, n * sizeof(float), hipMemcpyHostToDevice));
+  return LQSGD_OK;
+}
+
+int64_t lqsgd_wire_bytes(const lqsgd_ctx* c) { return c ? c->plan.wire_bytes : (int64_t)LQSGD_EINVAL; }
+
+int lqsgd_timing_enable(lqsgd_ctx* c, int32_t on) {
+  if (!c) return fail(nullptr, LQSGD_EINVAL, "NULL context");
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  c->timing = on != 0;
+  c->events_used = 0;
+  return LQSGD_OK;
+}
+
+int lqsgd_timing_read(lqsgd_ctx* c, double* total_ms, int64_t* launches) {
+  if (!c) return fail(nullptr, LQSGD_EINVAL, "NULL context");
+  if (!total_ms || !launches) return fail(c, LQSGD_EINVAL, "NULL output array");
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  for (int k = 0; k < LQSGD_KERNEL_COUNT; ++k) { total_ms[k] = 0.0; launches[k] = 0; }
+  for (size_t i = 0; i < c->events_used; ++i) {
+    float ms = 0.0f;
+    HIP_TRY(c, hipEventElapsedTime(&ms, c->events[i].a, c->events[i].b));
+    total_ms[c->events[i].kernel] += ms;
+    launches[c->events[i].kernel] += 1;
+  }
+  return LQSGD_OK;
+}
+
+const char* lqsgd_kernel_name(int32_t kernel) {
+  switch (kernel) {
+    case LQSGD_KERNEL_ADD_PROJECT: return "add_project_kernel";
+    case LQSGD_KERNEL_ORTH: return "orth_kernel";
+    case LQSGD_KERNEL_EXCHANGE_P: return "exchange_kernel";
+    case LQSGD_KERNEL_BACK_PROJECT: return "back_project_kernel";
+    case LQSGD_KERNEL_REDUCE_Q: return "reduce_q_kernel";
+    case LQSGD_KERNEL_EXCHANGE_Q: return "exchange_kernel";
+    case LQSGD_KERNEL_RESIDUAL: return "residual_kernel";
+    case LQSGD_KERNEL_VECTOR_MEAN: return "vector_mean_kernel";
+    default: return "";
+  }
+}
+
+}  // extern "C"

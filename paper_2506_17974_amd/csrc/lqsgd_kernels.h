@@ -1,0 +1,46 @@
+// Device-side argument block and the launchers of the gfx950 kernels.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include "lqsgd_plan.h"
+
+namespace lqsgd {
+
+// Passed by value to every kernel (lands in the kernarg segment, read with
+// scalar loads).  All pointers are device pointers.
+struct DevArgs {
+  const LayerDesc* layers;
+  const VecDesc* vecs;
+  const float* const* grads;   // W * n_all gradient tensors
+  float* const* ghat;          // n_all optional outputs (entries may be null), or null
+  float* E;                    // residual / M = G + E, per worker
+  float* Ppart;                // sweep-0 partial products, per worker
+  float* Ppre;                 // P_w before Gram-Schmidt
+  float* Porth;                // P_w after Gram-Schmidt
+  float* Pbar;                 // aggregated P (shared)
+  float* Qpart;                // sweep-1 partial products, per worker
+  float* Qw;                   // Q_w
+  float* Qbar;                 // aggregated Q = warm-start Q (shared)
+  uint8_t* magP; uint8_t* sgnP; float* scaleP;   // packets of the P exchange
+  uint8_t* magQ; uint8_t* sgnQ; float* scaleQ;   // packets of the Q exchange
+  const float* thrP; const float* levP;           // quantiser tables for b_p
+  const float* thrQ; const float* levQ;           // ... and b_q
+  float* vmean;
+  int64_t m_stride, p_stride, q_stride, ppart_stride, qpart_stride;
+  int64_t magp_stride, sgnp_stride, magq_stride, sgnq_stride;
+  int32_t W, L, n_all, bits_p, bits_q;
+};
+
+enum ExchangeMode { kQuantOnly = 0, kMeanOnly = 1, kFused = 2 };
+
+// Each launcher enqueues one kernel on `s` and returns hipGetLastError().
+hipError_t launch_add_project(int RP, const DevArgs& a, const Tile* tiles, int ntiles, hipStream_t s);
+hipError_t launch_orth(int RP, const DevArgs& a, hipStream_t s);
+hipError_t launch_exchange(int mode, int phase, const DevArgs& a, const XTile* tiles, int ntiles, hipStream_t s);
+hipError_t launch_back_project(int RP, const DevArgs& a, const Tile* tiles, int ntiles, hipStream_t s);
+hipError_t launch_reduce_q(const DevArgs& a, const RTile* tiles, int ntiles, hipStream_t s);
+hipError_t launch_residual(int RP, const DevArgs& a, const Tile* tiles, int ntiles, int write_ghat, hipStream_t s);
+hipError_t launch_vector_mean(const DevArgs& a, const VTile* tiles, int ntiles, hipStream_t s);
+
+}  // namespace lqsgd

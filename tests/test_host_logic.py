@@ -1,0 +1,102 @@
+"""CPU-only checks of the library's host side: it loads, exports the header's
+symbols, validates arguments, and its work lists cover every element once."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle.lqsgd_oracle as orc
+from paper_2506_17974_amd import binding as B
+from paper_2506_17974_amd import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    with open(os.path.join(ROOT, "include", "lqsgd.h")) as fh:
+        text = fh.read()
+    declared = set(re.findall(r"\b(lqsgd_[a-z_]+)\s*\(", text))
+    assert declared == set(B.SYMBOLS), declared ^ set(B.SYMBOLS)
+    L = B.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+def test_kernel_names():
+    names = [B.kernel_name(k) for k in range(B.KERNEL_COUNT)]
+    assert all(names) and B.kernel_name(99) == ""
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(rank=0), B.EINVAL), (dict(rank=33), B.EUNSUPPORTED), (dict(bits_p=9), B.EINVAL),
+    (dict(bits_q=-1), B.EINVAL), (dict(workers=0), B.EINVAL), (dict(workers=65), B.EINVAL),
+    (dict(alpha=0.0), B.EINVAL), (dict(alpha=float("nan")), B.EINVAL),
+    (dict(layers=[(0, 4, 0)]), B.ESHAPE), (dict(layers=[(4, -1, 0)]), B.ESHAPE),
+    (dict(layers=[(65536, 65536, 0)]), B.ESHAPE), (dict(layers=[(8, 2, B.LAYER_VECTOR)]), B.ESHAPE),
+    (dict(layers=[(8, 2, 4)]), B.EINVAL),
+])
+def test_plan_rejects_bad_arguments(kw, code):
+    args = dict(layers=[(16, 8, 0)], rank=2, bits_p=8, bits_q=8, workers=2, alpha=255.0)
+    args.update(kw)
+    with pytest.raises(B.LqsgdError) as ei:
+        B.plan_query(**args)
+    assert ei.value.code == code
+
+
+def _coverage(layers, rank, W, sweep):
+    tiles = B.plan_tiles(layers, rank, 8, 8, W, sweep)
+    cover = {}
+    for gidx, w, row0, nrows, col0, ncols in tiles.tolist():
+        rows, cols = layers[gidx][0], layers[gidx][1]
+        assert 0 <= row0 and nrows > 0 and row0 + nrows <= rows
+        assert 0 <= col0 and ncols > 0 and col0 + ncols <= cols
+        m = cover.setdefault((gidx, w), np.zeros((rows, cols), np.int32))
+        m[row0:row0 + nrows, col0:col0 + ncols] += 1
+    return cover
+
+
+@pytest.mark.parametrize("sweep", [0, 1, 2])
+def test_work_lists_cover_each_element_once(sweep):
+    w = wl.small_cnn()
+    layers = B.layer_list(w.layers, w.vectors)
+    layers += [(1, 1, 0), (3, 5000, 0), (2100, 132, 0), (64, 27, 0)]
+    W = 3
+    cover = _coverage(layers, 4, W, sweep)
+    n_matrix = sum(1 for l in layers if l[2] == 0)
+    assert len(cover) == n_matrix * W
+    for key, m in cover.items():
+        assert m.min() == 1 and m.max() == 1, key
+
+
+def test_plan_sizes_resnet18():
+    w = wl.resnet18()
+    info = B.plan_query(B.layer_list(w.layers, w.vectors), 4, 8, 8, 8)
+    assert info.matrix_elements == w.elements_per_worker == 11164352
+    assert info.n_matrix == 21 and info.n_vector == len(w.vectors) and info.rank_pad == 4
+    # the library's wire size equals the oracle's count (Section 4.3 + sign plane + scales)
+    assert info.wire_bytes == orc.wire_bytes(list(w.layers), 4, 8, 8)
+    for r, bp, bq in ((1, 8, 8), (2, 4, 8), (7, 0, 3), (32, 2, 0)):
+        info = B.plan_query(B.layer_list(w.layers), r, bp, bq, 2)
+        assert info.wire_bytes == orc.wire_bytes(list(w.layers), r, bp, bq)
+    # state + scratch stays close to the residual itself (4 B per element per worker)
+    info = B.plan_query(B.layer_list(w.layers, w.vectors), 4, 8, 8, 8)
+    assert info.device_bytes < 1.15 * 4 * 8 * w.elements_per_worker
+
+
+def test_plan_sizes_large_configs():
+    w3 = wl.llm_stack()
+    info = B.plan_query(B.layer_list(w3.layers), 4, 8, 8, 4)
+    assert info.matrix_elements == 5033164800
+    assert info.device_bytes < 1.02 * 4 * 4 * info.matrix_elements
+    w4 = wl.sweep_8192(32, 8)
+    info = B.plan_query(B.layer_list(w4.layers), 32, 8, 8, 16)
+    assert info.rank_pad == 32
+
+
+def test_compressor_refuses_to_run_without_gpu():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is visible")
+    with pytest.raises(RuntimeError):
+        B.Compressor([(4, 4, 0)], 1)
