@@ -223,9 +223,8 @@ int64_t lqsgd_plan_tiles(const lqsgd_config* cfg, const lqsgd_layer* layers, int
 #define LQSGD_KERNEL_BACK_PROJECT 3  /* Q partials = M^T P-bar            */
 #define LQSGD_KERNEL_REDUCE_Q 4      /* reduce partials, absmax           */
 #define LQSGD_KERNEL_EXCHANGE_Q 5    /* quantise / dequantise / mean of Q */
-#define LQSGD_KERNEL_RESIDUAL 6      /* E = M - P-bar Q-bar^T (+ G-hat)   */
-#define LQSGD_KERNEL_VECTOR_MEAN 7
-#define LQSGD_KERNEL_COUNT 8
+#define LQSGD_KERNEL_RESIDUAL 6      /* E = M - P-bar Q-bar^T (+ G-hat), and the mean of the VECTOR layers */
+#define LQSGD_KERNEL_COUNT 7
 
 /* on != 0: every kernel launched from now on is bracketed by a pair of HIP
  * events on the context's stream (this adds a little time between kernels).

@@ -10,15 +10,16 @@ from typing import List, Optional, Sequence
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "liblqsgd.so")
+# LQSGD_LIB points at another build of the same library (kernel experiments)
+LIB_PATH = os.environ.get("LQSGD_LIB") or os.path.join(_HERE, "liblqsgd.so")
 
 OK, EINVAL, ESHAPE, EUNSUPPORTED, ENOMEM, EHIP, ESTATE = 0, -1, -2, -3, -4, -5, -6
 LAYER_MATRIX, LAYER_VECTOR = 0, 1
 PHASE_P, PHASE_Q = 0, 1
 FACTOR_P_PRE, FACTOR_P_ORTH, FACTOR_P_BAR, FACTOR_Q_W, FACTOR_Q_BAR, FACTOR_VMEAN = range(6)
 (KERNEL_ADD_PROJECT, KERNEL_ORTH, KERNEL_EXCHANGE_P, KERNEL_BACK_PROJECT, KERNEL_REDUCE_Q,
- KERNEL_EXCHANGE_Q, KERNEL_RESIDUAL, KERNEL_VECTOR_MEAN) = range(8)
-KERNEL_COUNT = 8
+ KERNEL_EXCHANGE_Q, KERNEL_RESIDUAL) = range(7)
+KERNEL_COUNT = 7
 MAX_RANK, MAX_WORKERS = 32, 64
 
 # every symbol the header declares

@@ -4,7 +4,9 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cmath>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <string>
@@ -34,6 +36,8 @@ struct lqsgd_ctx {
   hipStream_t stream = nullptr;
   int device = 0;
   State state = kIdle;
+  int sweep_dir = 0;        // direction of the next streaming sweep (alternates)
+  bool flip = true;
   std::string err;
   std::vector<void*> allocs;
   DevArgs args{};
@@ -160,11 +164,17 @@ int bind_ghat(lqsgd_ctx* c, float* const* ghat) {
 }
 
 // ---- the phases -------------------------------------------------------------
+int next_dir(lqsgd_ctx* c) {
+  const int d = c->sweep_dir;
+  if (c->flip) c->sweep_dir ^= 1;
+  return d;
+}
+
 int run_sweep0(lqsgd_ctx* c) {
   { Timed t(c, LQSGD_KERNEL_ADD_PROJECT);
-    HIP_TRY(c, launch_add_project(c->plan.RP, c->args, c->d_tilesA, (int)c->plan.tilesA.size(), c->stream)); }
+    HIP_TRY(c, launch_add_project(c->plan.RP, c->args, c->d_tilesA, (int)c->plan.tilesA.size(), next_dir(c), c->stream)); }
   { Timed t(c, LQSGD_KERNEL_ORTH);
-    HIP_TRY(c, launch_orth(c->plan.RP, c->args, c->stream)); }
+    HIP_TRY(c, launch_orth(c->plan.RP, c->plan.max_rows, c->args, c->stream)); }
   return LQSGD_OK;
 }
 int run_exchange(lqsgd_ctx* c, int mode, int phase) {
@@ -175,14 +185,15 @@ int run_exchange(lqsgd_ctx* c, int mode, int phase) {
 }
 int run_sweep1(lqsgd_ctx* c) {
   { Timed t(c, LQSGD_KERNEL_BACK_PROJECT);
-    HIP_TRY(c, launch_back_project(c->plan.RP, c->args, c->d_tilesB, (int)c->plan.tilesB.size(), c->stream)); }
+    HIP_TRY(c, launch_back_project(c->plan.RP, c->args, c->d_tilesB, (int)c->plan.tilesB.size(), next_dir(c), c->stream)); }
   { Timed t(c, LQSGD_KERNEL_REDUCE_Q);
     HIP_TRY(c, launch_reduce_q(c->args, c->d_tilesRQ, (int)c->plan.tilesRQ.size(), c->stream)); }
   return LQSGD_OK;
 }
-int run_sweep2(lqsgd_ctx* c, int write_ghat) {
+int run_sweep2(lqsgd_ctx* c, int write_ghat, bool with_vectors) {
   Timed t(c, LQSGD_KERNEL_RESIDUAL);
-  HIP_TRY(c, launch_residual(c->plan.RP, c->args, c->d_tilesB, (int)c->plan.tilesB.size(), write_ghat, c->stream));
+  HIP_TRY(c, launch_residual(c->plan.RP, c->args, c->d_tilesB, (int)c->plan.tilesB.size(), c->d_tilesV,
+                             with_vectors ? (int)c->plan.tilesV.size() : 0, write_ghat, next_dir(c), c->stream));
   return LQSGD_OK;
 }
 
@@ -283,6 +294,7 @@ int lqsgd_create(const lqsgd_config* cfg, const lqsgd_layer* layers, int32_t n_l
     return rc;
   }
   c->stream = static_cast<hipStream_t>(hip_stream);
+  if (const char* f = std::getenv("LQSGD_FLIP")) c->flip = (f[0] != '0');
   auto bail = [&](int code) {
     g_create_error = c->err;
     for (void* p : c->allocs) (void)hipFree(p);
@@ -296,6 +308,9 @@ int lqsgd_create(const lqsgd_config* cfg, const lqsgd_layer* layers, int32_t n_l
   const Plan& p = c->plan;
   DevArgs& a = c->args;
   a.W = p.W; a.L = p.L; a.n_all = p.n_all; a.bits_p = p.cfg.bits_p; a.bits_q = p.cfg.bits_q;
+  a.alpha = p.cfg.alpha;
+  a.qscale_p = (float)(((1 << p.cfg.bits_p) - 1) / std::log2(1.0 + (double)p.cfg.alpha));
+  a.qscale_q = (float)(((1 << p.cfg.bits_q) - 1) / std::log2(1.0 + (double)p.cfg.alpha));
   a.m_stride = p.m_stride; a.p_stride = p.p_stride; a.q_stride = p.q_stride;
   a.ppart_stride = p.ppart_stride; a.qpart_stride = p.qpart_stride;
   a.magp_stride = p.magp_stride; a.sgnp_stride = p.sgnp_stride;
@@ -435,7 +450,7 @@ int lqsgd_decompress(lqsgd_ctx* c, int32_t phase) {
     if (c->state != kQCompressed) return fail(c, LQSGD_ESTATE, "decompress(Q) must follow compress(Q)");
     if ((rc = run_exchange(c, kMeanOnly, 1))) return rc;
     c->args.ghat = nullptr;
-    if ((rc = run_sweep2(c, 0))) return rc;
+    if ((rc = run_sweep2(c, 0, false))) return rc;
     c->state = kIdle;
     return LQSGD_OK;
   }
@@ -460,11 +475,7 @@ int lqsgd_step(lqsgd_ctx* c, const float* const* grads, float* const* ghat) {
   if ((rc = run_exchange(c, kFused, 0))) return rc;
   if ((rc = run_sweep1(c))) return rc;
   if ((rc = run_exchange(c, kFused, 1))) return rc;
-  if ((rc = run_sweep2(c, ghat != nullptr))) return rc;
-  if (c->plan.V > 0) {
-    Timed t(c, LQSGD_KERNEL_VECTOR_MEAN);
-    HIP_TRY(c, launch_vector_mean(c->args, c->d_tilesV, (int)c->plan.tilesV.size(), c->stream));
-  }
+  if ((rc = run_sweep2(c, ghat != nullptr, true))) return rc;
   return LQSGD_OK;
 }
 
@@ -616,7 +627,6 @@ const char* lqsgd_kernel_name(int32_t kernel) {
     case LQSGD_KERNEL_REDUCE_Q: return "reduce_q_kernel";
     case LQSGD_KERNEL_EXCHANGE_Q: return "exchange_kernel";
     case LQSGD_KERNEL_RESIDUAL: return "residual_kernel";
-    case LQSGD_KERNEL_VECTOR_MEAN: return "vector_mean_kernel";
     default: return "";
   }
 }

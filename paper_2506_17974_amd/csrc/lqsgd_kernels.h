@@ -30,17 +30,22 @@ struct DevArgs {
   int64_t m_stride, p_stride, q_stride, ppart_stride, qpart_stride;
   int64_t magp_stride, sgnp_stride, magq_stride, sgnq_stride;
   int32_t W, L, n_all, bits_p, bits_q;
+  float alpha;                 // log scale of Eq. (5)
+  float qscale_p, qscale_q;    // (2^b - 1) / log2(1 + alpha) for b_p, b_q
 };
 
 enum ExchangeMode { kQuantOnly = 0, kMeanOnly = 1, kFused = 2 };
 
 // Each launcher enqueues one kernel on `s` and returns hipGetLastError().
-hipError_t launch_add_project(int RP, const DevArgs& a, const Tile* tiles, int ntiles, hipStream_t s);
-hipError_t launch_orth(int RP, const DevArgs& a, hipStream_t s);
+// `reverse` walks the work list backwards: consecutive sweeps alternate direction so that
+// each one starts on the data the previous one touched last (still in the memory-side cache).
+hipError_t launch_add_project(int RP, const DevArgs& a, const Tile* tiles, int ntiles, int reverse, hipStream_t s);
+hipError_t launch_orth(int RP, int max_rows, const DevArgs& a, hipStream_t s);
 hipError_t launch_exchange(int mode, int phase, const DevArgs& a, const XTile* tiles, int ntiles, hipStream_t s);
-hipError_t launch_back_project(int RP, const DevArgs& a, const Tile* tiles, int ntiles, hipStream_t s);
+hipError_t launch_back_project(int RP, const DevArgs& a, const Tile* tiles, int ntiles, int reverse, hipStream_t s);
 hipError_t launch_reduce_q(const DevArgs& a, const RTile* tiles, int ntiles, hipStream_t s);
-hipError_t launch_residual(int RP, const DevArgs& a, const Tile* tiles, int ntiles, int write_ghat, hipStream_t s);
-hipError_t launch_vector_mean(const DevArgs& a, const VTile* tiles, int ntiles, hipStream_t s);
+// The residual sweep also runs the plain mean of the 1-D tensors (nvtiles extra workgroups).
+hipError_t launch_residual(int RP, const DevArgs& a, const Tile* tiles, int ntiles, const VTile* vtiles, int nvtiles,
+                           int write_ghat, int reverse, hipStream_t s);
 
 }  // namespace lqsgd

@@ -26,39 +26,89 @@ namespace {
 // ---------------------------------------------------------------------------
 // small helpers
 // ---------------------------------------------------------------------------
+typedef float v4f __attribute__((ext_vector_type(4)));
+// Loads through a pointer in the constant address space are assumed not to
+// change while the kernel runs; with a wave-uniform address they become
+// scalar loads (one fetch per wavefront, no vector register traffic).  Used
+// for factor rows that an earlier kernel wrote.
+typedef const float __attribute__((address_space(4)))* const_fp;
+
+// Streaming hints: data that is read once (gradients, residual) is loaded
+// with the non-temporal hint so that it does not displace the factor panels.
+#ifndef LQSGD_NT_G
+#define LQSGD_NT_G 1
+#endif
+#ifndef LQSGD_NT_E
+#define LQSGD_NT_E 1
+#endif
+#ifndef LQSGD_NT_M
+#define LQSGD_NT_M 1
+#endif
+#ifndef LQSGD_NT_ST_A      // store of M = G + E in sweep 0
+#define LQSGD_NT_ST_A 0
+#endif
+#ifndef LQSGD_NT_ST_C      // store of E in sweep 2
+#define LQSGD_NT_ST_C 0
+#endif
+#ifndef LQSGD_RT           // rows a wavefront carries through one column pass of sweep 0 (rank <= 8)
+#define LQSGD_RT 8
+#endif
+#ifndef LQSGD_A_WAVES      // occupancy target of sweep 0 (waves per SIMD)
+#define LQSGD_A_WAVES 1
+#endif
+
 template <int V>
 struct Pk {
   float v[V];
 };
 
-template <int V>
-__device__ __forceinline__ Pk<V> ldv(const float* p);
+// VEC floats at (wave-uniform row base) + (per-lane byte offset).
+template <int V, bool NT>
+__device__ __forceinline__ Pk<V> ldrow(const char* rowbase, unsigned boff);
 template <>
-__device__ __forceinline__ Pk<4> ldv<4>(const float* p) {
-  const float4 t = *reinterpret_cast<const float4*>(p);
+__device__ __forceinline__ Pk<4> ldrow<4, false>(const char* rowbase, unsigned boff) {
+  const v4f t = *reinterpret_cast<const v4f*>(rowbase + boff);
   return Pk<4>{{t.x, t.y, t.z, t.w}};
 }
 template <>
-__device__ __forceinline__ Pk<1> ldv<1>(const float* p) {
-  return Pk<1>{{*p}};
-}
-template <int V>
-__device__ __forceinline__ void stv(float* p, const Pk<V>& x);
-template <>
-__device__ __forceinline__ void stv<4>(float* p, const Pk<4>& x) {
-  *reinterpret_cast<float4*>(p) = make_float4(x.v[0], x.v[1], x.v[2], x.v[3]);
+__device__ __forceinline__ Pk<4> ldrow<4, true>(const char* rowbase, unsigned boff) {
+  const v4f t = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(rowbase + boff));
+  return Pk<4>{{t.x, t.y, t.z, t.w}};
 }
 template <>
-__device__ __forceinline__ void stv<1>(float* p, const Pk<1>& x) {
-  *p = x.v[0];
+__device__ __forceinline__ Pk<1> ldrow<1, false>(const char* rowbase, unsigned boff) {
+  return Pk<1>{{*reinterpret_cast<const float*>(rowbase + boff)}};
+}
+template <>
+__device__ __forceinline__ Pk<1> ldrow<1, true>(const char* rowbase, unsigned boff) {
+  return Pk<1>{{__builtin_nontemporal_load(reinterpret_cast<const float*>(rowbase + boff))}};
+}
+template <int V, bool NT>
+__device__ __forceinline__ void strow(char* rowbase, unsigned boff, const Pk<V>& x);
+template <>
+__device__ __forceinline__ void strow<4, false>(char* rowbase, unsigned boff, const Pk<4>& x) {
+  const v4f t = {x.v[0], x.v[1], x.v[2], x.v[3]};
+  *reinterpret_cast<v4f*>(rowbase + boff) = t;
+}
+template <>
+__device__ __forceinline__ void strow<4, true>(char* rowbase, unsigned boff, const Pk<4>& x) {
+  const v4f t = {x.v[0], x.v[1], x.v[2], x.v[3]};
+  __builtin_nontemporal_store(t, reinterpret_cast<v4f*>(rowbase + boff));
+}
+template <>
+__device__ __forceinline__ void strow<1, false>(char* rowbase, unsigned boff, const Pk<1>& x) {
+  *reinterpret_cast<float*>(rowbase + boff) = x.v[0];
+}
+template <>
+__device__ __forceinline__ void strow<1, true>(char* rowbase, unsigned boff, const Pk<1>& x) {
+  __builtin_nontemporal_store(x.v[0], reinterpret_cast<float*>(rowbase + boff));
 }
 
 // Factor slice of VEC consecutive columns starting at column c of a cols x r
-// row-major factor F, as s[v*RP + k].  `exact` (r == RP) is the fast path.
-template <int RP, int VEC>
-__device__ __forceinline__ void load_slice(const float* __restrict__ F, int c, int r, bool exact,
-                                           float (&s)[VEC * RP]) {
-  if (exact) {
+// row-major factor F, as s[v*RP + k].  EXACT (r == RP) is the fast path.
+template <int RP, int VEC, bool EXACT>
+__device__ __forceinline__ void load_slice(const float* __restrict__ F, int c, int r, float (&s)[VEC * RP]) {
+  if constexpr (EXACT) {
     const float* base = F + (size_t)c * RP;
     if constexpr ((VEC * RP) % 4 == 0) {
 #pragma unroll
@@ -78,10 +128,9 @@ __device__ __forceinline__ void load_slice(const float* __restrict__ F, int c, i
   }
 }
 
-template <int RP, int VEC>
-__device__ __forceinline__ void store_slice(float* __restrict__ F, int c, int r, bool exact,
-                                            const float (&s)[VEC * RP]) {
-  if (exact) {
+template <int RP, int VEC, bool EXACT>
+__device__ __forceinline__ void store_slice(float* __restrict__ F, int c, int r, const float (&s)[VEC * RP]) {
+  if constexpr (EXACT) {
     float* base = F + (size_t)c * RP;
     if constexpr ((VEC * RP) % 4 == 0) {
 #pragma unroll
@@ -100,7 +149,7 @@ __device__ __forceinline__ void store_slice(float* __restrict__ F, int c, int r,
   }
 }
 
-// Wave-uniform row of a rows x r factor into p[k] (zero beyond r).
+// Row of a rows x r factor into p[k] (zero beyond r), plain loads.
 template <int RP>
 __device__ __forceinline__ void load_row(const float* __restrict__ F, int row, int r, bool exact, float (&p)[RP]) {
   if (exact) {
@@ -109,6 +158,20 @@ __device__ __forceinline__ void load_row(const float* __restrict__ F, int row, i
     for (int k = 0; k < RP; ++k) p[k] = b[k];
   } else {
     const float* b = F + (size_t)row * r;
+#pragma unroll
+    for (int k = 0; k < RP; ++k) p[k] = (k < r) ? b[k] : 0.0f;
+  }
+}
+
+// Wave-uniform row of a factor written by an earlier kernel: scalar loads.
+template <int RP, bool EXACT>
+__device__ __forceinline__ void load_row_uniform(const float* F, int row, int r, float (&p)[RP]) {
+  if constexpr (EXACT) {
+    const_fp b = (const_fp)(F + (size_t)row * RP);
+#pragma unroll
+    for (int k = 0; k < RP; ++k) p[k] = b[k];
+  } else {
+    const_fp b = (const_fp)(F + (size_t)row * r);
 #pragma unroll
     for (int k = 0; k < RP; ++k) p[k] = (k < r) ? b[k] : 0.0f;
   }
@@ -154,55 +217,66 @@ constexpr int log2c(int n) { return n <= 1 ? 0 : 1 + log2c(n / 2); }
 
 // ---------------------------------------------------------------------------
 // sweep 0: M = G + E (Eq. (9)),  P_w partial = M_w Q  (Algorithm 1, "P <- G'Q")
-// One wavefront per work item: rows [row0, row0+nrows) x columns [col0, col1).
+// One wavefront per work item: rows [row0, row0+nrows) x columns [col0, col1),
+// RT rows at a time; a lane accumulates RT x r partial dot products over its
+// columns, one butterfly per row group adds them over the lanes.
 // ---------------------------------------------------------------------------
-template <int RP, int VEC, int RT>
+template <int RP, int VEC, int RT, bool EXACT, bool FULL>
+__device__ __forceinline__ void add_project_cols(const char* const (&gr)[RT], char* const (&mr)[RT],
+                                                 const float* __restrict__ Q, int r, int nr, int cbeg, int cend,
+                                                 float (&acc)[RT * RP]) {
+  for (int c = cbeg; c < cend; c += kWave * VEC) {
+    float q[VEC * RP];
+    load_slice<RP, VEC, EXACT>(Q, c, r, q);
+    const unsigned boff = (unsigned)c * 4u;
+    Pk<VEC> g[RT], e[RT];
+#pragma unroll
+    for (int t = 0; t < RT; ++t) {
+      if (FULL || t < nr) {
+        g[t] = ldrow<VEC, LQSGD_NT_G != 0>(gr[t], boff);
+        e[t] = ldrow<VEC, LQSGD_NT_E != 0>(mr[t], boff);
+      } else {
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) { g[t].v[v] = 0.0f; e[t].v[v] = 0.0f; }
+      }
+    }
+#pragma unroll
+    for (int t = 0; t < RT; ++t) {
+      Pk<VEC> m;
+#pragma unroll
+      for (int v = 0; v < VEC; ++v) m.v[v] = g[t].v[v] + e[t].v[v];
+      if (FULL || t < nr) strow<VEC, LQSGD_NT_ST_A != 0>(mr[t], boff, m);
+#pragma unroll
+      for (int v = 0; v < VEC; ++v)
+#pragma unroll
+        for (int k = 0; k < RP; ++k) acc[t * RP + k] = fmaf(m.v[v], q[v * RP + k], acc[t * RP + k]);
+    }
+  }
+}
+
+template <int RP, int VEC, int RT, bool EXACT>
 __device__ __forceinline__ void add_project_tile(const float* __restrict__ G, float* __restrict__ M,
                                                  const float* __restrict__ Q, float* __restrict__ Pp,
                                                  int cols, int r, int row0, int nrows, int col0, int col1,
                                                  int lane) {
   constexpr int N = RT * RP;
-  const bool exact = (r == RP);
   for (int rg = 0; rg < nrows; rg += RT) {
     const int nr = min(RT, nrows - rg);
     float acc[N];
 #pragma unroll
     for (int i = 0; i < N; ++i) acc[i] = 0.0f;
-    const size_t rowbase = (size_t)(row0 + rg) * cols;
-    for (int c = col0 + lane * VEC; c < col1; c += kWave * VEC) {
-      float q[VEC * RP];
-      load_slice<RP, VEC>(Q, c, r, exact, q);
-      Pk<VEC> g[RT], e[RT];
-      if (nr == RT) {
+    const char* gr[RT];
+    char* mr[RT];
 #pragma unroll
-        for (int t = 0; t < RT; ++t) {
-          g[t] = ldv<VEC>(G + rowbase + (size_t)t * cols + c);
-          e[t] = ldv<VEC>(M + rowbase + (size_t)t * cols + c);
-        }
-      } else {
-#pragma unroll
-        for (int t = 0; t < RT; ++t) {
-          if (t < nr) {
-            g[t] = ldv<VEC>(G + rowbase + (size_t)t * cols + c);
-            e[t] = ldv<VEC>(M + rowbase + (size_t)t * cols + c);
-          } else {
-#pragma unroll
-            for (int v = 0; v < VEC; ++v) { g[t].v[v] = 0.0f; e[t].v[v] = 0.0f; }
-          }
-        }
-      }
-#pragma unroll
-      for (int t = 0; t < RT; ++t) {
-        Pk<VEC> m;
-#pragma unroll
-        for (int v = 0; v < VEC; ++v) m.v[v] = g[t].v[v] + e[t].v[v];
-        if (t < nr) stv<VEC>(M + rowbase + (size_t)t * cols + c, m);
-#pragma unroll
-        for (int v = 0; v < VEC; ++v)
-#pragma unroll
-          for (int k = 0; k < RP; ++k) acc[t * RP + k] = fmaf(m.v[v], q[v * RP + k], acc[t * RP + k]);
-      }
+    for (int t = 0; t < RT; ++t) {
+      const size_t off = (size_t)(row0 + rg + min(t, nr - 1)) * cols;
+      gr[t] = reinterpret_cast<const char*>(G + off);
+      mr[t] = reinterpret_cast<char*>(M + off);
     }
+    if (nr == RT)
+      add_project_cols<RP, VEC, RT, EXACT, true>(gr, mr, Q, r, nr, col0 + lane * VEC, col1, acc);
+    else
+      add_project_cols<RP, VEC, RT, EXACT, false>(gr, mr, Q, r, nr, col0 + lane * VEC, col1, acc);
     transpose_reduce<N, N, 32>(acc, lane);
     constexpr int NPL = (N >= kWave) ? N / kWave : 1;
 #pragma unroll
@@ -223,13 +297,13 @@ __device__ __forceinline__ void add_project_tile(const float* __restrict__ G, fl
 }
 
 template <int RP>
-__global__ __launch_bounds__(256) void add_project_kernel(DevArgs a, const Tile* __restrict__ tiles, int ntiles) {
-  constexpr int RT = (RP <= 8) ? 8 : 4;
+__global__ __launch_bounds__(256, LQSGD_A_WAVES) void add_project_kernel(DevArgs a, const Tile* __restrict__ tiles, int ntiles, int reverse) {
+  constexpr int RT = (RP <= 8) ? LQSGD_RT : 4;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int lane = threadIdx.x & (kWave - 1);
   const int t = blockIdx.x * 4 + wave;
   if (t >= ntiles) return;
-  const Tile tl = tiles[t];
+  const Tile tl = tiles[reverse ? ntiles - 1 - t : t];
   const int layer = tl.lw / a.W, worker = tl.lw - layer * a.W;
   const LayerDesc& ld = a.layers[layer];
   const float* G = a.grads[(size_t)worker * a.n_all + ld.gidx];
@@ -238,10 +312,15 @@ __global__ __launch_bounds__(256) void add_project_kernel(DevArgs a, const Tile*
   float* Pp = a.Ppart + (size_t)worker * a.ppart_stride + ld.ppart_off + (size_t)tl.aux * ld.np_pad;
   const int col0 = tl.aux * ld.segw;
   const int col1 = min(ld.cols, col0 + ld.segw);
-  if (ld.vec == 4)
-    add_project_tile<RP, 4, RT>(G, M, Q, Pp, ld.cols, ld.r, tl.row0, tl.nrows, col0, col1, lane);
-  else
-    add_project_tile<RP, 1, RT>(G, M, Q, Pp, ld.cols, ld.r, tl.row0, tl.nrows, col0, col1, lane);
+  if (ld.vec == 4) {
+    if (ld.r == RP)
+      add_project_tile<RP, 4, RT, true>(G, M, Q, Pp, ld.cols, ld.r, tl.row0, tl.nrows, col0, col1, lane);
+    else
+      add_project_tile<RP, 4, RT, false>(G, M, Q, Pp, ld.cols, ld.r, tl.row0, tl.nrows, col0, col1, lane);
+  } else {
+    // rows that are not 16-byte aligned (cols % 4 != 0): tiny layers, one generic path
+    add_project_tile<RP, 1, RT, false>(G, M, Q, Pp, ld.cols, ld.r, tl.row0, tl.nrows, col0, col1, lane);
+  }
 }
 
 // ---------------------------------------------------------------------------
@@ -331,19 +410,130 @@ __global__ __launch_bounds__(256) void orth_kernel(DevArgs a) {
 }
 
 // ---------------------------------------------------------------------------
+// orth, register-resident: the same computation for layers of at most
+// BS * RPT rows; a lane keeps its RPT rows in registers through all passes and
+// only the block-wide sums go through LDS (one barrier per column).
+// ---------------------------------------------------------------------------
+template <int RP, int RPT, int BS>
+__global__ __launch_bounds__(BS) void orth_reg_kernel(DevArgs a) {
+  constexpr int NW = BS / kWave;
+  constexpr int LG = log2c(RP);
+  __shared__ float red[2][NW][RP];
+  __shared__ float redmax[NW];
+  const int lw = blockIdx.x;
+  const int layer = lw / a.W, worker = lw - layer * a.W;
+  const LayerDesc& ld = a.layers[layer];
+  const int rows = ld.rows, r = ld.r, nseg = ld.nseg;
+  const bool exact = (r == RP);
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
+  const float* Pp = a.Ppart + (size_t)worker * a.ppart_stride + ld.ppart_off;
+  float* pre = a.Ppre + (size_t)worker * a.p_stride + ld.p_off;
+  float* orth = a.Porth + (size_t)worker * a.p_stride + ld.p_off;
+
+  float v[RPT][RP];
+#pragma unroll
+  for (int i = 0; i < RPT; ++i) {
+    const int row = tid + i * BS;
+#pragma unroll
+    for (int k = 0; k < RP; ++k) v[i][k] = 0.0f;
+    if (row < rows) {
+      for (int s = 0; s < nseg; ++s) {
+        float t[RP];
+        load_row<RP>(Pp + (size_t)s * ld.np_pad, row, r, exact, t);
+#pragma unroll
+        for (int k = 0; k < RP; ++k) v[i][k] += t[k];
+      }
+#pragma unroll
+      for (int k = 0; k < RP; ++k)
+        if (k < r) pre[(size_t)row * r + k] = v[i][k];
+    }
+  }
+
+#pragma unroll
+  for (int j = 0; j < RP; ++j) {
+    if (j < r) {
+      float s[RP];
+#pragma unroll
+      for (int k = 0; k < RP; ++k) s[k] = 0.0f;
+#pragma unroll
+      for (int i = 0; i < RPT; ++i)
+#pragma unroll
+        for (int k = 0; k < RP; ++k) s[k] = fmaf(v[i][j], v[i][k], s[k]);
+      transpose_reduce<RP, RP, 32>(s, lane);
+      const int b = j & 1;
+      if ((lane & (kWave / RP - 1)) == 0) red[b][wave][lane >> (6 - LG)] = s[0];
+      __syncthreads();
+#pragma unroll
+      for (int k = 0; k < RP; ++k) {
+        float t = 0.0f;
+#pragma unroll
+        for (int wv = 0; wv < NW; ++wv) t += red[b][wv][k];
+        s[k] = t;
+      }
+      const float nrm2 = s[j];
+      const float inv = (nrm2 > FLT_MIN) ? 1.0f / sqrtf(nrm2) : 0.0f;
+#pragma unroll
+      for (int i = 0; i < RPT; ++i) {
+        const float qv = v[i][j] * inv;
+        v[i][j] = qv;
+#pragma unroll
+        for (int k = j + 1; k < RP; ++k) v[i][k] = fmaf(-(s[k] * inv), qv, v[i][k]);
+      }
+    }
+  }
+
+  float mx = 0.0f;
+#pragma unroll
+  for (int i = 0; i < RPT; ++i) {
+    const int row = tid + i * BS;
+    if (row < rows) {
+#pragma unroll
+      for (int k = 0; k < RP; ++k)
+        if (k < r) {
+          orth[(size_t)row * r + k] = v[i][k];
+          mx = fmaxf(mx, fabsf(v[i][k]));
+        }
+    }
+  }
+  mx = wave_max(mx);
+  if (lane == 0) redmax[wave] = mx;
+  __syncthreads();
+  if (tid == 0) {
+    float m = redmax[0];
+#pragma unroll
+    for (int wv = 1; wv < NW; ++wv) m = fmaxf(m, redmax[wv]);
+    a.scaleP[(size_t)worker * a.L + layer] = m;
+  }
+}
+
+// ---------------------------------------------------------------------------
 // exchange: LogQuantize (Eq. (5) discretised to 2^b levels, Section 4.1),
 // pack, LogDequantize (Eq. (6)) and the mean over workers that stands in for
-// the All-Reduce.  A lane handles 8 consecutive factor elements of every
-// worker: b magnitude bytes + 1 sign byte per worker.
+// the All-Reduce.
 //   kQuantOnly: factors -> packets      kMeanOnly: packets -> mean
 //   kFused:     factors -> packets and mean in one pass
-// The code of u = |x|/s is the number of thresholds <= u (binary search in
-// LDS), which is nearest-level rounding in the q-domain of Eq. (5).
+// A workgroup takes kXBlockGroups groups of 8 consecutive factor elements; a
+// lane handles one (group, worker) pair -- b magnitude bytes + 1 sign byte --
+// eight workers at a time; the dequantised values meet in LDS, where lane
+// (group, j) adds up element j over the workers in worker order.
+// The code of u = |x|/s is the number of decision thresholds <= u, i.e.
+// nearest-level rounding in the q-domain of Eq. (5): a hardware log2 gives the
+// level to within one, the two loops move it to the exact count.
 // ---------------------------------------------------------------------------
+__device__ __forceinline__ int quantise_one(float u, float alpha, float qscale, int lv, const float* s_thr) {
+  const float t = __log2f(fmaf(alpha, u, 1.0f)) * qscale;
+  int k = (int)(t + 0.5f);
+  k = max(0, min(lv, k));
+  while (k < lv && s_thr[k] <= u) ++k;
+  while (k > 0 && s_thr[k - 1] > u) --k;
+  return k;
+}
+
 template <int MODE>
 __global__ __launch_bounds__(256) void exchange_kernel(DevArgs a, const XTile* __restrict__ tiles, int phase) {
   __shared__ float s_thr[256];
   __shared__ float s_lev[256];
+  __shared__ float s_val[8][kXGroup][kXBlockGroups];   // [worker slot][element][group]
   const int bits = phase ? a.bits_q : a.bits_p;
   const int lv = (1 << bits) - 1;
   const int tid = threadIdx.x;
@@ -357,10 +547,12 @@ __global__ __launch_bounds__(256) void exchange_kernel(DevArgs a, const XTile* _
   const XTile tl = tiles[blockIdx.x];
   const LayerDesc& ld = a.layers[tl.layer];
   const int n_el = phase ? ld.nq_el : ld.np_el;
-  const int g = tl.grp0 + tid;
+  const int gl = tid & (kXBlockGroups - 1);
+  const int slot = tid / kXBlockGroups;            // worker slot, and the element this lane sums
+  const int g = tl.grp0 + gl;
   const int e0 = g * kXGroup;
-  if (e0 >= n_el) return;
-  const int nvalid = min(kXGroup, n_el - e0);
+  const bool gvalid = e0 < n_el;
+  const int nvalid = gvalid ? min(kXGroup, n_el - e0) : 0;
   const size_t fstride = phase ? a.q_stride : a.p_stride;
   const float* fac = (phase ? a.Qw + ld.q_off : a.Porth + ld.p_off) + e0;
   uint8_t* mag = (phase ? a.magQ + ld.magq_off : a.magP + ld.magp_off) + (size_t)g * bits;
@@ -368,101 +560,102 @@ __global__ __launch_bounds__(256) void exchange_kernel(DevArgs a, const XTile* _
   const size_t mstride = phase ? a.magq_stride : a.magp_stride;
   const size_t sstride = phase ? a.sgnq_stride : a.sgnp_stride;
   const float* scale = phase ? a.scaleQ : a.scaleP;
+  const float qscale = phase ? a.qscale_q : a.qscale_p;
 
-  float acc[kXGroup];
+  float acc = 0.0f;
+  for (int wbase = 0; wbase < a.W; wbase += 8) {
+    const int w = wbase + slot;
+    float val[kXGroup];
 #pragma unroll
-  for (int i = 0; i < kXGroup; ++i) acc[i] = 0.0f;
-
-  for (int w = 0; w < a.W; ++w) {
-    float x[kXGroup];
-    if (MODE != kMeanOnly || bits == 0) {
-      const float4 lo = reinterpret_cast<const float4*>(fac + (size_t)w * fstride)[0];
-      const float4 hi = reinterpret_cast<const float4*>(fac + (size_t)w * fstride)[1];
-      x[0] = lo.x; x[1] = lo.y; x[2] = lo.z; x[3] = lo.w;
-      x[4] = hi.x; x[5] = hi.y; x[6] = hi.z; x[7] = hi.w;
+    for (int i = 0; i < kXGroup; ++i) val[i] = 0.0f;
+    if (gvalid && w < a.W) {
+      float x[kXGroup];
+      if (MODE != kMeanOnly || bits == 0) {
+        const float4 lo = reinterpret_cast<const float4*>(fac + (size_t)w * fstride)[0];
+        const float4 hi = reinterpret_cast<const float4*>(fac + (size_t)w * fstride)[1];
+        x[0] = lo.x; x[1] = lo.y; x[2] = lo.z; x[3] = lo.w;
+        x[4] = hi.x; x[5] = hi.y; x[6] = hi.z; x[7] = hi.w;
 #pragma unroll
-      for (int i = 0; i < kXGroup; ++i)
-        if (i >= nvalid) x[i] = 0.0f;
-    }
-    if (bits == 0) {
-      if (MODE != kQuantOnly) {
-#pragma unroll
-        for (int i = 0; i < kXGroup; ++i) acc[i] += x[i];
+        for (int i = 0; i < kXGroup; ++i)
+          if (i >= nvalid) x[i] = 0.0f;
       }
-      continue;
-    }
-    const float s = scale[(size_t)w * a.L + tl.layer];
-    unsigned long long magbits = 0;
-    unsigned sgnbits = 0;
-    if (MODE != kMeanOnly) {
+      if (bits == 0) {
 #pragma unroll
-      for (int i = 0; i < kXGroup; ++i) {
-        int k = 0;
-        if (s > 0.0f) {
-          const float u = fabsf(x[i]) / s;
-          int lo = 0, hi = lv;
-          while (lo < hi) {
-            const int mid = (lo + hi) >> 1;
-            if (s_thr[mid] <= u) lo = mid + 1; else hi = mid;
-          }
-          k = lo;
-        }
-        magbits |= (unsigned long long)k << (i * bits);
-        if (x[i] < 0.0f && k > 0) sgnbits |= 1u << i;
-      }
-      uint8_t* mp = mag + (size_t)w * mstride;
-      if (bits == 8) {
-        *reinterpret_cast<unsigned long long*>(mp) = magbits;
-      } else if (bits == 4) {
-        *reinterpret_cast<unsigned*>(mp) = (unsigned)magbits;
-      } else if (bits == 2) {
-        *reinterpret_cast<unsigned short*>(mp) = (unsigned short)magbits;
+        for (int i = 0; i < kXGroup; ++i) val[i] = x[i];
       } else {
-        for (int bb = 0; bb < bits; ++bb) mp[bb] = (uint8_t)(magbits >> (8 * bb));
+        const float s = scale[(size_t)w * a.L + tl.layer];
+        unsigned long long magbits = 0;
+        unsigned sgnbits = 0;
+        if (MODE != kMeanOnly) {
+#pragma unroll
+          for (int i = 0; i < kXGroup; ++i) {
+            const int k = (s > 0.0f) ? quantise_one(fabsf(x[i]) / s, a.alpha, qscale, lv, s_thr) : 0;
+            magbits |= (unsigned long long)k << (i * bits);
+            if (x[i] < 0.0f && k > 0) sgnbits |= 1u << i;
+          }
+          uint8_t* mp = mag + (size_t)w * mstride;
+          if (bits == 8) {
+            *reinterpret_cast<unsigned long long*>(mp) = magbits;
+          } else if (bits == 4) {
+            *reinterpret_cast<unsigned*>(mp) = (unsigned)magbits;
+          } else if (bits == 2) {
+            *reinterpret_cast<unsigned short*>(mp) = (unsigned short)magbits;
+          } else {
+            for (int bb = 0; bb < bits; ++bb) mp[bb] = (uint8_t)(magbits >> (8 * bb));
+          }
+          sgn[(size_t)w * sstride] = (uint8_t)sgnbits;
+        } else {
+          const uint8_t* mp = mag + (size_t)w * mstride;
+          for (int bb = 0; bb < bits; ++bb) magbits |= (unsigned long long)mp[bb] << (8 * bb);
+          sgnbits = sgn[(size_t)w * sstride];
+        }
+        if (MODE != kQuantOnly) {
+#pragma unroll
+          for (int i = 0; i < kXGroup; ++i) {
+            const int k = (int)((magbits >> (i * bits)) & (unsigned long long)lv);
+            const float v = s * s_lev[k];
+            val[i] = ((sgnbits >> i) & 1u) ? -v : v;
+          }
+        }
       }
-      sgn[(size_t)w * sstride] = (uint8_t)sgnbits;
-    } else {
-      const uint8_t* mp = mag + (size_t)w * mstride;
-      for (int bb = 0; bb < bits; ++bb) magbits |= (unsigned long long)mp[bb] << (8 * bb);
-      sgnbits = sgn[(size_t)w * sstride];
     }
     if (MODE != kQuantOnly) {
 #pragma unroll
-      for (int i = 0; i < kXGroup; ++i) {
-        const int k = (int)((magbits >> (i * bits)) & (unsigned long long)lv);
-        const float val = s * s_lev[k];
-        acc[i] += ((sgnbits >> i) & 1u) ? -val : val;
-      }
+      for (int i = 0; i < kXGroup; ++i) s_val[slot][i][gl] = val[i];
+      __syncthreads();
+      const int nw = min(8, a.W - wbase);
+      for (int sidx = 0; sidx < nw; ++sidx) acc += s_val[sidx][slot][gl];
+      __syncthreads();
     }
   }
   if (MODE != kQuantOnly) {
-    float* out = (phase ? a.Qbar + ld.q_off : a.Pbar + ld.p_off) + e0;
-    const float wf = (float)a.W;
-#pragma unroll
-    for (int i = 0; i < kXGroup; ++i)
-      if (i < nvalid) out[i] = acc[i] / wf;
+    if (gvalid && slot < nvalid) {
+      float* out = (phase ? a.Qbar + ld.q_off : a.Pbar + ld.p_off) + e0;
+      out[slot] = acc / (float)a.W;
+    }
   }
 }
 
 // ---------------------------------------------------------------------------
 // sweep 1: Q_w partial = M_w^T P-bar over a row block (Algorithm 1,
 // "Q <- G'^T P").  One workgroup per (row block, 64*VEC-column chunk); its four
-// wavefronts split the rows and combine through LDS in a fixed tree.
+// wavefronts split the rows and their partial sums meet in LDS, where they are
+// added in wavefront order.
 // ---------------------------------------------------------------------------
-template <int RP, int VEC>
-__device__ __forceinline__ void back_project_rows(const float* __restrict__ M, const float* __restrict__ Pb,
-                                                  int cols, int r, bool exact, int ra, int rb, int c,
-                                                  float (&acc)[VEC * RP]) {
+template <int RP, int VEC, bool EXACT>
+__device__ __forceinline__ void back_project_rows(const float* __restrict__ M, const float* Pb, int cols, int r,
+                                                  int ra, int rb, unsigned boff, float (&acc)[VEC * RP]) {
   constexpr int U = 8;
   int i = ra;
   for (; i + U <= rb; i += U) {
     Pk<VEC> m[U];
 #pragma unroll
-    for (int u = 0; u < U; ++u) m[u] = ldv<VEC>(M + (size_t)(i + u) * cols + c);
+    for (int u = 0; u < U; ++u)
+      m[u] = ldrow<VEC, LQSGD_NT_M != 0>(reinterpret_cast<const char*>(M + (size_t)(i + u) * cols), boff);
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       float p[RP];
-      load_row<RP>(Pb, i + u, r, exact, p);
+      load_row_uniform<RP, EXACT>(Pb, i + u, r, p);
 #pragma unroll
       for (int v = 0; v < VEC; ++v)
 #pragma unroll
@@ -470,9 +663,9 @@ __device__ __forceinline__ void back_project_rows(const float* __restrict__ M, c
     }
   }
   for (; i < rb; ++i) {
-    const Pk<VEC> m = ldv<VEC>(M + (size_t)i * cols + c);
+    const Pk<VEC> m = ldrow<VEC, LQSGD_NT_M != 0>(reinterpret_cast<const char*>(M + (size_t)i * cols), boff);
     float p[RP];
-    load_row<RP>(Pb, i, r, exact, p);
+    load_row_uniform<RP, EXACT>(Pb, i, r, p);
 #pragma unroll
     for (int v = 0; v < VEC; ++v)
 #pragma unroll
@@ -480,15 +673,15 @@ __device__ __forceinline__ void back_project_rows(const float* __restrict__ M, c
   }
 }
 
-template <int RP, int VEC>
+template <int RP, int VEC, bool EXACT>
 __device__ __forceinline__ void back_project_tile(const DevArgs& a, const LayerDesc& ld, const Tile& tl, int worker,
                                                   float* comb, int wave, int lane) {
   constexpr int NV = VEC * RP;
   const int cols = ld.cols, r = ld.r;
-  const bool exact = (r == RP);
   const float* M = a.E + (size_t)worker * a.m_stride + ld.m_off;
   const float* Pb = a.Pbar + ld.p_off;
-  const int c = tl.aux * (kWave * VEC) + lane * VEC;
+  const int c0 = tl.aux * (kWave * VEC);
+  const int c = c0 + lane * VEC;
   const bool active = c < cols;
   const int per = (tl.nrows + 3) >> 2;
   const int ra = min(tl.row0 + wave * per, tl.row0 + tl.nrows);
@@ -496,46 +689,77 @@ __device__ __forceinline__ void back_project_tile(const DevArgs& a, const LayerD
   float acc[NV];
 #pragma unroll
   for (int i = 0; i < NV; ++i) acc[i] = 0.0f;
-  if (active) back_project_rows<RP, VEC>(M, Pb, cols, r, exact, ra, rb, c, acc);
-  // (wave 0 + wave 2) + (wave 1 + wave 3)
-  if (wave >= 2) {
+  if (active) back_project_rows<RP, VEC, EXACT>(M, Pb, cols, r, ra, rb, (unsigned)c * 4u, acc);
+  float* Qp = a.Qpart + (size_t)worker * a.qpart_stride + ld.qpart_off + (size_t)(tl.row0 / ld.rbb) * ld.nq_pad;
+  if constexpr (EXACT && NV % 4 == 0 && NV <= 64) {
+    // comb[wave][lane * NV + i]; afterwards every lane of the workgroup adds the four
+    // partials of NV/4 consecutive outputs (wave order) and stores them: the chunk's
+    // slice of the factor is contiguous, 64 * NV floats from column c0.
 #pragma unroll
-    for (int i = 0; i < NV; ++i) comb[(wave - 2) * (kWave * NV) + i * kWave + lane] = acc[i];
-  }
-  __syncthreads();
-  if (wave < 2) {
+    for (int i = 0; i < NV / 4; ++i)
+      reinterpret_cast<float4*>(comb + (size_t)wave * (kWave * NV) + lane * NV)[i] =
+          make_float4(acc[4 * i], acc[4 * i + 1], acc[4 * i + 2], acc[4 * i + 3]);
+    __syncthreads();
+    const int tid = wave * kWave + lane;
+    const int nout = min(kWave * VEC, cols - c0) * RP;     // floats this chunk owns
 #pragma unroll
-    for (int i = 0; i < NV; ++i) acc[i] += comb[wave * (kWave * NV) + i * kWave + lane];
-  }
-  __syncthreads();
-  if (wave == 1) {
+    for (int j = 0; j < (NV + 15) / 16; ++j) {   // 64 * NV / 4 float4 outputs over 256 lanes
+      const int o = (j * 256 + tid) * 4;
+      if (o < nout) {
+        float4 s = reinterpret_cast<const float4*>(comb + o)[0];
 #pragma unroll
-    for (int i = 0; i < NV; ++i) comb[i * kWave + lane] = acc[i];
-  }
-  __syncthreads();
-  if (wave == 0 && active) {
+        for (int wv = 1; wv < 4; ++wv) {
+          const float4 t = reinterpret_cast<const float4*>(comb + (size_t)wv * (kWave * NV) + o)[0];
+          s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
+        }
+        reinterpret_cast<float4*>(Qp + (size_t)c0 * RP + o)[0] = s;
+      }
+    }
+  } else {
+    // generic path: (wave 0 + wave 2) + (wave 1 + wave 3) through two LDS planes
+    if (wave >= 2) {
 #pragma unroll
-    for (int i = 0; i < NV; ++i) acc[i] += comb[i * kWave + lane];
-    float* Qp = a.Qpart + (size_t)worker * a.qpart_stride + ld.qpart_off + (size_t)(tl.row0 / ld.rbb) * ld.nq_pad;
-    store_slice<RP, VEC>(Qp, c, r, exact, acc);
+      for (int i = 0; i < NV; ++i) comb[(wave - 2) * (kWave * NV) + i * kWave + lane] = acc[i];
+    }
+    __syncthreads();
+    if (wave < 2) {
+#pragma unroll
+      for (int i = 0; i < NV; ++i) acc[i] += comb[wave * (kWave * NV) + i * kWave + lane];
+    }
+    __syncthreads();
+    if (wave == 1) {
+#pragma unroll
+      for (int i = 0; i < NV; ++i) comb[i * kWave + lane] = acc[i];
+    }
+    __syncthreads();
+    if (wave == 0 && active) {
+#pragma unroll
+      for (int i = 0; i < NV; ++i) acc[i] += comb[i * kWave + lane];
+      store_slice<RP, VEC, EXACT>(Qp, c, r, acc);
+    }
   }
 }
 
 template <int RP>
-__global__ __launch_bounds__(256) void back_project_kernel(DevArgs a, const Tile* __restrict__ tiles) {
-  __shared__ float comb[2 * kWave * 4 * RP];
+__global__ __launch_bounds__(256) void back_project_kernel(DevArgs a, const Tile* __restrict__ tiles, int reverse) {
+  // fast path: 4 planes of 64 * 4 * RP floats (RP <= 16); generic path: 2 planes
+  __shared__ float comb[(RP <= 16 ? 4 : 2) * kWave * 4 * RP];
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int lane = threadIdx.x & (kWave - 1);
   if (blockIdx.x == 0) {   // absmax accumulators of reduce_q start from zero
     for (int i = threadIdx.x; i < a.W * a.L; i += 256) a.scaleQ[i] = 0.0f;
   }
-  const Tile tl = tiles[blockIdx.x];
+  const Tile tl = tiles[reverse ? gridDim.x - 1 - blockIdx.x : blockIdx.x];
   const int layer = tl.lw / a.W, worker = tl.lw - layer * a.W;
   const LayerDesc& ld = a.layers[layer];
-  if (ld.vec == 4)
-    back_project_tile<RP, 4>(a, ld, tl, worker, comb, wave, lane);
-  else
-    back_project_tile<RP, 1>(a, ld, tl, worker, comb, wave, lane);
+  if (ld.vec == 4) {
+    if (ld.r == RP)
+      back_project_tile<RP, 4, true>(a, ld, tl, worker, comb, wave, lane);
+    else
+      back_project_tile<RP, 4, false>(a, ld, tl, worker, comb, wave, lane);
+  } else {
+    back_project_tile<RP, 1, false>(a, ld, tl, worker, comb, wave, lane);
+  }
 }
 
 // ---------------------------------------------------------------------------
@@ -583,31 +807,21 @@ __global__ __launch_bounds__(256) void reduce_q_kernel(DevArgs a, const RTile* _
 // write G-hat when the caller asked for it.  Same work items as sweep 1, the
 // four wavefronts of a workgroup split the rows.
 // ---------------------------------------------------------------------------
-template <int RP, int VEC>
-__device__ __forceinline__ void residual_tile(const DevArgs& a, const LayerDesc& ld, const Tile& tl, int worker,
-                                              float* __restrict__ ghat, int wave, int lane) {
-  constexpr int NV = VEC * RP;
+template <int RP, int VEC, bool EXACT, bool GHAT>
+__device__ __forceinline__ void residual_rows(float* __restrict__ M, const float* Pb, float* __restrict__ ghat,
+                                              int cols, int r, int ra, int rb, unsigned boff,
+                                              const float (&q)[VEC * RP]) {
   constexpr int U = 8;
-  const int cols = ld.cols, r = ld.r;
-  const bool exact = (r == RP);
-  float* M = a.E + (size_t)worker * a.m_stride + ld.m_off;
-  const float* Pb = a.Pbar + ld.p_off;
-  const int c = tl.aux * (kWave * VEC) + lane * VEC;
-  if (c >= cols) return;
-  const int per = (tl.nrows + 3) >> 2;
-  const int ra = min(tl.row0 + wave * per, tl.row0 + tl.nrows);
-  const int rb = min(ra + per, tl.row0 + tl.nrows);
-  float q[NV];
-  load_slice<RP, VEC>(a.Qbar + ld.q_off, c, r, exact, q);
   int i = ra;
   for (; i + U <= rb; i += U) {
     Pk<VEC> m[U];
 #pragma unroll
-    for (int u = 0; u < U; ++u) m[u] = ldv<VEC>(M + (size_t)(i + u) * cols + c);
+    for (int u = 0; u < U; ++u)
+      m[u] = ldrow<VEC, LQSGD_NT_M != 0>(reinterpret_cast<const char*>(M + (size_t)(i + u) * cols), boff);
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       float p[RP];
-      load_row<RP>(Pb, i + u, r, exact, p);
+      load_row_uniform<RP, EXACT>(Pb, i + u, r, p);
       Pk<VEC> gh, e;
 #pragma unroll
       for (int v = 0; v < VEC; ++v) {
@@ -617,14 +831,14 @@ __device__ __forceinline__ void residual_tile(const DevArgs& a, const LayerDesc&
         gh.v[v] = s;
         e.v[v] = m[u].v[v] - s;
       }
-      stv<VEC>(M + (size_t)(i + u) * cols + c, e);
-      if (ghat) stv<VEC>(ghat + (size_t)(i + u) * cols + c, gh);
+      strow<VEC, LQSGD_NT_ST_C != 0>(reinterpret_cast<char*>(M + (size_t)(i + u) * cols), boff, e);
+      if (GHAT) strow<VEC, true>(reinterpret_cast<char*>(ghat + (size_t)(i + u) * cols), boff, gh);
     }
   }
   for (; i < rb; ++i) {
-    const Pk<VEC> m = ldv<VEC>(M + (size_t)i * cols + c);
+    const Pk<VEC> m = ldrow<VEC, LQSGD_NT_M != 0>(reinterpret_cast<const char*>(M + (size_t)i * cols), boff);
     float p[RP];
-    load_row<RP>(Pb, i, r, exact, p);
+    load_row_uniform<RP, EXACT>(Pb, i, r, p);
     Pk<VEC> gh, e;
 #pragma unroll
     for (int v = 0; v < VEC; ++v) {
@@ -634,31 +848,36 @@ __device__ __forceinline__ void residual_tile(const DevArgs& a, const LayerDesc&
       gh.v[v] = s;
       e.v[v] = m.v[v] - s;
     }
-    stv<VEC>(M + (size_t)i * cols + c, e);
-    if (ghat) stv<VEC>(ghat + (size_t)i * cols + c, gh);
+    strow<VEC, LQSGD_NT_ST_C != 0>(reinterpret_cast<char*>(M + (size_t)i * cols), boff, e);
+    if (GHAT) strow<VEC, true>(reinterpret_cast<char*>(ghat + (size_t)i * cols), boff, gh);
   }
 }
 
-template <int RP>
-__global__ __launch_bounds__(256) void residual_kernel(DevArgs a, const Tile* __restrict__ tiles, int write_ghat) {
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int lane = threadIdx.x & (kWave - 1);
-  const Tile tl = tiles[blockIdx.x];
-  const int layer = tl.lw / a.W, worker = tl.lw - layer * a.W;
-  const LayerDesc& ld = a.layers[layer];
-  float* ghat = nullptr;
-  if (write_ghat && worker == 0 && a.ghat) ghat = a.ghat[ld.gidx];
-  if (ld.vec == 4)
-    residual_tile<RP, 4>(a, ld, tl, worker, ghat, wave, lane);
+template <int RP, int VEC, bool EXACT>
+__device__ __forceinline__ void residual_tile(const DevArgs& a, const LayerDesc& ld, const Tile& tl, int worker,
+                                              float* __restrict__ ghat, int wave, int lane) {
+  constexpr int NV = VEC * RP;
+  const int cols = ld.cols, r = ld.r;
+  float* M = a.E + (size_t)worker * a.m_stride + ld.m_off;
+  const float* Pb = a.Pbar + ld.p_off;
+  const int c = tl.aux * (kWave * VEC) + lane * VEC;
+  if (c >= cols) return;
+  const int per = (tl.nrows + 3) >> 2;
+  const int ra = min(tl.row0 + wave * per, tl.row0 + tl.nrows);
+  const int rb = min(ra + per, tl.row0 + tl.nrows);
+  float q[NV];
+  load_slice<RP, VEC, EXACT>(a.Qbar + ld.q_off, c, r, q);
+  if (ghat)
+    residual_rows<RP, VEC, EXACT, true>(M, Pb, ghat, cols, r, ra, rb, (unsigned)c * 4u, q);
   else
-    residual_tile<RP, 1>(a, ld, tl, worker, ghat, wave, lane);
+    residual_rows<RP, VEC, EXACT, false>(M, Pb, nullptr, cols, r, ra, rb, (unsigned)c * 4u, q);
 }
 
 // ---------------------------------------------------------------------------
-// 1-D tensors: plain mean over the workers (Eq. (1)).
+// 1-D tensors: plain mean over the workers (Eq. (1)).  Runs as extra
+// workgroups at the end of the residual sweep's grid.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void vector_mean_kernel(DevArgs a, const VTile* __restrict__ tiles) {
-  const VTile tl = tiles[blockIdx.x];
+__device__ __forceinline__ void vector_mean_tile(const DevArgs& a, const VTile& tl) {
   const VecDesc& vd = a.vecs[tl.vec];
   float* extra = a.ghat ? a.ghat[vd.gidx] : nullptr;
   const float wf = (float)a.W;
@@ -671,6 +890,30 @@ __global__ __launch_bounds__(256) void vector_mean_kernel(DevArgs a, const VTile
       a.vmean[vd.off + e] = s;
       if (extra) extra[e] = s;
     }
+  }
+}
+
+template <int RP>
+__global__ __launch_bounds__(256) void residual_kernel(DevArgs a, const Tile* __restrict__ tiles, int ntiles,
+                                                       const VTile* __restrict__ vtiles, int write_ghat, int reverse) {
+  if ((int)blockIdx.x >= ntiles) {
+    vector_mean_tile(a, vtiles[blockIdx.x - ntiles]);
+    return;
+  }
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int lane = threadIdx.x & (kWave - 1);
+  const Tile tl = tiles[reverse ? ntiles - 1 - blockIdx.x : blockIdx.x];
+  const int layer = tl.lw / a.W, worker = tl.lw - layer * a.W;
+  const LayerDesc& ld = a.layers[layer];
+  float* ghat = nullptr;
+  if (write_ghat && worker == 0 && a.ghat) ghat = a.ghat[ld.gidx];
+  if (ld.vec == 4) {
+    if (ld.r == RP)
+      residual_tile<RP, 4, true>(a, ld, tl, worker, ghat, wave, lane);
+    else
+      residual_tile<RP, 4, false>(a, ld, tl, worker, ghat, wave, lane);
+  } else {
+    residual_tile<RP, 1, false>(a, ld, tl, worker, ghat, wave, lane);
   }
 }
 
@@ -690,17 +933,38 @@ __global__ __launch_bounds__(256) void vector_mean_kernel(DevArgs a, const VTile
     default: return hipErrorInvalidValue;     \
   }
 
-hipError_t launch_add_project(int rp, const DevArgs& a, const Tile* tiles, int ntiles, hipStream_t s) {
+hipError_t launch_add_project(int rp, const DevArgs& a, const Tile* tiles, int ntiles, int reverse, hipStream_t s) {
   if (ntiles <= 0) return hipSuccess;
   const dim3 grid((ntiles + 3) / 4), block(256);
-  LQSGD_RP_SWITCH(rp, (add_project_kernel<RP><<<grid, block, 0, s>>>(a, tiles, ntiles)));
+  LQSGD_RP_SWITCH(rp, (add_project_kernel<RP><<<grid, block, 0, s>>>(a, tiles, ntiles, reverse)));
   return hipGetLastError();
 }
 
-hipError_t launch_orth(int rp, const DevArgs& a, hipStream_t s) {
+// Register-resident Gram-Schmidt where rows-per-lane x rank fits the register
+// file comfortably; the in-memory kernel otherwise.
+template <int RP, int RPT, int BS>
+void launch_orth_reg(const DevArgs& a, dim3 grid, hipStream_t s) {
+  if constexpr (RP * RPT <= (BS == 256 ? 64 : 48)) {
+    orth_reg_kernel<RP, RPT, BS><<<grid, dim3(BS), 0, s>>>(a);
+  } else {
+    orth_kernel<RP><<<grid, dim3(256), 0, s>>>(a);
+  }
+}
+
+hipError_t launch_orth(int rp, int max_rows, const DevArgs& a, hipStream_t s) {
   if (a.L <= 0) return hipSuccess;
-  const dim3 grid(a.L * a.W), block(256);
-  LQSGD_RP_SWITCH(rp, (orth_kernel<RP><<<grid, block, 0, s>>>(a)));
+  const dim3 grid(a.L * a.W);
+  if (max_rows <= 512) {
+    LQSGD_RP_SWITCH(rp, (launch_orth_reg<RP, 2, 256>(a, grid, s)));
+  } else if (max_rows <= 2048) {
+    LQSGD_RP_SWITCH(rp, (launch_orth_reg<RP, 8, 256>(a, grid, s)));
+  } else if (max_rows <= 4096) {
+    LQSGD_RP_SWITCH(rp, (launch_orth_reg<RP, 4, 1024>(a, grid, s)));
+  } else if (max_rows <= 11264) {
+    LQSGD_RP_SWITCH(rp, (launch_orth_reg<RP, 11, 1024>(a, grid, s)));
+  } else {
+    LQSGD_RP_SWITCH(rp, (orth_kernel<RP><<<grid, dim3(256), 0, s>>>(a)));
+  }
   return hipGetLastError();
 }
 
@@ -716,10 +980,10 @@ hipError_t launch_exchange(int mode, int phase, const DevArgs& a, const XTile* t
   return hipGetLastError();
 }
 
-hipError_t launch_back_project(int rp, const DevArgs& a, const Tile* tiles, int ntiles, hipStream_t s) {
+hipError_t launch_back_project(int rp, const DevArgs& a, const Tile* tiles, int ntiles, int reverse, hipStream_t s) {
   if (ntiles <= 0) return hipSuccess;
   const dim3 grid(ntiles), block(256);
-  LQSGD_RP_SWITCH(rp, (back_project_kernel<RP><<<grid, block, 0, s>>>(a, tiles)));
+  LQSGD_RP_SWITCH(rp, (back_project_kernel<RP><<<grid, block, 0, s>>>(a, tiles, reverse)));
   return hipGetLastError();
 }
 
@@ -729,16 +993,11 @@ hipError_t launch_reduce_q(const DevArgs& a, const RTile* tiles, int ntiles, hip
   return hipGetLastError();
 }
 
-hipError_t launch_residual(int rp, const DevArgs& a, const Tile* tiles, int ntiles, int write_ghat, hipStream_t s) {
-  if (ntiles <= 0) return hipSuccess;
-  const dim3 grid(ntiles), block(256);
-  LQSGD_RP_SWITCH(rp, (residual_kernel<RP><<<grid, block, 0, s>>>(a, tiles, write_ghat)));
-  return hipGetLastError();
-}
-
-hipError_t launch_vector_mean(const DevArgs& a, const VTile* tiles, int ntiles, hipStream_t s) {
-  if (ntiles <= 0) return hipSuccess;
-  vector_mean_kernel<<<dim3(ntiles), dim3(256), 0, s>>>(a, tiles);
+hipError_t launch_residual(int rp, const DevArgs& a, const Tile* tiles, int ntiles, const VTile* vtiles,
+                           int nvtiles, int write_ghat, int reverse, hipStream_t s) {
+  if (ntiles + nvtiles <= 0) return hipSuccess;
+  const dim3 grid(ntiles + nvtiles), block(256);
+  LQSGD_RP_SWITCH(rp, (residual_kernel<RP><<<grid, block, 0, s>>>(a, tiles, ntiles, vtiles, write_ghat, reverse)));
   return hipGetLastError();
 }
 

@@ -64,6 +64,7 @@ int Plan::build(const lqsgd_config* c, const lqsgd_layer* ls, int32_t n_layers) 
   tilesA.clear(); tilesB.clear(); tilesXP.clear(); tilesXQ.clear(); tilesRQ.clear(); tilesV.clear();
 
   int max_r = 1;
+  max_rows = 0;
   matrix_elements = 0;
   for (int i = 0; i < n_layers; ++i) {
     const lqsgd_layer& l = ls[i];
@@ -105,6 +106,7 @@ int Plan::build(const lqsgd_config* c, const lqsgd_layer* ls, int32_t n_layers) 
       d.np_pad = (int32_t)round_up(d.np_el, 16);
       d.nq_pad = (int32_t)round_up(d.nq_el, 16);
       max_r = std::max(max_r, d.r);
+      max_rows = std::max(max_rows, d.rows);
       matrix_elements += (int64_t)d.rows * d.cols;
       kind_of.push_back((int32_t)layers.size());
       layers.push_back(d);
@@ -166,8 +168,8 @@ int Plan::build(const lqsgd_config* c, const lqsgd_layer* ls, int32_t n_layers) 
           tilesB.push_back(Tile{lw, rb * d.rbb, std::min(d.rbb, d.rows - rb * d.rbb), ch});
       for (int32_t e = 0; e < d.nq_el; e += 1024) tilesRQ.push_back(RTile{lw, e});
     }
-    for (int32_t g = 0; g < gp; g += 256) tilesXP.push_back(XTile{li, g});
-    for (int32_t g = 0; g < gq; g += 256) tilesXQ.push_back(XTile{li, g});
+    for (int32_t g = 0; g < gp; g += kXBlockGroups) tilesXP.push_back(XTile{li, g});
+    for (int32_t g = 0; g < gq; g += kXBlockGroups) tilesXQ.push_back(XTile{li, g});
   }
   m_stride = round_up(m_acc, 64);
   p_stride = round_up(p_acc, 64);

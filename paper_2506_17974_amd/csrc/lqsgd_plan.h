@@ -14,6 +14,7 @@ namespace lqsgd {
 constexpr int kWave = 64;
 constexpr int kRowsPerGroup = 8;   // rows a wavefront carries through one column pass of sweep 0
 constexpr int kXGroup = 8;         // elements one lane quantises / packs (b bytes + 1 sign byte)
+constexpr int kXBlockGroups = 32;  // groups of 8 elements one exchange workgroup covers
 
 // One matrix layer as the kernels see it.  Offsets are in elements (floats)
 // from the start of a per-worker slab unless they say bytes.
@@ -45,7 +46,7 @@ struct VecDesc {
 struct Tile {
   int32_t lw, row0, nrows, aux;
 };
-struct XTile {   // exchange kernels: 256 lanes x 8 elements starting at group grp0 of `layer`
+struct XTile {   // exchange kernels: kXBlockGroups groups of 8 elements starting at group grp0 of `layer`
   int32_t layer, grp0;
 };
 struct RTile {   // reduce_q: 1024 elements of (layer, worker) starting at el0
@@ -60,6 +61,7 @@ struct Plan {
   int32_t n_all = 0;            // tensors in the caller's list
   int32_t W = 0, L = 0, V = 0;  // workers, matrix layers, vector layers
   int32_t RP = 0;               // register rank: smallest of 1,2,4,8,16,32 >= max layer rank
+  int32_t max_rows = 0;         // largest row count of a matrix layer
   std::vector<LayerDesc> layers;
   std::vector<VecDesc> vecs;
   std::vector<int32_t> kind_of;    // per caller index: >= 0 matrix index, < 0 -(vector index) - 1
