@@ -63,6 +63,13 @@ typedef struct {
 
 /* Config flags. */
 #define LQSGD_FLAG_NONE 0u
+/* By default the residual update E = G' - G-hat (Eq. (8)) that ends an
+ * iteration is deferred: the context keeps G' and the two aggregated factors,
+ * and the next iteration's first sweep forms E on the fly while it adds the new
+ * gradient (one pass over the data fewer; bit-identical results).
+ * lqsgd_get_state / lqsgd_set_state apply a deferred update first, so callers
+ * always see E.  With this flag the update runs at the end of every iteration. */
+#define LQSGD_FLAG_EAGER_RESIDUAL 1u
 
 /* The "Require" line of Algorithm 1, plus the number of simulated workers. */
 typedef struct {
@@ -217,13 +224,13 @@ int64_t lqsgd_plan_tiles(const lqsgd_config* cfg, const lqsgd_layer* layers, int
 
 /* ---- per-kernel timing with HIP events on the context's stream ---------- */
 
-#define LQSGD_KERNEL_ADD_PROJECT 0   /* M = G + E, P partials             */
+#define LQSGD_KERNEL_ADD_PROJECT 0   /* M = G + E (+ deferred residual), P partials */
 #define LQSGD_KERNEL_ORTH 1          /* reduce partials, Gram-Schmidt, absmax */
 #define LQSGD_KERNEL_EXCHANGE_P 2    /* quantise / dequantise / mean of P */
-#define LQSGD_KERNEL_BACK_PROJECT 3  /* Q partials = M^T P-bar            */
+#define LQSGD_KERNEL_BACK_PROJECT 3  /* Q partials = M^T P-bar, and the mean of the VECTOR layers */
 #define LQSGD_KERNEL_REDUCE_Q 4      /* reduce partials, absmax           */
 #define LQSGD_KERNEL_EXCHANGE_Q 5    /* quantise / dequantise / mean of Q */
-#define LQSGD_KERNEL_RESIDUAL 6      /* E = M - P-bar Q-bar^T (+ G-hat), and the mean of the VECTOR layers */
+#define LQSGD_KERNEL_RESIDUAL 6      /* E = M - P-bar Q-bar^T and / or G-hat */
 #define LQSGD_KERNEL_COUNT 7
 
 /* on != 0: every kernel launched from now on is bracketed by a pair of HIP

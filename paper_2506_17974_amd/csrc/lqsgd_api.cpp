@@ -38,11 +38,13 @@ struct lqsgd_ctx {
   State state = kIdle;
   int sweep_dir = 0;        // direction of the next streaming sweep (alternates)
   bool flip = true;
+  bool eager = false;       // LQSGD_FLAG_EAGER_RESIDUAL
+  bool pending = false;     // E buffer holds M; E = M - P-bar Q-bar^T not applied yet
   std::string err;
   std::vector<void*> allocs;
   DevArgs args{};
   // device copies of the work lists
-  Tile* d_tilesA = nullptr; Tile* d_tilesB = nullptr;
+  Tile* d_tilesA = nullptr; Tile* d_tilesB = nullptr; Tile* d_tilesG = nullptr;
   XTile* d_tilesXP = nullptr; XTile* d_tilesXQ = nullptr;
   RTile* d_tilesRQ = nullptr; VTile* d_tilesV = nullptr;
   // pointer tables
@@ -172,7 +174,9 @@ int next_dir(lqsgd_ctx* c) {
 
 int run_sweep0(lqsgd_ctx* c) {
   { Timed t(c, LQSGD_KERNEL_ADD_PROJECT);
-    HIP_TRY(c, launch_add_project(c->plan.RP, c->args, c->d_tilesA, (int)c->plan.tilesA.size(), next_dir(c), c->stream)); }
+    HIP_TRY(c, launch_add_project(c->plan.RP, c->args, c->d_tilesA, (int)c->plan.tilesA.size(), c->pending ? 1 : 0,
+                                  next_dir(c), c->stream)); }
+  c->pending = false;
   { Timed t(c, LQSGD_KERNEL_ORTH);
     HIP_TRY(c, launch_orth(c->plan.RP, c->plan.max_rows, c->args, c->stream)); }
   return LQSGD_OK;
@@ -183,17 +187,35 @@ int run_exchange(lqsgd_ctx* c, int mode, int phase) {
   HIP_TRY(c, launch_exchange(mode, phase, c->args, phase ? c->d_tilesXQ : c->d_tilesXP, (int)tl.size(), c->stream));
   return LQSGD_OK;
 }
-int run_sweep1(lqsgd_ctx* c) {
+int run_sweep1(lqsgd_ctx* c, bool with_vectors) {
   { Timed t(c, LQSGD_KERNEL_BACK_PROJECT);
-    HIP_TRY(c, launch_back_project(c->plan.RP, c->args, c->d_tilesB, (int)c->plan.tilesB.size(), next_dir(c), c->stream)); }
+    HIP_TRY(c, launch_back_project(c->plan.RP, c->args, c->d_tilesB, (int)c->plan.tilesB.size(), c->d_tilesV,
+                                   with_vectors ? (int)c->plan.tilesV.size() : 0, next_dir(c), c->stream)); }
   { Timed t(c, LQSGD_KERNEL_REDUCE_Q);
     HIP_TRY(c, launch_reduce_q(c->args, c->d_tilesRQ, (int)c->plan.tilesRQ.size(), c->stream)); }
   return LQSGD_OK;
 }
-int run_sweep2(lqsgd_ctx* c, int write_ghat, bool with_vectors) {
+// End of an iteration: either apply E = M - P-bar Q-bar^T now (eager), or leave M
+// in place and let the next iteration's first sweep apply it on the fly; G-hat,
+// when asked for, is then written by a pass of its own over the layers.
+int run_sweep2(lqsgd_ctx* c, bool write_ghat) {
   Timed t(c, LQSGD_KERNEL_RESIDUAL);
-  HIP_TRY(c, launch_residual(c->plan.RP, c->args, c->d_tilesB, (int)c->plan.tilesB.size(), c->d_tilesV,
-                             with_vectors ? (int)c->plan.tilesV.size() : 0, write_ghat, next_dir(c), c->stream));
+  if (c->eager) {
+    HIP_TRY(c, launch_residual(c->plan.RP, write_ghat ? 1 : 0, c->args, c->d_tilesB, (int)c->plan.tilesB.size(),
+                               next_dir(c), c->stream));
+  } else {
+    if (write_ghat)
+      HIP_TRY(c, launch_residual(c->plan.RP, 2, c->args, c->d_tilesG, (int)c->plan.tilesG.size(), 0, c->stream));
+    c->pending = true;
+  }
+  return LQSGD_OK;
+}
+// Applies a deferred residual update, so that the buffer holds E again.
+int materialise(lqsgd_ctx* c) {
+  if (!c->pending) return LQSGD_OK;
+  Timed t(c, LQSGD_KERNEL_RESIDUAL);
+  HIP_TRY(c, launch_residual(c->plan.RP, 0, c->args, c->d_tilesB, (int)c->plan.tilesB.size(), next_dir(c), c->stream));
+  c->pending = false;
   return LQSGD_OK;
 }
 
@@ -295,6 +317,8 @@ int lqsgd_create(const lqsgd_config* cfg, const lqsgd_layer* layers, int32_t n_l
   }
   c->stream = static_cast<hipStream_t>(hip_stream);
   if (const char* f = std::getenv("LQSGD_FLIP")) c->flip = (f[0] != '0');
+  c->eager = (cfg->flags & LQSGD_FLAG_EAGER_RESIDUAL) != 0;
+  if (const char* f = std::getenv("LQSGD_EAGER")) c->eager = (f[0] != '0');
   auto bail = [&](int code) {
     g_create_error = c->err;
     for (void* p : c->allocs) (void)hipFree(p);
@@ -343,6 +367,7 @@ int lqsgd_create(const lqsgd_config* cfg, const lqsgd_layer* layers, int32_t n_l
   TRY_(dev_upload(c, &thrQ, tQ)); TRY_(dev_upload(c, &levQ, lQ));
   TRY_(dev_upload(c, &c->d_tilesA, p.tilesA));
   TRY_(dev_upload(c, &c->d_tilesB, p.tilesB));
+  TRY_(dev_upload(c, &c->d_tilesG, p.tilesG));
   TRY_(dev_upload(c, &c->d_tilesXP, p.tilesXP));
   TRY_(dev_upload(c, &c->d_tilesXQ, p.tilesXQ));
   TRY_(dev_upload(c, &c->d_tilesRQ, p.tilesRQ));
@@ -391,6 +416,7 @@ int lqsgd_get_state(lqsgd_ctx* c, int32_t layer, int32_t worker, float* host_e, 
   int rc = check_matrix_layer(c, layer, &ld);
   if (rc) return rc;
   if ((rc = check_worker(c, worker))) return rc;
+  if (host_e && (rc = materialise(c))) return rc;
   HIP_TRY(c, hipStreamSynchronize(c->stream));
   if (host_e)
     HIP_TRY(c, hipMemcpy(host_e, c->args.E + (size_t)worker * c->args.m_stride + ld->m_off,
@@ -406,6 +432,7 @@ int lqsgd_set_state(lqsgd_ctx* c, int32_t layer, int32_t worker, const float* ho
   int rc = check_matrix_layer(c, layer, &ld);
   if (rc) return rc;
   if ((rc = check_worker(c, worker))) return rc;
+  if ((rc = materialise(c))) return rc;      // a deferred update depends on the old E buffer and the old Q
   HIP_TRY(c, hipStreamSynchronize(c->stream));
   if (host_e)
     HIP_TRY(c, hipMemcpy(c->args.E + (size_t)worker * c->args.m_stride + ld->m_off, host_e,
@@ -429,7 +456,7 @@ int lqsgd_compress(lqsgd_ctx* c, int32_t phase, const float* const* grads) {
   }
   if (phase == LQSGD_PHASE_Q) {
     if (c->state != kPDone) return fail(c, LQSGD_ESTATE, "compress(Q) must follow decompress(P)");
-    if ((rc = run_sweep1(c))) return rc;
+    if ((rc = run_sweep1(c, false))) return rc;
     if ((rc = run_exchange(c, kQuantOnly, 1))) return rc;
     c->state = kQCompressed;
     return LQSGD_OK;
@@ -450,7 +477,7 @@ int lqsgd_decompress(lqsgd_ctx* c, int32_t phase) {
     if (c->state != kQCompressed) return fail(c, LQSGD_ESTATE, "decompress(Q) must follow compress(Q)");
     if ((rc = run_exchange(c, kMeanOnly, 1))) return rc;
     c->args.ghat = nullptr;
-    if ((rc = run_sweep2(c, 0, false))) return rc;
+    if ((rc = run_sweep2(c, false))) return rc;
     c->state = kIdle;
     return LQSGD_OK;
   }
@@ -473,9 +500,9 @@ int lqsgd_step(lqsgd_ctx* c, const float* const* grads, float* const* ghat) {
   }
   if ((rc = run_sweep0(c))) return rc;
   if ((rc = run_exchange(c, kFused, 0))) return rc;
-  if ((rc = run_sweep1(c))) return rc;
+  if ((rc = run_sweep1(c, true))) return rc;
   if ((rc = run_exchange(c, kFused, 1))) return rc;
-  if ((rc = run_sweep2(c, ghat != nullptr, true))) return rc;
+  if ((rc = run_sweep2(c, ghat != nullptr))) return rc;
   return LQSGD_OK;
 }
 
@@ -589,6 +616,7 @@ int lqsgd_set_factor(lqsgd_ctx* c, int32_t which, int32_t layer, const float* ho
   if (which == LQSGD_FACTOR_P_BAR) { dst = c->args.Pbar + ld->p_off; n = ld->np_el; }
   else if (which == LQSGD_FACTOR_Q_BAR) { dst = c->args.Qbar + ld->q_off; n = ld->nq_el; }
   else return fail(c, LQSGD_EINVAL, "only P-bar and Q-bar can be set");
+  if ((rc = materialise(c))) return rc;      // a deferred update is defined by the old factors
   HIP_TRY(c, hipStreamSynchronize(c->stream));
   HIP_TRY(c, hipMemcpy(dst, host, n * sizeof(float), hipMemcpyHostToDevice));
   return LQSGD_OK;

@@ -39,13 +39,17 @@ enum ExchangeMode { kQuantOnly = 0, kMeanOnly = 1, kFused = 2 };
 // Each launcher enqueues one kernel on `s` and returns hipGetLastError().
 // `reverse` walks the work list backwards: consecutive sweeps alternate direction so that
 // each one starts on the data the previous one touched last (still in the memory-side cache).
-hipError_t launch_add_project(int RP, const DevArgs& a, const Tile* tiles, int ntiles, int reverse, hipStream_t s);
+// fuse_residual: the buffer E holds last iteration's M and the residual update
+// E = M - P-bar Q-bar^T is applied on the fly (see add_project_kernel).
+hipError_t launch_add_project(int RP, const DevArgs& a, const Tile* tiles, int ntiles, int fuse_residual, int reverse,
+                              hipStream_t s);
 hipError_t launch_orth(int RP, int max_rows, const DevArgs& a, hipStream_t s);
 hipError_t launch_exchange(int mode, int phase, const DevArgs& a, const XTile* tiles, int ntiles, hipStream_t s);
-hipError_t launch_back_project(int RP, const DevArgs& a, const Tile* tiles, int ntiles, int reverse, hipStream_t s);
+// Sweep 1 also runs the plain mean of the 1-D tensors (nvtiles extra workgroups).
+hipError_t launch_back_project(int RP, const DevArgs& a, const Tile* tiles, int ntiles, const VTile* vtiles, int nvtiles,
+                               int reverse, hipStream_t s);
 hipError_t launch_reduce_q(const DevArgs& a, const RTile* tiles, int ntiles, hipStream_t s);
-// The residual sweep also runs the plain mean of the 1-D tensors (nvtiles extra workgroups).
-hipError_t launch_residual(int RP, const DevArgs& a, const Tile* tiles, int ntiles, const VTile* vtiles, int nvtiles,
-                           int write_ghat, int reverse, hipStream_t s);
+// mode: 0 = residual for all workers, 1 = residual + G-hat, 2 = G-hat only (tiles of worker 0).
+hipError_t launch_residual(int RP, int mode, const DevArgs& a, const Tile* tiles, int ntiles, int reverse, hipStream_t s);
 
 }  // namespace lqsgd

@@ -221,10 +221,10 @@ constexpr int log2c(int n) { return n <= 1 ? 0 : 1 + log2c(n / 2); }
 // RT rows at a time; a lane accumulates RT x r partial dot products over its
 // columns, one butterfly per row group adds them over the lanes.
 // ---------------------------------------------------------------------------
-template <int RP, int VEC, int RT, bool EXACT, bool FULL>
+template <int RP, int VEC, int RT, bool EXACT, bool FULL, bool FUSE>
 __device__ __forceinline__ void add_project_cols(const char* const (&gr)[RT], char* const (&mr)[RT],
-                                                 const float* __restrict__ Q, int r, int nr, int cbeg, int cend,
-                                                 float (&acc)[RT * RP]) {
+                                                 const float* __restrict__ Q, const float (&pb)[RT * RP], int r, int nr,
+                                                 int cbeg, int cend, float (&acc)[RT * RP]) {
   for (int c = cbeg; c < cend; c += kWave * VEC) {
     float q[VEC * RP];
     load_slice<RP, VEC, EXACT>(Q, c, r, q);
@@ -244,7 +244,18 @@ __device__ __forceinline__ void add_project_cols(const char* const (&gr)[RT], ch
     for (int t = 0; t < RT; ++t) {
       Pk<VEC> m;
 #pragma unroll
-      for (int v = 0; v < VEC; ++v) m.v[v] = g[t].v[v] + e[t].v[v];
+      for (int v = 0; v < VEC; ++v) {
+        float ev = e[t].v[v];
+        if constexpr (FUSE) {
+          // the buffer still holds last iteration's M: E = M - P-bar Q-bar^T (Eq. (8)),
+          // with the same operation order as the stand-alone residual sweep
+          float gh = 0.0f;
+#pragma unroll
+          for (int k = 0; k < RP; ++k) gh = fmaf(pb[t * RP + k], q[v * RP + k], gh);
+          ev = ev - gh;
+        }
+        m.v[v] = g[t].v[v] + ev;
+      }
       if (FULL || t < nr) strow<VEC, LQSGD_NT_ST_A != 0>(mr[t], boff, m);
 #pragma unroll
       for (int v = 0; v < VEC; ++v)
@@ -254,29 +265,40 @@ __device__ __forceinline__ void add_project_cols(const char* const (&gr)[RT], ch
   }
 }
 
-template <int RP, int VEC, int RT, bool EXACT>
+template <int RP, int VEC, int RT, bool EXACT, bool FUSE>
 __device__ __forceinline__ void add_project_tile(const float* __restrict__ G, float* __restrict__ M,
-                                                 const float* __restrict__ Q, float* __restrict__ Pp,
-                                                 int cols, int r, int row0, int nrows, int col0, int col1,
-                                                 int lane) {
+                                                 const float* __restrict__ Q, const float* Pb,
+                                                 float* __restrict__ Pp, int cols, int r, int row0, int nrows,
+                                                 int col0, int col1, int lane) {
   constexpr int N = RT * RP;
   for (int rg = 0; rg < nrows; rg += RT) {
     const int nr = min(RT, nrows - rg);
     float acc[N];
+    float pb[N];
 #pragma unroll
     for (int i = 0; i < N; ++i) acc[i] = 0.0f;
     const char* gr[RT];
     char* mr[RT];
 #pragma unroll
     for (int t = 0; t < RT; ++t) {
-      const size_t off = (size_t)(row0 + rg + min(t, nr - 1)) * cols;
+      const int row = row0 + rg + min(t, nr - 1);
+      const size_t off = (size_t)row * cols;
       gr[t] = reinterpret_cast<const char*>(G + off);
       mr[t] = reinterpret_cast<char*>(M + off);
+      if constexpr (FUSE) {
+        float p[RP];
+        load_row_uniform<RP, EXACT>(Pb, row, r, p);
+#pragma unroll
+        for (int k = 0; k < RP; ++k) pb[t * RP + k] = p[k];
+      } else {
+#pragma unroll
+        for (int k = 0; k < RP; ++k) pb[t * RP + k] = 0.0f;
+      }
     }
     if (nr == RT)
-      add_project_cols<RP, VEC, RT, EXACT, true>(gr, mr, Q, r, nr, col0 + lane * VEC, col1, acc);
+      add_project_cols<RP, VEC, RT, EXACT, true, FUSE>(gr, mr, Q, pb, r, nr, col0 + lane * VEC, col1, acc);
     else
-      add_project_cols<RP, VEC, RT, EXACT, false>(gr, mr, Q, r, nr, col0 + lane * VEC, col1, acc);
+      add_project_cols<RP, VEC, RT, EXACT, false, FUSE>(gr, mr, Q, pb, r, nr, col0 + lane * VEC, col1, acc);
     transpose_reduce<N, N, 32>(acc, lane);
     constexpr int NPL = (N >= kWave) ? N / kWave : 1;
 #pragma unroll
@@ -296,7 +318,10 @@ __device__ __forceinline__ void add_project_tile(const float* __restrict__ G, fl
   }
 }
 
-template <int RP>
+// FUSE: the residual update of the previous iteration has been deferred; the
+// buffer holds M_{t-1} and this sweep forms E_{t-1} = M_{t-1} - P-bar Q-bar^T on
+// the fly (Q-bar is the warm-start Q this sweep multiplies by anyway).
+template <int RP, bool FUSE>
 __global__ __launch_bounds__(256, LQSGD_A_WAVES) void add_project_kernel(DevArgs a, const Tile* __restrict__ tiles, int ntiles, int reverse) {
   constexpr int RT = (RP <= 8) ? LQSGD_RT : 4;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -309,17 +334,18 @@ __global__ __launch_bounds__(256, LQSGD_A_WAVES) void add_project_kernel(DevArgs
   const float* G = a.grads[(size_t)worker * a.n_all + ld.gidx];
   float* M = a.E + (size_t)worker * a.m_stride + ld.m_off;
   const float* Q = a.Qbar + ld.q_off;
+  const float* Pb = a.Pbar + ld.p_off;
   float* Pp = a.Ppart + (size_t)worker * a.ppart_stride + ld.ppart_off + (size_t)tl.aux * ld.np_pad;
   const int col0 = tl.aux * ld.segw;
   const int col1 = min(ld.cols, col0 + ld.segw);
   if (ld.vec == 4) {
     if (ld.r == RP)
-      add_project_tile<RP, 4, RT, true>(G, M, Q, Pp, ld.cols, ld.r, tl.row0, tl.nrows, col0, col1, lane);
+      add_project_tile<RP, 4, RT, true, FUSE>(G, M, Q, Pb, Pp, ld.cols, ld.r, tl.row0, tl.nrows, col0, col1, lane);
     else
-      add_project_tile<RP, 4, RT, false>(G, M, Q, Pp, ld.cols, ld.r, tl.row0, tl.nrows, col0, col1, lane);
+      add_project_tile<RP, 4, RT, false, FUSE>(G, M, Q, Pb, Pp, ld.cols, ld.r, tl.row0, tl.nrows, col0, col1, lane);
   } else {
     // rows that are not 16-byte aligned (cols % 4 != 0): tiny layers, one generic path
-    add_project_tile<RP, 1, RT, false>(G, M, Q, Pp, ld.cols, ld.r, tl.row0, tl.nrows, col0, col1, lane);
+    add_project_tile<RP, 1, RT, false, FUSE>(G, M, Q, Pb, Pp, ld.cols, ld.r, tl.row0, tl.nrows, col0, col1, lane);
   }
 }
 
@@ -740,16 +766,41 @@ __device__ __forceinline__ void back_project_tile(const DevArgs& a, const LayerD
   }
 }
 
+// ---------------------------------------------------------------------------
+// 1-D tensors: plain mean over the workers (Eq. (1)).  Runs as extra
+// workgroups at the end of sweep 1's grid.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ void vector_mean_tile(const DevArgs& a, const VTile& tl) {
+  const VecDesc& vd = a.vecs[tl.vec];
+  float* extra = a.ghat ? a.ghat[vd.gidx] : nullptr;
+  const float wf = (float)a.W;
+  for (int i = 0; i < 4; ++i) {
+    const int e = tl.el0 + i * 256 + threadIdx.x;
+    if (e < vd.len) {
+      float s = 0.0f;
+      for (int w = 0; w < a.W; ++w) s += a.grads[(size_t)w * a.n_all + vd.gidx][e];
+      s /= wf;
+      a.vmean[vd.off + e] = s;
+      if (extra) extra[e] = s;
+    }
+  }
+}
+
 template <int RP>
-__global__ __launch_bounds__(256) void back_project_kernel(DevArgs a, const Tile* __restrict__ tiles, int reverse) {
+__global__ __launch_bounds__(256) void back_project_kernel(DevArgs a, const Tile* __restrict__ tiles, int ntiles,
+                                                           const VTile* __restrict__ vtiles, int reverse) {
   // fast path: 4 planes of 64 * 4 * RP floats (RP <= 16); generic path: 2 planes
   __shared__ float comb[(RP <= 16 ? 4 : 2) * kWave * 4 * RP];
+  if ((int)blockIdx.x >= ntiles) {
+    vector_mean_tile(a, vtiles[blockIdx.x - ntiles]);
+    return;
+  }
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int lane = threadIdx.x & (kWave - 1);
   if (blockIdx.x == 0) {   // absmax accumulators of reduce_q start from zero
     for (int i = threadIdx.x; i < a.W * a.L; i += 256) a.scaleQ[i] = 0.0f;
   }
-  const Tile tl = tiles[reverse ? gridDim.x - 1 - blockIdx.x : blockIdx.x];
+  const Tile tl = tiles[reverse ? ntiles - 1 - blockIdx.x : blockIdx.x];
   const int layer = tl.lw / a.W, worker = tl.lw - layer * a.W;
   const LayerDesc& ld = a.layers[layer];
   if (ld.vec == 4) {
@@ -803,57 +854,59 @@ __global__ __launch_bounds__(256) void reduce_q_kernel(DevArgs a, const RTile* _
 }
 
 // ---------------------------------------------------------------------------
-// sweep 2: E_w = M_w - P-bar Q-bar^T (Eq. (7), (8)); worker 0's items also
-// write G-hat when the caller asked for it.  Same work items as sweep 1, the
-// four wavefronts of a workgroup split the rows.
+// sweep 2: E_w = M_w - P-bar Q-bar^T (Eq. (7), (8)) and / or G-hat = P-bar Q-bar^T.
+//   kResidual      E for every worker                          (8 B / element)
+//   kResidualGhat  E for every worker, G-hat from worker 0's items
+//   kGhatOnly      G-hat only, one item list per layer (4 B / element / W);
+//                  used when the residual update is deferred into the next
+//                  iteration's sweep 0
+// The four wavefronts of a workgroup split the rows of the item.
 // ---------------------------------------------------------------------------
-template <int RP, int VEC, bool EXACT, bool GHAT>
+enum ResidualMode { kResidual = 0, kResidualGhat = 1, kGhatOnly = 2 };
+
+template <int RP, int VEC, bool EXACT, int MODE>
 __device__ __forceinline__ void residual_rows(float* __restrict__ M, const float* Pb, float* __restrict__ ghat,
                                               int cols, int r, int ra, int rb, unsigned boff,
                                               const float (&q)[VEC * RP]) {
   constexpr int U = 8;
-  int i = ra;
-  for (; i + U <= rb; i += U) {
+  for (int i = ra; i < rb; i += U) {
+    const int nu = min(U, rb - i);
     Pk<VEC> m[U];
+    if constexpr (MODE != kGhatOnly) {
 #pragma unroll
-    for (int u = 0; u < U; ++u)
-      m[u] = ldrow<VEC, LQSGD_NT_M != 0>(reinterpret_cast<const char*>(M + (size_t)(i + u) * cols), boff);
+      for (int u = 0; u < U; ++u) {
+        if (u < nu) {
+          m[u] = ldrow<VEC, LQSGD_NT_M != 0>(reinterpret_cast<const char*>(M + (size_t)(i + u) * cols), boff);
+        } else {
+#pragma unroll
+          for (int v = 0; v < VEC; ++v) m[u].v[v] = 0.0f;
+        }
+      }
+    }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      float p[RP];
-      load_row_uniform<RP, EXACT>(Pb, i + u, r, p);
-      Pk<VEC> gh, e;
+      if (u < nu) {
+        float p[RP];
+        load_row_uniform<RP, EXACT>(Pb, i + u, r, p);
+        Pk<VEC> gh, e;
 #pragma unroll
-      for (int v = 0; v < VEC; ++v) {
-        float s = 0.0f;
+        for (int v = 0; v < VEC; ++v) {
+          float s = 0.0f;
 #pragma unroll
-        for (int k = 0; k < RP; ++k) s = fmaf(p[k], q[v * RP + k], s);
-        gh.v[v] = s;
-        e.v[v] = m[u].v[v] - s;
+          for (int k = 0; k < RP; ++k) s = fmaf(p[k], q[v * RP + k], s);
+          gh.v[v] = s;
+          if constexpr (MODE != kGhatOnly) e.v[v] = m[u].v[v] - s;
+        }
+        if constexpr (MODE != kGhatOnly)
+          strow<VEC, LQSGD_NT_ST_C != 0>(reinterpret_cast<char*>(M + (size_t)(i + u) * cols), boff, e);
+        if (MODE == kGhatOnly || (MODE == kResidualGhat && ghat))
+          strow<VEC, true>(reinterpret_cast<char*>(ghat + (size_t)(i + u) * cols), boff, gh);
       }
-      strow<VEC, LQSGD_NT_ST_C != 0>(reinterpret_cast<char*>(M + (size_t)(i + u) * cols), boff, e);
-      if (GHAT) strow<VEC, true>(reinterpret_cast<char*>(ghat + (size_t)(i + u) * cols), boff, gh);
     }
-  }
-  for (; i < rb; ++i) {
-    const Pk<VEC> m = ldrow<VEC, LQSGD_NT_M != 0>(reinterpret_cast<const char*>(M + (size_t)i * cols), boff);
-    float p[RP];
-    load_row_uniform<RP, EXACT>(Pb, i, r, p);
-    Pk<VEC> gh, e;
-#pragma unroll
-    for (int v = 0; v < VEC; ++v) {
-      float s = 0.0f;
-#pragma unroll
-      for (int k = 0; k < RP; ++k) s = fmaf(p[k], q[v * RP + k], s);
-      gh.v[v] = s;
-      e.v[v] = m.v[v] - s;
-    }
-    strow<VEC, LQSGD_NT_ST_C != 0>(reinterpret_cast<char*>(M + (size_t)i * cols), boff, e);
-    if (GHAT) strow<VEC, true>(reinterpret_cast<char*>(ghat + (size_t)i * cols), boff, gh);
   }
 }
 
-template <int RP, int VEC, bool EXACT>
+template <int RP, int VEC, bool EXACT, int MODE>
 __device__ __forceinline__ void residual_tile(const DevArgs& a, const LayerDesc& ld, const Tile& tl, int worker,
                                               float* __restrict__ ghat, int wave, int lane) {
   constexpr int NV = VEC * RP;
@@ -867,53 +920,26 @@ __device__ __forceinline__ void residual_tile(const DevArgs& a, const LayerDesc&
   const int rb = min(ra + per, tl.row0 + tl.nrows);
   float q[NV];
   load_slice<RP, VEC, EXACT>(a.Qbar + ld.q_off, c, r, q);
-  if (ghat)
-    residual_rows<RP, VEC, EXACT, true>(M, Pb, ghat, cols, r, ra, rb, (unsigned)c * 4u, q);
-  else
-    residual_rows<RP, VEC, EXACT, false>(M, Pb, nullptr, cols, r, ra, rb, (unsigned)c * 4u, q);
+  residual_rows<RP, VEC, EXACT, MODE>(M, Pb, ghat, cols, r, ra, rb, (unsigned)c * 4u, q);
 }
 
-// ---------------------------------------------------------------------------
-// 1-D tensors: plain mean over the workers (Eq. (1)).  Runs as extra
-// workgroups at the end of the residual sweep's grid.
-// ---------------------------------------------------------------------------
-__device__ __forceinline__ void vector_mean_tile(const DevArgs& a, const VTile& tl) {
-  const VecDesc& vd = a.vecs[tl.vec];
-  float* extra = a.ghat ? a.ghat[vd.gidx] : nullptr;
-  const float wf = (float)a.W;
-  for (int i = 0; i < 4; ++i) {
-    const int e = tl.el0 + i * 256 + threadIdx.x;
-    if (e < vd.len) {
-      float s = 0.0f;
-      for (int w = 0; w < a.W; ++w) s += a.grads[(size_t)w * a.n_all + vd.gidx][e];
-      s /= wf;
-      a.vmean[vd.off + e] = s;
-      if (extra) extra[e] = s;
-    }
-  }
-}
-
-template <int RP>
-__global__ __launch_bounds__(256) void residual_kernel(DevArgs a, const Tile* __restrict__ tiles, int ntiles,
-                                                       const VTile* __restrict__ vtiles, int write_ghat, int reverse) {
-  if ((int)blockIdx.x >= ntiles) {
-    vector_mean_tile(a, vtiles[blockIdx.x - ntiles]);
-    return;
-  }
+template <int RP, int MODE>
+__global__ __launch_bounds__(256) void residual_kernel(DevArgs a, const Tile* __restrict__ tiles, int ntiles, int reverse) {
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int lane = threadIdx.x & (kWave - 1);
   const Tile tl = tiles[reverse ? ntiles - 1 - blockIdx.x : blockIdx.x];
   const int layer = tl.lw / a.W, worker = tl.lw - layer * a.W;
   const LayerDesc& ld = a.layers[layer];
   float* ghat = nullptr;
-  if (write_ghat && worker == 0 && a.ghat) ghat = a.ghat[ld.gidx];
+  if (MODE != kResidual && worker == 0 && a.ghat) ghat = a.ghat[ld.gidx];
+  if (MODE == kGhatOnly && !ghat) return;
   if (ld.vec == 4) {
     if (ld.r == RP)
-      residual_tile<RP, 4, true>(a, ld, tl, worker, ghat, wave, lane);
+      residual_tile<RP, 4, true, MODE>(a, ld, tl, worker, ghat, wave, lane);
     else
-      residual_tile<RP, 4, false>(a, ld, tl, worker, ghat, wave, lane);
+      residual_tile<RP, 4, false, MODE>(a, ld, tl, worker, ghat, wave, lane);
   } else {
-    residual_tile<RP, 1, false>(a, ld, tl, worker, ghat, wave, lane);
+    residual_tile<RP, 1, false, MODE>(a, ld, tl, worker, ghat, wave, lane);
   }
 }
 
@@ -933,10 +959,15 @@ __global__ __launch_bounds__(256) void residual_kernel(DevArgs a, const Tile* __
     default: return hipErrorInvalidValue;     \
   }
 
-hipError_t launch_add_project(int rp, const DevArgs& a, const Tile* tiles, int ntiles, int reverse, hipStream_t s) {
+hipError_t launch_add_project(int rp, const DevArgs& a, const Tile* tiles, int ntiles, int fuse_residual, int reverse,
+                              hipStream_t s) {
   if (ntiles <= 0) return hipSuccess;
   const dim3 grid((ntiles + 3) / 4), block(256);
-  LQSGD_RP_SWITCH(rp, (add_project_kernel<RP><<<grid, block, 0, s>>>(a, tiles, ntiles, reverse)));
+  if (fuse_residual) {
+    LQSGD_RP_SWITCH(rp, (add_project_kernel<RP, true><<<grid, block, 0, s>>>(a, tiles, ntiles, reverse)));
+  } else {
+    LQSGD_RP_SWITCH(rp, (add_project_kernel<RP, false><<<grid, block, 0, s>>>(a, tiles, ntiles, reverse)));
+  }
   return hipGetLastError();
 }
 
@@ -980,10 +1011,11 @@ hipError_t launch_exchange(int mode, int phase, const DevArgs& a, const XTile* t
   return hipGetLastError();
 }
 
-hipError_t launch_back_project(int rp, const DevArgs& a, const Tile* tiles, int ntiles, int reverse, hipStream_t s) {
-  if (ntiles <= 0) return hipSuccess;
-  const dim3 grid(ntiles), block(256);
-  LQSGD_RP_SWITCH(rp, (back_project_kernel<RP><<<grid, block, 0, s>>>(a, tiles, reverse)));
+hipError_t launch_back_project(int rp, const DevArgs& a, const Tile* tiles, int ntiles, const VTile* vtiles, int nvtiles,
+                               int reverse, hipStream_t s) {
+  if (ntiles + nvtiles <= 0) return hipSuccess;
+  const dim3 grid(ntiles + nvtiles), block(256);
+  LQSGD_RP_SWITCH(rp, (back_project_kernel<RP><<<grid, block, 0, s>>>(a, tiles, ntiles, vtiles, reverse)));
   return hipGetLastError();
 }
 
@@ -993,11 +1025,15 @@ hipError_t launch_reduce_q(const DevArgs& a, const RTile* tiles, int ntiles, hip
   return hipGetLastError();
 }
 
-hipError_t launch_residual(int rp, const DevArgs& a, const Tile* tiles, int ntiles, const VTile* vtiles,
-                           int nvtiles, int write_ghat, int reverse, hipStream_t s) {
-  if (ntiles + nvtiles <= 0) return hipSuccess;
-  const dim3 grid(ntiles + nvtiles), block(256);
-  LQSGD_RP_SWITCH(rp, (residual_kernel<RP><<<grid, block, 0, s>>>(a, tiles, ntiles, vtiles, write_ghat, reverse)));
+hipError_t launch_residual(int rp, int mode, const DevArgs& a, const Tile* tiles, int ntiles, int reverse, hipStream_t s) {
+  if (ntiles <= 0) return hipSuccess;
+  const dim3 grid(ntiles), block(256);
+  switch (mode) {
+    case kResidual: LQSGD_RP_SWITCH(rp, (residual_kernel<RP, kResidual><<<grid, block, 0, s>>>(a, tiles, ntiles, reverse))); break;
+    case kResidualGhat: LQSGD_RP_SWITCH(rp, (residual_kernel<RP, kResidualGhat><<<grid, block, 0, s>>>(a, tiles, ntiles, reverse))); break;
+    case kGhatOnly: LQSGD_RP_SWITCH(rp, (residual_kernel<RP, kGhatOnly><<<grid, block, 0, s>>>(a, tiles, ntiles, reverse))); break;
+    default: return hipErrorInvalidValue;
+  }
   return hipGetLastError();
 }
 

@@ -57,11 +57,12 @@ int Plan::build(const lqsgd_config* c, const lqsgd_layer* ls, int32_t n_layers) 
     return LQSGD_EINVAL;
   }
   if (!(c->alpha > 0.0f) || !std::isfinite(c->alpha)) { err = "alpha must be finite and > 0"; return LQSGD_EINVAL; }
+  if (c->flags & ~LQSGD_FLAG_EAGER_RESIDUAL) { err = "unknown config flags"; return LQSGD_EINVAL; }
   cfg = *c;
   W = c->workers;
   n_all = n_layers;
   layers.clear(); vecs.clear(); kind_of.clear();
-  tilesA.clear(); tilesB.clear(); tilesXP.clear(); tilesXQ.clear(); tilesRQ.clear(); tilesV.clear();
+  tilesA.clear(); tilesB.clear(); tilesG.clear(); tilesXP.clear(); tilesXQ.clear(); tilesRQ.clear(); tilesV.clear();
 
   int max_r = 1;
   max_rows = 0;
@@ -122,7 +123,7 @@ int Plan::build(const lqsgd_config* c, const lqsgd_layer* ls, int32_t n_layers) 
   // work lists stay small.
   const int64_t total = matrix_elements * W;
   const int64_t tgtA = env_i64("LQSGD_TILE_A", std::min<int64_t>(131072, std::max<int64_t>(4096, total / 49152)));
-  const int64_t tgtB = env_i64("LQSGD_TILE_B", std::min<int64_t>(524288, std::max<int64_t>(16384, total / 12288)));
+  const int64_t tgtB = env_i64("LQSGD_TILE_B", std::min<int64_t>(524288, std::max<int64_t>(8192, total / 12288)));
   const int64_t segmax4 = env_i64("LQSGD_SEGMAX", 1024);
 
   int64_t m_acc = 0, p_acc = 0, q_acc = 0, pp_acc = 0, qp_acc = 0;
@@ -166,6 +167,7 @@ int Plan::build(const lqsgd_config* c, const lqsgd_layer* ls, int32_t n_layers) 
       for (int32_t rb = 0; rb < d.nrb; ++rb)
         for (int32_t ch = 0; ch < nchunk; ++ch)
           tilesB.push_back(Tile{lw, rb * d.rbb, std::min(d.rbb, d.rows - rb * d.rbb), ch});
+      if (w == 0) tilesG.insert(tilesG.end(), tilesB.end() - (size_t)d.nrb * nchunk, tilesB.end());
       for (int32_t e = 0; e < d.nq_el; e += 1024) tilesRQ.push_back(RTile{lw, e});
     }
     for (int32_t g = 0; g < gp; g += kXBlockGroups) tilesXP.push_back(XTile{li, g});
@@ -189,7 +191,7 @@ int Plan::build(const lqsgd_config* c, const lqsgd_layer* ls, int32_t n_layers) 
   }
   v_total = v_acc;
 
-  const int64_t tile_bytes = (int64_t)(tilesA.size() + tilesB.size()) * sizeof(Tile) +
+  const int64_t tile_bytes = (int64_t)(tilesA.size() + tilesB.size() + tilesG.size()) * sizeof(Tile) +
                              (int64_t)(tilesXP.size() + tilesXQ.size()) * sizeof(XTile) +
                              (int64_t)tilesRQ.size() * sizeof(RTile) + (int64_t)tilesV.size() * sizeof(VTile);
   device_bytes = 4 * ((int64_t)W * (m_stride + 2 * p_stride + q_stride + ppart_stride + qpart_stride) +

@@ -66,6 +66,7 @@ struct Plan {
   std::vector<VecDesc> vecs;
   std::vector<int32_t> kind_of;    // per caller index: >= 0 matrix index, < 0 -(vector index) - 1
   std::vector<Tile> tilesA, tilesB;
+  std::vector<Tile> tilesG;        // worker 0's items of tilesB: one pass over every layer (G-hat only)
   std::vector<XTile> tilesXP, tilesXQ;
   std::vector<RTile> tilesRQ;
   std::vector<VTile> tilesV;

@@ -26,9 +26,9 @@ def _vector_mean_ok(got, vs):
     return bool(np.all(np.abs(got.astype(f64) - want) <= bound))
 
 
-def _make(layers, vectors, rank, bits_p, bits_q, W, alpha=255.0):
+def _make(layers, vectors, rank, bits_p, bits_q, W, alpha=255.0, flags=0):
     ll = B.layer_list(layers, vectors)
-    return B.Compressor(ll, rank, bits_p, bits_q, W, alpha), list(range(len(layers)))
+    return B.Compressor(ll, rank, bits_p, bits_q, W, alpha, flags), list(range(len(layers)))
 
 
 def _random_inputs(rng, layers, W, dist="normal", scale=1e-3):
@@ -314,6 +314,53 @@ def test_resnet18_free_run_matches_oracle_and_is_deterministic():
     _say("   free run: %d of %d codes differ from the oracle's free run in step 2" % (n_flips, n_codes))
     for v in range(V):
         assert _vector_mean_ok(a["G"][L + v], [Vg[k][v] for k in range(w.workers)])
+
+
+# ---------------------------------------------------------------------------
+# deferred residual update (the default) against the eager one: same bits
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("layers,rank,bits,W", [
+    ([(64, 576), (128, 64), (64, 27), (10, 512)], 4, 8, 4),
+    ([(300, 260), (17, 4100)], 3, 4, 3),
+    ([(96, 520)], 16, 8, 2),
+])
+def test_deferred_residual_is_bit_identical_to_eager(layers, rank, bits, W):
+    import torch
+    _say("case: deferred vs eager residual", layers, rank, bits, W)
+    rng = np.random.default_rng(17)
+    vectors = (33,)
+    lazy, ml = _make(layers, vectors, rank, bits, bits, W)
+    eager, _ = _make(layers, vectors, rank, bits, bits, W, flags=B.FLAG_EAGER_RESIDUAL)
+    for l in ml:
+        q0 = rng.standard_normal((layers[l][1], min(rank, *layers[l]))).astype(f32)
+        lazy.set_q(l, q0); eager.set_q(l, q0)
+    n = len(layers)
+    gl = [torch.empty(s, device="cuda") for s in layers] + [torch.empty(33, device="cuda")]
+    ge = [torch.empty(s, device="cuda") for s in layers] + [torch.empty(33, device="cuda")]
+    for t in range(5):
+        G = _random_inputs(rng, layers, W)
+        Gd = pu.to_device([G[k] + [rng.standard_normal(33).astype(f32)] for k in range(W)])
+        lazy.step(Gd, gl if t != 2 else None)       # one step without G-hat
+        eager.step(Gd, ge if t != 2 else None)
+        for l in range(n + 1):
+            if t != 2:
+                assert torch.equal(gl[l], ge[l]), (t, l)
+        for l in ml:
+            assert np.array_equal(lazy.get_factor(B.FACTOR_Q_BAR, l), eager.get_factor(B.FACTOR_Q_BAR, l))
+            assert np.array_equal(lazy.get_factor(B.FACTOR_P_BAR, l), eager.get_factor(B.FACTOR_P_BAR, l))
+        if t in (1, 3):          # reading the state applies the deferred update; the run must not notice
+            for l in ml:
+                for k in range(W):
+                    assert np.array_equal(lazy.get_state(l, k)[0], eager.get_state(l, k)[0]), (t, l, k)
+        if t == 3:               # overwriting one residual while an update is deferred
+            e_new = (rng.standard_normal(layers[0]) * 1e-4).astype(f32)
+            lazy.set_state(0, W - 1, e=e_new); eager.set_state(0, W - 1, e=e_new)
+    for l in ml:
+        for k in range(W):
+            el, ql = lazy.get_state(l, k)
+            ee, qe = eager.get_state(l, k)
+            assert np.array_equal(el, ee) and np.array_equal(ql, qe)
+    lazy.close(); eager.close()
 
 
 # ---------------------------------------------------------------------------
