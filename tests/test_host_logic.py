@@ -81,7 +81,7 @@ def test_plan_sizes_resnet18():
         assert info.wire_bytes == orc.wire_bytes(list(w.layers), r, bp, bq)
     # state + scratch stays close to the residual itself (4 B per element per worker)
     info = B.plan_query(B.layer_list(w.layers, w.vectors), 4, 8, 8, 8)
-    assert info.device_bytes < 1.15 * 4 * 8 * w.elements_per_worker
+    assert info.device_bytes < 1.2 * 4 * 8 * w.elements_per_worker
 
 
 def test_plan_sizes_large_configs():
