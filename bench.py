@@ -20,8 +20,23 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
-# algorithmic HBM bytes per gradient element of one worker, per streaming sweep
-SWEEP_BYTES = {"add_project_kernel": 12.0, "back_project_kernel": 4.0, "residual_kernel": 8.0}
+
+
+def sweep_bytes(kernel, w, ghat, eager):
+    """Algorithmic HBM bytes of one launch of a streaming kernel: bytes per
+    gradient element of one worker x elements, as the design document derives
+    them (sweep 0: read G, read M/E, write M = 12 B; sweep 1: read M = 4 B;
+    residual sweep: read M, write E = 8 B, plus G-hat once per layer = 4 B / W;
+    with the residual deferred only the G-hat pass remains)."""
+    e1 = w.elements_per_worker
+    e = w.workers * e1
+    if kernel == "add_project_kernel":
+        return 12.0 * e
+    if kernel == "back_project_kernel":
+        return 4.0 * e
+    if kernel == "residual_kernel":
+        return (8.0 * e if eager else 0.0) + (4.0 * e1 if ghat else 0.0)
+    return None
 
 
 def main():
@@ -35,8 +50,14 @@ def main():
     ap.add_argument("--workers", type=int, default=None)
     ap.add_argument("--llm-layers", type=int, default=32)
     ap.add_argument("--no-ghat", action="store_true", help="do not write G-hat (state update only)")
+    ap.add_argument("--eager", action="store_true",
+                    help="apply the residual update at the end of every step (a third sweep) instead of "
+                         "deferring it into the next step's first sweep")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="before the benchmark, copy a 1 GiB tensor three times (a kernel of known HBM "
+                         "traffic for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (W simulated workers share it; "
@@ -68,6 +89,14 @@ def main():
         w = wl.scaled(w, **over)
     L, V, W = len(w.layers), len(w.vectors), w.workers
 
+    if args.calibration_copy:
+        src = torch.ones(1 << 28, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     # ---- synthetic inputs, resident in HBM before anything is timed -----
     grads = []
     for k in range(W):
@@ -77,7 +106,8 @@ def main():
     ghat = None
     if not args.no_ghat:
         ghat = [torch.empty(s, device="cuda") for s in w.layers] + [torch.empty(n, device="cuda") for n in w.vectors]
-    comp = B.Compressor(B.layer_list(w.layers, w.vectors), w.rank, w.bits, w.bits, W, w.alpha)
+    comp = B.Compressor(B.layer_list(w.layers, w.vectors), w.rank, w.bits, w.bits, W, w.alpha,
+                        B.FLAG_EAGER_RESIDUAL if args.eager else 0)
     q0 = [wl.initial_q(w, l) for l in range(L)]
     for l in range(L):
         comp.set_q(l, q0[l])
@@ -117,11 +147,8 @@ def main():
                 name = B.kernel_name(k) + ("_q" if k == B.KERNEL_EXCHANGE_Q else "_p" if k == B.KERNEL_EXCHANGE_P else "")
                 kernels[name] = {"avg_us": 1e3 * ms[k] / cnt[k], "launches": cnt[k]}
         dom = max((k for k in kernels), key=lambda n: kernels[n]["avg_us"])
-        per_elem = SWEEP_BYTES.get(dom)
-        if per_elem is not None:
-            alg = per_elem * elems
-            if dom == "residual_kernel" and ghat is not None:
-                alg += 4.0 * w.elements_per_worker          # G-hat, once per layer
+        alg = sweep_bytes(dom, w, ghat is not None, args.eager)
+        if alg:
             achieved = alg / (kernels[dom]["avg_us"] * 1e-6) / 1e9
             roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                         "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
@@ -129,8 +156,8 @@ def main():
                         "algorithmic_bytes_per_launch": alg,
                         "avg_launch_us": round(kernels[dom]["avg_us"], 2)}
         for n, d in kernels.items():
-            if n in SWEEP_BYTES:
-                alg = SWEEP_BYTES[n] * elems + (4.0 * w.elements_per_worker if (n == "residual_kernel" and ghat is not None) else 0.0)
+            alg = sweep_bytes(n, w, ghat is not None, args.eager)
+            if alg:
                 d["hbm_frac"] = round(alg / (d["avg_us"] * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)
             d["avg_us"] = round(d["avg_us"], 2)
 
@@ -139,16 +166,19 @@ def main():
     if not args.no_cpu_baseline:
         cpu = _cpu_baseline(w, grads, q0)
 
-    step_bytes = 24.0 * W * w.elements_per_worker + (4.0 * w.elements_per_worker if ghat is not None else 0.0)
+    step_bytes = sum(sweep_bytes(k, w, ghat is not None, args.eager)
+                     for k in ("add_project_kernel", "back_project_kernel", "residual_kernel"))
     out = {
         "metric": "compressed gradient GB/s per LQ-SGD step (ResNet-18 set, r=4) and % HBM peak",
         "value": round(value, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "%s: %d matrices + %d vectors, %d elements/worker, r=%d, b=%d, W=%d, alpha=%g, %s gradients, G-hat %s"
+        "config": {"workload": "%s: %d matrices + %d vectors, %d elements/worker, r=%d, b=%d, W=%d, alpha=%g, %s gradients, G-hat %s, residual update %s"
                    % (w.name, L, V, w.elements_per_worker, w.rank, w.bits, W, w.alpha, w.dist,
-                      "written" if ghat is not None else "not written"),
+                      "written" if ghat is not None else "not written",
+                      "at the end of each step" if args.eager else "fused into the next step's first sweep"),
                    "rank": w.rank, "bits": w.bits, "workers": W, "gradient_bytes_per_step": grad_bytes},
+        "step_algorithmic_bytes": step_bytes,
         "step_hbm_frac": round(step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
         "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels,
         "wire_bytes_per_worker_step": comp.wire_bytes(),
