@@ -82,7 +82,10 @@ def staged_iteration(comp: B.Compressor, G_host, G_dev, E_host, Q_host, matrix_l
     G_host[w][l], E_host[w][l] (state before the iteration), Q_host[l]: numpy.
     matrix_layers: indices (in the compressor's layer list) of the 2-D layers;
     G_host / E_host / Q_host are indexed by position in that list.
-    Returns (E_new[w][l], Q_bar[l]) as read back from the device.
+    layers_to_check / workers_to_check restrict the comparison (and the copies
+    to the host) to a sample; entries of G_host / E_host outside it may be None.
+    Returns (E_new[w][l], Q_bar[l]) as read back from the device (None outside
+    the sample).
     """
     W = comp.workers
     bp, bq, alpha = comp.bits_p, comp.bits_q, comp.alpha
@@ -93,10 +96,10 @@ def staged_iteration(comp: B.Compressor, G_host, G_dev, E_host, Q_host, matrix_l
     M = {}
     for li in Ls:
         l = matrix_layers[li]
-        for w in range(W):
+        for w in Ws:
             m_gpu, _ = comp.get_state(l, w, want_q=False)
             M[(li, w)] = m_gpu
-            if w in Ws:
+            if True:
                 # G' = G + E: one IEEE addition per element, must be bit-exact
                 assert np.array_equal(m_gpu, (G_host[w][li].astype(f64) + E_host[w][li].astype(f64)).astype(f32))
                 p_pre = comp.get_factor(B.FACTOR_P_PRE, l, w)
@@ -161,11 +164,11 @@ def staged_iteration(comp: B.Compressor, G_host, G_dev, E_host, Q_host, matrix_l
         ghat = (Pbar[li].astype(f64) @ qb.astype(f64).T).astype(f32)
         absterms = np.abs(Pbar[li]).astype(f64) @ np.abs(qb).astype(f64).T
         r_l = qb.shape[1]
-        for w in range(W):
+        for w in Ws:
             e_gpu, q_state = comp.get_state(l, w)
             E_new[w][li] = e_gpu
             assert np.array_equal(q_state, qb)            # warm start = aggregated Q
-            if w in Ws:
+            if True:
                 want = (M[(li, w)].astype(f64) - ghat.astype(f64)).astype(f32)
                 rep.note("E", rel_fro(e_gpu, want))
                 assert rel_fro(e_gpu, want) <= FP_TOL

@@ -1,0 +1,80 @@
+"""GPU parity at the benchmark's full sizes for the sets that do not fit the
+host: the HIP path runs the whole workload in the launch configuration the
+benchmark times; a sample of (layer, worker) pairs is copied back and every
+stage of those is compared with the CPU oracle (the stage-wise protocol needs
+only that worker's matrix plus the small factors and packets of all workers)."""
+import numpy as np
+import pytest
+
+from paper_2506_17974_amd import binding as B
+from paper_2506_17974_amd import workloads as wl
+from tests import parity_utils as pu
+
+pytestmark = pytest.mark.gpu
+f32 = np.float32
+
+
+def _say(*a):
+    print(*a, flush=True)
+
+
+def _sampled_run(w, layers_to_check, workers_to_check, steps):
+    import torch
+    L, W = len(w.layers), w.workers
+    comp = B.Compressor(B.layer_list(w.layers), w.rank, w.bits, w.bits, W, w.alpha)
+    Q = [None] * L
+    for l in range(L):
+        q0 = wl.initial_q(w, l)
+        comp.set_q(l, q0)
+        if l in layers_to_check:
+            Q[l] = q0
+    E = [[np.zeros(w.layers[l], f32) if (l in layers_to_check and k in workers_to_check) else None
+          for l in range(L)] for k in range(W)]
+    rep = pu.StageReport()
+    for t in range(steps):
+        Gd = [[wl.device_gradient(w, t, l, k) for l in range(L)] for k in range(W)]
+        torch.cuda.synchronize()
+        G = [[Gd[k][l].cpu().numpy() if (l in layers_to_check and k in workers_to_check) else None
+              for l in range(L)] for k in range(W)]
+        _say("   step %d: inputs ready" % t)
+        E, Qn = pu.staged_iteration(comp, G, Gd, E, Q, list(range(L)), rep,
+                                    layers_to_check=layers_to_check, workers_to_check=workers_to_check)
+        for l in layers_to_check:
+            Q[l] = Qn[l]
+        _say("   step %d: %s" % (t, rep))
+        del Gd
+    comp.close()
+    return rep
+
+
+def test_sweep_8192_full_size():
+    """8192 x 8192, W = 16, r = 4, b = 8: two iterations (the second carries the
+    residual and the warm start), three of the sixteen workers checked."""
+    w = wl.sweep_8192(4, 8)
+    _say("case: sweep_8192 r=4 b=8 W=16 full size")
+    _sampled_run(w, [0], [0, 7, 15], steps=2)
+
+
+@pytest.mark.parametrize("rank,bits", [(1, 2), (2, 4), (8, 8), (16, 4), (32, 8)])
+def test_sweep_8192_other_ranks(rank, bits):
+    """The other points of the rank / bit-width sweep at the full matrix size,
+    with four workers (the per-worker kernels do not depend on W)."""
+    w = wl.sweep_8192(rank, bits, workers=4)
+    _say("case: sweep_8192 r=%d b=%d W=4" % (rank, bits))
+    _sampled_run(w, [0], [3], steps=2 if rank <= 8 else 1)
+
+
+def test_llm_stack_full_size():
+    """32 layers x {4 x (4096 x 4096), 4096 x 11008, 11008 x 4096}, W = 4: 80.5 GB
+    of gradients and as much residual state on the device, one batched launch
+    per kernel; one matrix of each shape from the first, a middle and the last
+    layer is checked, on two of the four workers."""
+    import torch
+    free, total = torch.cuda.mem_get_info()
+    w = wl.llm_stack(32)
+    need = 2 * w.gradient_bytes * 1.03
+    if free < need:
+        pytest.skip("needs %.0f GB of device memory, %.0f GB free" % (need / 1e9, free / 1e9))
+    _say("case: llm_stack 32 layers W=4 full size")
+    sample = [0, 4, 5, 6 * 15 + 2, 6 * 15 + 5, 6 * 31 + 3, 6 * 31 + 4]
+    _sampled_run(w, sample, [0, 3], steps=2)
