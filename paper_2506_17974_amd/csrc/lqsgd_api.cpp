@@ -178,7 +178,7 @@ int run_sweep0(lqsgd_ctx* c) {
                                   next_dir(c), c->stream)); }
   c->pending = false;
   { Timed t(c, LQSGD_KERNEL_ORTH);
-    HIP_TRY(c, launch_orth(c->plan.RP, c->plan.max_rows, c->args, c->stream)); }
+    HIP_TRY(c, launch_orth(c->plan.RP, c->plan.max_rows, c->plan.max_rank, c->args, c->stream)); }
   return LQSGD_OK;
 }
 int run_exchange(lqsgd_ctx* c, int mode, int phase) {
@@ -350,6 +350,7 @@ int lqsgd_create(const lqsgd_config* cfg, const lqsgd_layer* layers, int32_t n_l
   TRY_(dev_alloc(c, &a.Ppart, W * p.ppart_stride, true));
   TRY_(dev_alloc(c, &a.Ppre, W * p.p_stride, true));
   TRY_(dev_alloc(c, &a.Porth, W * p.p_stride, true));
+  TRY_(dev_alloc(c, &a.orth_part, 2 * W * (size_t)std::max(p.L, 1) * ((p.max_rows + 255) / 256) * p.RP, true));
   TRY_(dev_alloc(c, &a.Pbar, (size_t)p.p_stride, true));
   TRY_(dev_alloc(c, &a.Qpart, W * p.qpart_stride, true));
   TRY_(dev_alloc(c, &a.Qw, W * p.q_stride, true));

@@ -18,6 +18,7 @@ struct DevArgs {
   float* Ppart;                // sweep-0 partial products, per worker
   float* Ppre;                 // P_w before Gram-Schmidt
   float* Porth;                // P_w after Gram-Schmidt
+  float* orth_part;            // [2][L*W][ceil(max_rows/256)][RP] slice partials of the many-workgroup Gram-Schmidt
   float* Pbar;                 // aggregated P (shared)
   float* Qpart;                // sweep-1 partial products, per worker
   float* Qw;                   // Q_w
@@ -43,7 +44,7 @@ enum ExchangeMode { kQuantOnly = 0, kMeanOnly = 1, kFused = 2 };
 // E = M - P-bar Q-bar^T is applied on the fly (see add_project_kernel).
 hipError_t launch_add_project(int RP, const DevArgs& a, const Tile* tiles, int ntiles, int fuse_residual, int reverse,
                               hipStream_t s);
-hipError_t launch_orth(int RP, int max_rows, const DevArgs& a, hipStream_t s);
+hipError_t launch_orth(int RP, int max_rows, int max_rank, const DevArgs& a, hipStream_t s);
 hipError_t launch_exchange(int mode, int phase, const DevArgs& a, const XTile* tiles, int ntiles, hipStream_t s);
 // Sweep 1 also runs the plain mean of the 1-D tensors (nvtiles extra workgroups).
 hipError_t launch_back_project(int RP, const DevArgs& a, const Tile* tiles, int ntiles, const VTile* vtiles, int nvtiles,

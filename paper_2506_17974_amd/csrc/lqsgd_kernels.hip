@@ -533,6 +533,117 @@ __global__ __launch_bounds__(BS) void orth_reg_kernel(DevArgs a) {
 }
 
 // ---------------------------------------------------------------------------
+// orth, many workgroups per (layer, worker): for tall factors with few
+// (layer, worker) pairs, where one workgroup each would leave the chip idle.
+// The rows are cut into slices of 256; launch j (j = 0 .. r) applies the update
+// of column j-1 to its slice (using the block-wide totals of launch j-1, added
+// up over the slices in slice order) and then forms its slice's partial dot
+// products of column j with the columns after it.  The grid-wide dependency
+// between columns is the kernel boundary.  Launch 0 sums the sweep-0 partials,
+// launch r finishes with absmax(P_w) through an integer atomic max.
+// ---------------------------------------------------------------------------
+template <int RP>
+__global__ __launch_bounds__(256) void orth_wide_kernel(DevArgs a, int j, int nslice_max) {
+  __shared__ float red[4][RP];
+  __shared__ float redmax[4];
+  const int lw = blockIdx.x / nslice_max, slice = blockIdx.x - lw * nslice_max;
+  const int layer = lw / a.W, worker = lw - layer * a.W;
+  const LayerDesc& ld = a.layers[layer];
+  const int rows = ld.rows, r = ld.r;
+  const int nslice = (rows + 255) >> 8;
+  if (slice >= nslice || j > r) return;
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
+  const int row = slice * 256 + tid;
+  const bool live = row < rows;
+  float* pre = a.Ppre + (size_t)worker * a.p_stride + ld.p_off;
+  float* orth = a.Porth + (size_t)worker * a.p_stride + ld.p_off;
+  float* part = a.orth_part;    // [2][L*W][nslice_max][RP]
+  const size_t pstride = (size_t)a.L * a.W * nslice_max * RP;
+  float v[RP];
+#pragma unroll
+  for (int k = 0; k < RP; ++k) v[k] = 0.0f;
+  if (j == 0) {
+    if (slice == 0 && tid == 0) a.scaleP[(size_t)worker * a.L + layer] = 0.0f;
+    if (live) {
+      const float* Pp = a.Ppart + (size_t)worker * a.ppart_stride + ld.ppart_off;
+      for (int s = 0; s < ld.nseg; ++s) {
+        const float* src = Pp + (size_t)s * ld.np_pad + (size_t)row * r;
+#pragma unroll
+        for (int k = 0; k < RP; ++k)
+          if (k < r) v[k] += src[k];
+      }
+#pragma unroll
+      for (int k = 0; k < RP; ++k)
+        if (k < r) {
+          pre[(size_t)row * r + k] = v[k];
+          orth[(size_t)row * r + k] = v[k];
+        }
+    }
+  } else {
+    const int c = j - 1;                         // the column this launch finishes
+    const float* pin = part + (size_t)(c & 1) * pstride + (size_t)lw * nslice_max * RP;
+    float tot[RP];
+#pragma unroll
+    for (int k = 0; k < RP; ++k) tot[k] = 0.0f;
+    for (int s = 0; s < nslice; ++s) {
+#pragma unroll
+      for (int k = 0; k < RP; ++k) tot[k] += pin[(size_t)s * RP + k];
+    }
+    float nrm2 = 0.0f;
+#pragma unroll
+    for (int k = 0; k < RP; ++k)
+      if (k == c) nrm2 = tot[k];
+    const float inv = (nrm2 > FLT_MIN) ? 1.0f / sqrtf(nrm2) : 0.0f;
+    if (live) {
+      float* dst = orth + (size_t)row * r;
+#pragma unroll
+      for (int k = 0; k < RP; ++k)
+        if (k < r) v[k] = dst[k];
+      float qv = 0.0f;
+#pragma unroll
+      for (int k = 0; k < RP; ++k)
+        if (k == c) qv = v[k] * inv;
+#pragma unroll
+      for (int k = 0; k < RP; ++k) {
+        if (k == c) v[k] = qv;
+        else if (k > c && k < r) v[k] = fmaf(-(tot[k] * inv), qv, v[k]);
+      }
+#pragma unroll
+      for (int k = 0; k < RP; ++k)
+        if (k >= c && k < r) dst[k] = v[k];
+    }
+  }
+  if (j < r) {
+    // partial <column j, column k> over this slice, every k (entries k < j are not used)
+    float vj = 0.0f;
+#pragma unroll
+    for (int k = 0; k < RP; ++k)
+      if (k == j) vj = v[k];
+    float s[RP];
+#pragma unroll
+    for (int k = 0; k < RP; ++k) s[k] = vj * v[k];
+    transpose_reduce<RP, RP, 32>(s, lane);
+    if ((lane & (kWave / RP - 1)) == 0) red[wave][lane >> (6 - log2c(RP))] = s[0];
+    __syncthreads();
+    if (tid < RP)
+      part[(size_t)(j & 1) * pstride + ((size_t)lw * nslice_max + slice) * RP + tid] =
+          (red[0][tid] + red[1][tid]) + (red[2][tid] + red[3][tid]);
+  } else {
+    float mx = 0.0f;
+#pragma unroll
+    for (int k = 0; k < RP; ++k)
+      if (k < r) mx = fmaxf(mx, fabsf(v[k]));
+    mx = wave_max(mx);
+    if (lane == 0) redmax[wave] = mx;
+    __syncthreads();
+    if (tid == 0) {
+      const float m = fmaxf(fmaxf(redmax[0], redmax[1]), fmaxf(redmax[2], redmax[3]));
+      atomicMax(reinterpret_cast<unsigned int*>(a.scaleP + (size_t)worker * a.L + layer), __float_as_uint(m));
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
 // exchange: LogQuantize (Eq. (5) discretised to 2^b levels, Section 4.1),
 // pack, LogDequantize (Eq. (6)) and the mean over workers that stands in for
 // the All-Reduce.
@@ -982,9 +1093,20 @@ void launch_orth_reg(const DevArgs& a, dim3 grid, hipStream_t s) {
   }
 }
 
-hipError_t launch_orth(int rp, int max_rows, const DevArgs& a, hipStream_t s) {
+hipError_t launch_orth(int rp, int max_rows, int max_rank, const DevArgs& a, hipStream_t s) {
   if (a.L <= 0) return hipSuccess;
   const dim3 grid(a.L * a.W);
+  const int nslice = (max_rows + 255) / 256;
+  // Tall factors and too few (layer, worker) pairs to fill 256 CUs with one workgroup
+  // each, or no register-resident variant for this rank: one launch per column.
+  const bool reg_fits = (max_rows <= 512 && rp * 2 <= 64) || (max_rows <= 2048 && rp * 8 <= 64) ||
+                        (max_rows <= 4096 && rp * 4 <= 48) || (max_rows <= 11264 && rp * 11 <= 48);
+  if (a.orth_part && nslice >= 8 && ((int)grid.x < 128 || !reg_fits)) {
+    for (int j = 0; j <= max_rank; ++j) {
+      LQSGD_RP_SWITCH(rp, (orth_wide_kernel<RP><<<dim3(grid.x * nslice), dim3(256), 0, s>>>(a, j, nslice)));
+    }
+    return hipGetLastError();
+  }
   if (max_rows <= 512) {
     LQSGD_RP_SWITCH(rp, (launch_orth_reg<RP, 2, 256>(a, grid, s)));
   } else if (max_rows <= 2048) {

@@ -116,6 +116,7 @@ int Plan::build(const lqsgd_config* c, const lqsgd_layer* ls, int32_t n_layers) 
   L = (int32_t)layers.size();
   V = (int32_t)vecs.size();
   RP = pad_rank(max_r);
+  max_rank = max_r;
 
   // ---- tile sizes --------------------------------------------------------
   // A launch wants several times 256 CUs x 16 wavefronts of work items, each
@@ -195,7 +196,8 @@ int Plan::build(const lqsgd_config* c, const lqsgd_layer* ls, int32_t n_layers) 
                              (int64_t)(tilesXP.size() + tilesXQ.size()) * sizeof(XTile) +
                              (int64_t)tilesRQ.size() * sizeof(RTile) + (int64_t)tilesV.size() * sizeof(VTile);
   device_bytes = 4 * ((int64_t)W * (m_stride + 2 * p_stride + q_stride + ppart_stride + qpart_stride) +
-                      p_stride + q_stride + v_total + 2 * (int64_t)W * std::max(L, 1)) +
+                      p_stride + q_stride + v_total + 2 * (int64_t)W * std::max(L, 1) +
+                      2 * (int64_t)W * std::max(L, 1) * ((max_rows + 255) / 256) * RP) +
                  (int64_t)W * (magp_stride + sgnp_stride + magq_stride + sgnq_stride) + tile_bytes +
                  (int64_t)L * sizeof(LayerDesc) + (int64_t)V * sizeof(VecDesc) +
                  (int64_t)(W + 1) * n_all * 8 + 4 * 4 * 256;

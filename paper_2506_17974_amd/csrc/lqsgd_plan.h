@@ -62,6 +62,7 @@ struct Plan {
   int32_t W = 0, L = 0, V = 0;  // workers, matrix layers, vector layers
   int32_t RP = 0;               // register rank: smallest of 1,2,4,8,16,32 >= max layer rank
   int32_t max_rows = 0;         // largest row count of a matrix layer
+  int32_t max_rank = 0;         // largest effective rank of a matrix layer
   std::vector<LayerDesc> layers;
   std::vector<VecDesc> vecs;
   std::vector<int32_t> kind_of;    // per caller index: >= 0 matrix index, < 0 -(vector index) - 1
