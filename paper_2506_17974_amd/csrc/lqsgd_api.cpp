@@ -44,7 +44,7 @@ struct lqsgd_ctx {
   std::vector<void*> allocs;
   DevArgs args{};
   // device copies of the work lists
-  Tile* d_tilesA = nullptr; Tile* d_tilesB = nullptr; Tile* d_tilesG = nullptr;
+  Tile* d_tilesA = nullptr; Tile* d_tilesB = nullptr; Tile* d_tilesG = nullptr; Tile* d_tilesBM = nullptr;
   XTile* d_tilesXP = nullptr; XTile* d_tilesXQ = nullptr;
   RTile* d_tilesRQ = nullptr; VTile* d_tilesV = nullptr;
   // pointer tables
@@ -189,8 +189,13 @@ int run_exchange(lqsgd_ctx* c, int mode, int phase) {
 }
 int run_sweep1(lqsgd_ctx* c, bool with_vectors) {
   { Timed t(c, LQSGD_KERNEL_BACK_PROJECT);
-    HIP_TRY(c, launch_back_project(c->plan.RP, c->args, c->d_tilesB, (int)c->plan.tilesB.size(), c->d_tilesV,
-                                   with_vectors ? (int)c->plan.tilesV.size() : 0, next_dir(c), c->stream)); }
+    const int nv = with_vectors ? (int)c->plan.tilesV.size() : 0;
+    if (c->plan.mfma)
+      HIP_TRY(c, launch_back_project_mfma(c->args, c->d_tilesBM, (int)c->plan.tilesBM.size(), c->d_tilesV, nv,
+                                          next_dir(c), c->stream));
+    else
+      HIP_TRY(c, launch_back_project(c->plan.RP, c->args, c->d_tilesB, (int)c->plan.tilesB.size(), c->d_tilesV, nv,
+                                     next_dir(c), c->stream)); }
   { Timed t(c, LQSGD_KERNEL_REDUCE_Q);
     HIP_TRY(c, launch_reduce_q(c->args, c->d_tilesRQ, (int)c->plan.tilesRQ.size(), c->stream)); }
   return LQSGD_OK;
@@ -268,7 +273,7 @@ int lqsgd_plan_query(const lqsgd_config* cfg, const lqsgd_layer* layers, int32_t
   out->n_vector = p.V;
   out->rank_pad = p.RP;
   out->tiles[0] = (int32_t)p.tilesA.size();
-  out->tiles[1] = (int32_t)p.tilesB.size();
+  out->tiles[1] = (int32_t)(p.mfma ? p.tilesBM.size() : p.tilesB.size());
   out->tiles[2] = (int32_t)p.tilesB.size();
   return LQSGD_OK;
 }
@@ -279,7 +284,8 @@ int64_t lqsgd_plan_tiles(const lqsgd_config* cfg, const lqsgd_layer* layers, int
   Plan p;
   const int rc = p.build(cfg, layers, n_layers);
   if (rc) return fail(nullptr, rc, p.err);
-  const std::vector<Tile>& tl = sweep == 0 ? p.tilesA : p.tilesB;
+  const bool bm = sweep == 1 && p.mfma;
+  const std::vector<Tile>& tl = sweep == 0 ? p.tilesA : (bm ? p.tilesBM : p.tilesB);
   if (out) {
     const int64_t n = std::min<int64_t>(cap, (int64_t)tl.size());
     for (int64_t i = 0; i < n; ++i) {
@@ -295,8 +301,9 @@ int64_t lqsgd_plan_tiles(const lqsgd_config* cfg, const lqsgd_layer* layers, int
         o[4] = t.aux * d.segw;
         o[5] = std::min(d.cols, o[4] + d.segw) - o[4];
       } else {
-        o[4] = t.aux * kWave * d.vec;
-        o[5] = std::min(d.cols, o[4] + kWave * d.vec) - o[4];
+        const int cw = bm ? kMfmaCols : kWave * d.vec;
+        o[4] = t.aux * cw;
+        o[5] = std::min(d.cols, o[4] + cw) - o[4];
       }
     }
   }
@@ -369,6 +376,7 @@ int lqsgd_create(const lqsgd_config* cfg, const lqsgd_layer* layers, int32_t n_l
   TRY_(dev_upload(c, &c->d_tilesA, p.tilesA));
   TRY_(dev_upload(c, &c->d_tilesB, p.tilesB));
   TRY_(dev_upload(c, &c->d_tilesG, p.tilesG));
+  TRY_(dev_upload(c, &c->d_tilesBM, p.tilesBM));
   TRY_(dev_upload(c, &c->d_tilesXP, p.tilesXP));
   TRY_(dev_upload(c, &c->d_tilesXQ, p.tilesXQ));
   TRY_(dev_upload(c, &c->d_tilesRQ, p.tilesRQ));

@@ -49,6 +49,9 @@ hipError_t launch_exchange(int mode, int phase, const DevArgs& a, const XTile* t
 // Sweep 1 also runs the plain mean of the 1-D tensors (nvtiles extra workgroups).
 hipError_t launch_back_project(int RP, const DevArgs& a, const Tile* tiles, int ntiles, const VTile* vtiles, int nvtiles,
                                int reverse, hipStream_t s);
+// The same sweep on the matrix cores (rank pad 16 or 32; tiles are row block x 128-column group).
+hipError_t launch_back_project_mfma(const DevArgs& a, const Tile* tiles, int ntiles, const VTile* vtiles, int nvtiles,
+                                    int reverse, hipStream_t s);
 hipError_t launch_reduce_q(const DevArgs& a, const RTile* tiles, int ntiles, hipStream_t s);
 // mode: 0 = residual for all workers, 1 = residual + G-hat, 2 = G-hat only (tiles of worker 0).
 hipError_t launch_residual(int RP, int mode, const DevArgs& a, const Tile* tiles, int ntiles, int reverse, hipStream_t s);

@@ -925,6 +925,98 @@ __global__ __launch_bounds__(256) void back_project_kernel(DevArgs a, const Tile
 }
 
 // ---------------------------------------------------------------------------
+// sweep 1 on the matrix cores, for rank pad 32, where 4 x r accumulators per
+// lane no longer fit the vector register file.
+// v_mfma_f32_32x32x2_f32 computes D[32 x 32] += A[32 x 2] B[2 x 32] with
+//   A: lane l holds A[i = l % 32][k = l / 32]
+//   B: lane l holds B[k = l / 32][j = l % 32]
+//   D: lane l, register v holds D[i = 8 (v / 4) + 4 (l / 32) + v % 4][j = l % 32]
+// Here j = rank, k = two gradient rows per instruction, i = gradient column.
+// Which column an index i stands for is free, as long as the result is read
+// back the same way: lane (i, k) loads the float4 of columns 4 i .. 4 i + 3 of
+// its row (so a half-wavefront reads 512 contiguous bytes of a row, a
+// wavefront two rows, a workgroup 2 KiB of each row), and component s of that
+// float4 feeds matrix instruction s, whose block D_s then belongs to columns
+// 4 i + s.  No transposition and no LDS; a 32 x 32 block of Q_w accumulates in
+// 16 registers.
+// ---------------------------------------------------------------------------
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+template <bool VEC4>
+__device__ __forceinline__ void back_project_mfma_tile(const DevArgs& a, const LayerDesc& ld, const Tile& tl, int worker,
+                                                       int wave, int lane) {
+  const int cols = ld.cols, r = ld.r;
+  const int c0 = tl.aux * kMfmaCols + wave * 128;
+  if (c0 >= cols) return;
+  const int li = lane & 31, h = lane >> 5;
+  const float* M = a.E + (size_t)worker * a.m_stride + ld.m_off;
+  const float* Pb = a.Pbar + ld.p_off;
+  const bool rankok = li < r;
+  const int rend = tl.row0 + tl.nrows;
+  const int cl = c0 + 4 * li;                      // first of this lane's four columns
+  v16f acc[4];
+#pragma unroll
+  for (int s = 0; s < 4; ++s)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[s][i] = 0.0f;
+  constexpr int U = 4;
+  for (int rb = tl.row0; rb < rend; rb += 2 * U) {
+    Pk<4> am[U];
+    float bp[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int row = rb + 2 * u + h;
+      const bool ok = row < rend;
+      const float* mrow = M + (size_t)row * cols;
+      if constexpr (VEC4) {
+        if (ok && cl < cols) {
+          am[u] = ldrow<4, LQSGD_NT_M != 0>(reinterpret_cast<const char*>(mrow), (unsigned)cl * 4u);
+        } else {
+#pragma unroll
+          for (int s = 0; s < 4; ++s) am[u].v[s] = 0.0f;
+        }
+      } else {
+#pragma unroll
+        for (int s = 0; s < 4; ++s) am[u].v[s] = (ok && cl + s < cols) ? mrow[cl + s] : 0.0f;
+      }
+      bp[u] = (ok && rankok) ? Pb[(size_t)row * r + li] : 0.0f;
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int s = 0; s < 4; ++s) acc[s] = __builtin_amdgcn_mfma_f32_32x32x2f32(am[u].v[s], bp[u], acc[s], 0, 0, 0);
+  }
+  float* Qp = a.Qpart + (size_t)worker * a.qpart_stride + ld.qpart_off + (size_t)(tl.row0 / ld.rbb) * ld.nq_pad;
+#pragma unroll
+  for (int s = 0; s < 4; ++s)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int col = c0 + 4 * (8 * (v >> 2) + 4 * h + (v & 3)) + s;
+      if (col < cols && rankok) Qp[(size_t)col * r + li] = acc[s][v];
+    }
+}
+
+__global__ __launch_bounds__(256) void back_project_mfma_kernel(DevArgs a, const Tile* __restrict__ tiles, int ntiles,
+                                                                const VTile* __restrict__ vtiles, int reverse) {
+  if ((int)blockIdx.x >= ntiles) {
+    vector_mean_tile(a, vtiles[blockIdx.x - ntiles]);
+    return;
+  }
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int lane = threadIdx.x & (kWave - 1);
+  if (blockIdx.x == 0) {   // absmax accumulators of reduce_q start from zero
+    for (int i = threadIdx.x; i < a.W * a.L; i += 256) a.scaleQ[i] = 0.0f;
+  }
+  const Tile tl = tiles[reverse ? ntiles - 1 - blockIdx.x : blockIdx.x];
+  const int layer = tl.lw / a.W, worker = tl.lw - layer * a.W;
+  const LayerDesc& ld = a.layers[layer];
+  if (ld.vec == 4)
+    back_project_mfma_tile<true>(a, ld, tl, worker, wave, lane);
+  else
+    back_project_mfma_tile<false>(a, ld, tl, worker, wave, lane);
+}
+
+// ---------------------------------------------------------------------------
 // reduce_q: Q_w = sum over row blocks of the partials (fixed order), and
 // absmax(Q_w) -> scaleQ.  The max over workgroups goes through an integer
 // atomic max on the float's bit pattern (non-negative floats order like
@@ -1138,6 +1230,13 @@ hipError_t launch_back_project(int rp, const DevArgs& a, const Tile* tiles, int 
   if (ntiles + nvtiles <= 0) return hipSuccess;
   const dim3 grid(ntiles + nvtiles), block(256);
   LQSGD_RP_SWITCH(rp, (back_project_kernel<RP><<<grid, block, 0, s>>>(a, tiles, ntiles, vtiles, reverse)));
+  return hipGetLastError();
+}
+
+hipError_t launch_back_project_mfma(const DevArgs& a, const Tile* tiles, int ntiles, const VTile* vtiles, int nvtiles,
+                                    int reverse, hipStream_t s) {
+  if (ntiles + nvtiles <= 0) return hipSuccess;
+  back_project_mfma_kernel<<<dim3(ntiles + nvtiles), dim3(256), 0, s>>>(a, tiles, ntiles, vtiles, reverse);
   return hipGetLastError();
 }
 

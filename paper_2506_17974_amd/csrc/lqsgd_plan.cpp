@@ -62,7 +62,7 @@ int Plan::build(const lqsgd_config* c, const lqsgd_layer* ls, int32_t n_layers) 
   W = c->workers;
   n_all = n_layers;
   layers.clear(); vecs.clear(); kind_of.clear();
-  tilesA.clear(); tilesB.clear(); tilesG.clear(); tilesXP.clear(); tilesXQ.clear(); tilesRQ.clear(); tilesV.clear();
+  tilesA.clear(); tilesB.clear(); tilesBM.clear(); tilesG.clear(); tilesXP.clear(); tilesXQ.clear(); tilesRQ.clear(); tilesV.clear();
 
   int max_r = 1;
   max_rows = 0;
@@ -117,6 +117,7 @@ int Plan::build(const lqsgd_config* c, const lqsgd_layer* ls, int32_t n_layers) 
   V = (int32_t)vecs.size();
   RP = pad_rank(max_r);
   max_rank = max_r;
+  mfma = RP >= env_i64("LQSGD_MFMA_MIN_RP", 32);   // measured: at rank pad 16 the vector kernel is still faster
 
   // ---- tile sizes --------------------------------------------------------
   // A launch wants several times 256 CUs x 16 wavefronts of work items, each
@@ -141,8 +142,17 @@ int Plan::build(const lqsgd_config* c, const lqsgd_layer* ls, int32_t n_layers) 
     int64_t ng = std::max<int64_t>(1, (tgtA + seg_elems / 2) / seg_elems);
     const int32_t trows = (int32_t)std::min<int64_t>(round_up(d.rows, kRowsPerGroup), ng * kRowsPerGroup);
 
+    // sweeps 1 / 2 on the vector units: row blocks of rbb_v rows
     int64_t rbb = std::max<int64_t>(4, round_up(std::max<int64_t>(1, tgtB / cw), 4));
-    d.rbb = (int32_t)std::min<int64_t>(rbb, round_up(d.rows, 4));
+    const int32_t rbb_v = (int32_t)std::min<int64_t>(rbb, round_up(d.rows, 4));
+    const int32_t nrb_v = (d.rows + rbb_v - 1) / rbb_v;
+    // the partial planes of Q belong to whichever kernel runs sweep 1
+    if (mfma) {
+      const int64_t rbm = env_i64("LQSGD_TILE_BM", std::min<int64_t>(2048, std::max<int64_t>(256, total / (49152 * 16))));
+      d.rbb = (int32_t)std::min<int64_t>(round_up(rbm, 2), round_up(d.rows, 2));
+    } else {
+      d.rbb = rbb_v;
+    }
     d.nrb = (d.rows + d.rbb - 1) / d.rbb;
     const int nchunk = (d.cols + cw - 1) / cw;
 
@@ -165,10 +175,14 @@ int Plan::build(const lqsgd_config* c, const lqsgd_layer* ls, int32_t n_layers) 
       for (int32_t row0 = 0; row0 < d.rows; row0 += trows)
         for (int32_t s = 0; s < d.nseg; ++s)
           tilesA.push_back(Tile{lw, row0, std::min(trows, d.rows - row0), s});
-      for (int32_t rb = 0; rb < d.nrb; ++rb)
+      for (int32_t rb = 0; rb < nrb_v; ++rb)
         for (int32_t ch = 0; ch < nchunk; ++ch)
-          tilesB.push_back(Tile{lw, rb * d.rbb, std::min(d.rbb, d.rows - rb * d.rbb), ch});
-      if (w == 0) tilesG.insert(tilesG.end(), tilesB.end() - (size_t)d.nrb * nchunk, tilesB.end());
+          tilesB.push_back(Tile{lw, rb * rbb_v, std::min(rbb_v, d.rows - rb * rbb_v), ch});
+      if (w == 0) tilesG.insert(tilesG.end(), tilesB.end() - (size_t)nrb_v * nchunk, tilesB.end());
+      if (mfma)
+        for (int32_t rb = 0; rb < d.nrb; ++rb)
+          for (int32_t cg = 0; cg < (d.cols + kMfmaCols - 1) / kMfmaCols; ++cg)
+            tilesBM.push_back(Tile{lw, rb * d.rbb, std::min(d.rbb, d.rows - rb * d.rbb), cg});
       for (int32_t e = 0; e < d.nq_el; e += 1024) tilesRQ.push_back(RTile{lw, e});
     }
     for (int32_t g = 0; g < gp; g += kXBlockGroups) tilesXP.push_back(XTile{li, g});
@@ -192,7 +206,7 @@ int Plan::build(const lqsgd_config* c, const lqsgd_layer* ls, int32_t n_layers) 
   }
   v_total = v_acc;
 
-  const int64_t tile_bytes = (int64_t)(tilesA.size() + tilesB.size() + tilesG.size()) * sizeof(Tile) +
+  const int64_t tile_bytes = (int64_t)(tilesA.size() + tilesB.size() + tilesBM.size() + tilesG.size()) * sizeof(Tile) +
                              (int64_t)(tilesXP.size() + tilesXQ.size()) * sizeof(XTile) +
                              (int64_t)tilesRQ.size() * sizeof(RTile) + (int64_t)tilesV.size() * sizeof(VTile);
   device_bytes = 4 * ((int64_t)W * (m_stride + 2 * p_stride + q_stride + ppart_stride + qpart_stride) +

@@ -13,6 +13,7 @@ namespace lqsgd {
 
 constexpr int kWave = 64;
 constexpr int kRowsPerGroup = 8;   // rows a wavefront carries through one column pass of sweep 0
+constexpr int kMfmaCols = 512;     // columns one workgroup of the matrix-core sweep 1 covers (4 waves x 4 strips x 32)
 constexpr int kXGroup = 8;         // elements one lane quantises / packs (b bytes + 1 sign byte)
 constexpr int kXBlockGroups = 32;  // groups of 8 elements one exchange workgroup covers
 
@@ -63,10 +64,12 @@ struct Plan {
   int32_t RP = 0;               // register rank: smallest of 1,2,4,8,16,32 >= max layer rank
   int32_t max_rows = 0;         // largest row count of a matrix layer
   int32_t max_rank = 0;         // largest effective rank of a matrix layer
+  bool mfma = false;            // rank pad >= 16: the products run on the matrix cores
   std::vector<LayerDesc> layers;
   std::vector<VecDesc> vecs;
   std::vector<int32_t> kind_of;    // per caller index: >= 0 matrix index, < 0 -(vector index) - 1
   std::vector<Tile> tilesA, tilesB;
+  std::vector<Tile> tilesBM;       // sweep 1 on the matrix cores (rank pad >= 16): row block x 128-column group
   std::vector<Tile> tilesG;        // worker 0's items of tilesB: one pass over every layer (G-hat only)
   std::vector<XTile> tilesXP, tilesXQ;
   std::vector<RTile> tilesRQ;
