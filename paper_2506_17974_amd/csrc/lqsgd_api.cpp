@@ -44,7 +44,7 @@ struct lqsgd_ctx {
   std::vector<void*> allocs;
   DevArgs args{};
   // device copies of the work lists
-  Tile* d_tilesA = nullptr; Tile* d_tilesB = nullptr; Tile* d_tilesG = nullptr; Tile* d_tilesBM = nullptr;
+  Tile* d_tilesA = nullptr; Tile* d_tilesB = nullptr; Tile* d_tilesG = nullptr; Tile* d_tilesBM = nullptr; Tile* d_tilesAG = nullptr;
   XTile* d_tilesXP = nullptr; XTile* d_tilesXQ = nullptr;
   RTile* d_tilesRQ = nullptr; VTile* d_tilesV = nullptr;
   // pointer tables
@@ -174,8 +174,12 @@ int next_dir(lqsgd_ctx* c) {
 
 int run_sweep0(lqsgd_ctx* c) {
   { Timed t(c, LQSGD_KERNEL_ADD_PROJECT);
-    HIP_TRY(c, launch_add_project(c->plan.RP, c->args, c->d_tilesA, (int)c->plan.tilesA.size(), c->pending ? 1 : 0,
-                                  next_dir(c), c->stream)); }
+    if (c->plan.mfma_a)
+      HIP_TRY(c, launch_mfma_sweep(c->plan.RP, c->pending ? 1 : 0, c->args, c->d_tilesA, (int)c->plan.tilesA.size(),
+                                   next_dir(c), c->stream));
+    else
+      HIP_TRY(c, launch_add_project(c->plan.RP, c->args, c->d_tilesA, (int)c->plan.tilesA.size(), c->pending ? 1 : 0,
+                                    next_dir(c), c->stream)); }
   c->pending = false;
   { Timed t(c, LQSGD_KERNEL_ORTH);
     HIP_TRY(c, launch_orth(c->plan.RP, c->plan.max_rows, c->plan.max_rank, c->args, c->stream)); }
@@ -205,12 +209,19 @@ int run_sweep1(lqsgd_ctx* c, bool with_vectors) {
 // when asked for, is then written by a pass of its own over the layers.
 int run_sweep2(lqsgd_ctx* c, bool write_ghat) {
   Timed t(c, LQSGD_KERNEL_RESIDUAL);
+  const Plan& p = c->plan;
   if (c->eager) {
-    HIP_TRY(c, launch_residual(c->plan.RP, write_ghat ? 1 : 0, c->args, c->d_tilesB, (int)c->plan.tilesB.size(),
-                               next_dir(c), c->stream));
+    if (p.mfma_a)
+      HIP_TRY(c, launch_mfma_sweep(p.RP, write_ghat ? 3 : 2, c->args, c->d_tilesA, (int)p.tilesA.size(), next_dir(c), c->stream));
+    else
+      HIP_TRY(c, launch_residual(p.RP, write_ghat ? 1 : 0, c->args, c->d_tilesB, (int)p.tilesB.size(), next_dir(c), c->stream));
   } else {
-    if (write_ghat)
-      HIP_TRY(c, launch_residual(c->plan.RP, 2, c->args, c->d_tilesG, (int)c->plan.tilesG.size(), 0, c->stream));
+    if (write_ghat) {
+      if (p.mfma_a)
+        HIP_TRY(c, launch_mfma_sweep(p.RP, 4, c->args, c->d_tilesAG, (int)p.tilesAG.size(), 0, c->stream));
+      else
+        HIP_TRY(c, launch_residual(p.RP, 2, c->args, c->d_tilesG, (int)p.tilesG.size(), 0, c->stream));
+    }
     c->pending = true;
   }
   return LQSGD_OK;
@@ -219,7 +230,11 @@ int run_sweep2(lqsgd_ctx* c, bool write_ghat) {
 int materialise(lqsgd_ctx* c) {
   if (!c->pending) return LQSGD_OK;
   Timed t(c, LQSGD_KERNEL_RESIDUAL);
-  HIP_TRY(c, launch_residual(c->plan.RP, 0, c->args, c->d_tilesB, (int)c->plan.tilesB.size(), next_dir(c), c->stream));
+  const Plan& p = c->plan;
+  if (p.mfma_a)
+    HIP_TRY(c, launch_mfma_sweep(p.RP, 2, c->args, c->d_tilesA, (int)p.tilesA.size(), next_dir(c), c->stream));
+  else
+    HIP_TRY(c, launch_residual(p.RP, 0, c->args, c->d_tilesB, (int)p.tilesB.size(), next_dir(c), c->stream));
   c->pending = false;
   return LQSGD_OK;
 }
@@ -274,7 +289,7 @@ int lqsgd_plan_query(const lqsgd_config* cfg, const lqsgd_layer* layers, int32_t
   out->rank_pad = p.RP;
   out->tiles[0] = (int32_t)p.tilesA.size();
   out->tiles[1] = (int32_t)(p.mfma ? p.tilesBM.size() : p.tilesB.size());
-  out->tiles[2] = (int32_t)p.tilesB.size();
+  out->tiles[2] = (int32_t)(p.mfma_a ? p.tilesA.size() : p.tilesB.size());
   return LQSGD_OK;
 }
 
@@ -285,7 +300,8 @@ int64_t lqsgd_plan_tiles(const lqsgd_config* cfg, const lqsgd_layer* layers, int
   const int rc = p.build(cfg, layers, n_layers);
   if (rc) return fail(nullptr, rc, p.err);
   const bool bm = sweep == 1 && p.mfma;
-  const std::vector<Tile>& tl = sweep == 0 ? p.tilesA : (bm ? p.tilesBM : p.tilesB);
+  const bool as0 = sweep == 0 || (sweep == 2 && p.mfma_a);     // items of sweep 0's kind
+  const std::vector<Tile>& tl = as0 ? p.tilesA : (bm ? p.tilesBM : p.tilesB);
   if (out) {
     const int64_t n = std::min<int64_t>(cap, (int64_t)tl.size());
     for (int64_t i = 0; i < n; ++i) {
@@ -297,7 +313,7 @@ int64_t lqsgd_plan_tiles(const lqsgd_config* cfg, const lqsgd_layer* layers, int
       o[1] = t.lw - li * p.W;
       o[2] = t.row0;
       o[3] = t.nrows;
-      if (sweep == 0) {
+      if (as0) {
         o[4] = t.aux * d.segw;
         o[5] = std::min(d.cols, o[4] + d.segw) - o[4];
       } else {
@@ -377,6 +393,7 @@ int lqsgd_create(const lqsgd_config* cfg, const lqsgd_layer* layers, int32_t n_l
   TRY_(dev_upload(c, &c->d_tilesB, p.tilesB));
   TRY_(dev_upload(c, &c->d_tilesG, p.tilesG));
   TRY_(dev_upload(c, &c->d_tilesBM, p.tilesBM));
+  TRY_(dev_upload(c, &c->d_tilesAG, p.tilesAG));
   TRY_(dev_upload(c, &c->d_tilesXP, p.tilesXP));
   TRY_(dev_upload(c, &c->d_tilesXQ, p.tilesXQ));
   TRY_(dev_upload(c, &c->d_tilesRQ, p.tilesRQ));

@@ -56,4 +56,9 @@ hipError_t launch_reduce_q(const DevArgs& a, const RTile* tiles, int ntiles, hip
 // mode: 0 = residual for all workers, 1 = residual + G-hat, 2 = G-hat only (tiles of worker 0).
 hipError_t launch_residual(int RP, int mode, const DevArgs& a, const Tile* tiles, int ntiles, int reverse, hipStream_t s);
 
+// Sweeps 0 and 2 on the matrix cores (rank pad 16 or 32), over the wavefront work list of
+// sweep 0 (32-row items).  mode: 0 = M = G + E and P partials, 1 = the same with the deferred
+// residual applied on the fly, 2 = residual, 3 = residual + G-hat, 4 = G-hat only (worker 0's items).
+hipError_t launch_mfma_sweep(int RP, int mode, const DevArgs& a, const Tile* tiles, int ntiles, int reverse, hipStream_t s);
+
 }  // namespace lqsgd

@@ -1146,6 +1146,245 @@ __global__ __launch_bounds__(256) void residual_kernel(DevArgs a, const Tile* __
   }
 }
 
+// ---------------------------------------------------------------------------
+// Sweeps 0 and 2 on the matrix cores, rank pads 16 and 32.
+// One wavefront per work item (32 rows x one column segment), 64 columns at a
+// time.  The 32 x 64 tile is loaded and stored in "row layout" (float4 per
+// lane, 16 lanes = 256 contiguous bytes of a row, 4 rows per instruction).
+//
+//   G-hat tile = P-bar[32 x r] Q-bar^T[r x 64]: i = row, j = column, k = rank.
+//     Lane (i, h) holds P-bar[row i][h r/2 .. h r/2 + r/2) -- a contiguous run of
+//     its factor row, so the wavefront reads one contiguous block of P-bar;
+//     lane (h, j) holds Q-bar[col j][the same ranks].  Which rank a step k
+//     stands for is free as long as both operands agree.
+//   P tile += M[32 x 64] Q[64 x r]: i = row, j = rank, k = column.  Lanes index
+//     rows here while memory runs along columns, so M goes through a
+//     wave-private LDS tile ([row][column], pitch 68 floats): written in row
+//     layout, read back as lane (i, h) -> columns 32 h .. 32 h + 31 of row i.
+//   The G-hat block comes out of the matrix cores in their D layout (lanes =
+//   columns); it takes the same LDS tile the other way to meet G and M in row
+//   layout for  M_new = G + (M_old - G-hat).
+// Modes: kMAdd (first iteration: M = G + E), kMAddFused (deferred residual),
+// kMResidual / kMResidualGhat / kMGhatOnly (the residual sweep; G-hat uses the
+// very same instruction sequence as in kMAddFused, so deferring the residual
+// does not change a bit of the result).
+// ---------------------------------------------------------------------------
+enum MfmaMode { kMAdd = 0, kMAddFused = 1, kMResidual = 2, kMResidualGhat = 3, kMGhatOnly = 4 };
+constexpr int kLP = 68;   // LDS pitch (floats): 16-byte aligned rows, 4-bank skew per row
+
+__device__ __forceinline__ void wave_lds_fence() {
+  // LDS traffic between the lanes of one wavefront: the hardware keeps DS
+  // operations of a wavefront in order; this only stops the compiler.
+  __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+}
+
+template <int RP, int MODE, bool EXACT>
+__device__ __forceinline__ void mfma_tile(const float* __restrict__ G, float* __restrict__ M,
+                                          const float* Q, const float* Pb, float* __restrict__ Pp,
+                                          float* __restrict__ ghat_out, int cols, int r, int row0, int nrows,
+                                          int col0, int col1, int lane, float* lds) {
+  constexpr bool ADD = (MODE == kMAdd || MODE == kMAddFused);
+  constexpr bool NEEDG = (MODE != kMAdd);
+  constexpr bool HASM = (MODE != kMGhatOnly);
+  constexpr int KH = RP / 2;                       // ranks per half-wavefront
+  const int li = lane & 31, h = lane >> 5;
+  const int sr = lane >> 4, c4 = (lane & 15) * 4;  // row layout: rows 4 i + sr, columns c4 .. c4 + 3
+  float pa[KH];
+  if constexpr (NEEDG) {
+    const int row = row0 + li;
+    if constexpr (EXACT) {
+      if (li < nrows) {
+        const float4* src = reinterpret_cast<const float4*>(Pb + (size_t)row * RP + KH * h);
+#pragma unroll
+        for (int t = 0; t < KH / 4; ++t) {
+          const float4 x = src[t];
+          pa[4 * t] = x.x; pa[4 * t + 1] = x.y; pa[4 * t + 2] = x.z; pa[4 * t + 3] = x.w;
+        }
+      } else {
+#pragma unroll
+        for (int k = 0; k < KH; ++k) pa[k] = 0.0f;
+      }
+    } else {
+#pragma unroll
+      for (int k = 0; k < KH; ++k) pa[k] = (li < nrows && KH * h + k < r) ? Pb[(size_t)row * r + KH * h + k] : 0.0f;
+    }
+  }
+  v16f accP, accP2;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) { accP[i] = 0.0f; accP2[i] = 0.0f; }
+
+  for (int c = col0; c < col1; c += 64) {
+    const int cl = c + c4;
+    const bool colok = cl < col1;
+    Pk<4> g[8], e[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int rr = 4 * i + sr;
+      const bool ok = colok && rr < nrows;
+      const size_t off = (size_t)(row0 + rr) * cols;
+#pragma unroll
+      for (int v = 0; v < 4; ++v) { g[i].v[v] = 0.0f; e[i].v[v] = 0.0f; }
+      if (ok) {
+        if constexpr (ADD) g[i] = ldrow<4, LQSGD_NT_G != 0>(reinterpret_cast<const char*>(G + off), (unsigned)cl * 4u);
+        if constexpr (HASM) e[i] = ldrow<4, LQSGD_NT_E != 0>(reinterpret_cast<const char*>(M + off), (unsigned)cl * 4u);
+      }
+    }
+    float bq[32];
+    if constexpr (ADD) {
+#pragma unroll
+      for (int kk = 0; kk < 32; ++kk) {
+        const int col = c + 32 * h + kk;
+        bq[kk] = (col < col1 && li < r) ? Q[(size_t)col * r + li] : 0.0f;
+      }
+    }
+    if constexpr (NEEDG) {
+      float qb[2][KH];
+#pragma unroll
+      for (int b = 0; b < 2; ++b) {
+        const int col = c + 32 * b + li;
+        if constexpr (EXACT) {
+          if (col < col1) {
+            const float4* src = reinterpret_cast<const float4*>(Q + (size_t)col * RP + KH * h);
+#pragma unroll
+            for (int t = 0; t < KH / 4; ++t) {
+              const float4 x = src[t];
+              qb[b][4 * t] = x.x; qb[b][4 * t + 1] = x.y; qb[b][4 * t + 2] = x.z; qb[b][4 * t + 3] = x.w;
+            }
+          } else {
+#pragma unroll
+            for (int k = 0; k < KH; ++k) qb[b][k] = 0.0f;
+          }
+        } else {
+#pragma unroll
+          for (int k = 0; k < KH; ++k) qb[b][k] = (col < col1 && KH * h + k < r) ? Q[(size_t)col * r + KH * h + k] : 0.0f;
+        }
+      }
+      // the two 32-column blocks accumulate in turn: two independent chains on the matrix pipe
+      v16f gh0, gh1;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) { gh0[i] = 0.0f; gh1[i] = 0.0f; }
+#pragma unroll
+      for (int k = 0; k < KH; ++k) {
+        gh0 = __builtin_amdgcn_mfma_f32_32x32x2f32(pa[k], qb[0][k], gh0, 0, 0, 0);
+        gh1 = __builtin_amdgcn_mfma_f32_32x32x2f32(pa[k], qb[1][k], gh1, 0, 0, 0);
+      }
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        lds[(8 * (v >> 2) + 4 * h + (v & 3)) * kLP + li] = gh0[v];
+        lds[(8 * (v >> 2) + 4 * h + (v & 3)) * kLP + 32 + li] = gh1[v];
+      }
+      wave_lds_fence();
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int rr = 4 * i + sr;
+        const float4 t = *reinterpret_cast<const float4*>(lds + rr * kLP + c4);
+        if constexpr (HASM) {
+          e[i].v[0] -= t.x; e[i].v[1] -= t.y; e[i].v[2] -= t.z; e[i].v[3] -= t.w;
+        }
+        if (MODE == kMGhatOnly || (MODE == kMResidualGhat && ghat_out)) {
+          if (colok && rr < nrows) {
+            const Pk<4> o{{t.x, t.y, t.z, t.w}};
+            strow<4, true>(reinterpret_cast<char*>(ghat_out + (size_t)(row0 + rr) * cols), (unsigned)cl * 4u, o);
+          }
+        }
+      }
+      wave_lds_fence();
+    }
+    if constexpr (HASM) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int rr = 4 * i + sr;
+        Pk<4> m;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) m.v[v] = ADD ? g[i].v[v] + e[i].v[v] : e[i].v[v];
+        if (colok && rr < nrows)
+          strow<4, LQSGD_NT_ST_A != 0>(reinterpret_cast<char*>(M + (size_t)(row0 + rr) * cols), (unsigned)cl * 4u, m);
+        if constexpr (ADD)
+          *reinterpret_cast<float4*>(lds + rr * kLP + c4) = make_float4(m.v[0], m.v[1], m.v[2], m.v[3]);
+      }
+    }
+    if constexpr (ADD) {
+      wave_lds_fence();
+      // two accumulators (even / odd float4 of the lane's run of columns): two independent chains
+#pragma unroll
+      for (int t = 0; t < 8; t += 2) {
+        const float4 a0 = *reinterpret_cast<const float4*>(lds + li * kLP + 32 * h + 4 * t);
+        const float4 a1 = *reinterpret_cast<const float4*>(lds + li * kLP + 32 * h + 4 * t + 4);
+        accP = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.x, bq[4 * t + 0], accP, 0, 0, 0);
+        accP2 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.x, bq[4 * t + 4], accP2, 0, 0, 0);
+        accP = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.y, bq[4 * t + 1], accP, 0, 0, 0);
+        accP2 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.y, bq[4 * t + 5], accP2, 0, 0, 0);
+        accP = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.z, bq[4 * t + 2], accP, 0, 0, 0);
+        accP2 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.z, bq[4 * t + 6], accP2, 0, 0, 0);
+        accP = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.w, bq[4 * t + 3], accP, 0, 0, 0);
+        accP2 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.w, bq[4 * t + 7], accP2, 0, 0, 0);
+      }
+      wave_lds_fence();
+    }
+  }
+  if constexpr (ADD) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int rr = 8 * (v >> 2) + 4 * h + (v & 3);
+      if (rr < nrows && li < r) Pp[(size_t)(row0 + rr) * r + li] = accP[v] + accP2[v];
+    }
+  }
+}
+
+// rows that are not 16-byte aligned (cols % 4 != 0; tiny layers): vector units
+template <int RP, int MODE>
+__device__ __forceinline__ void mfma_mode_vector_fallback(const DevArgs& a, const LayerDesc& ld, const Tile& tl, int worker,
+                                                          const float* G, float* M, float* Pp, float* ghat_out,
+                                                          int col0, int col1, int lane) {
+  if constexpr (MODE == kMAdd) {
+    add_project_tile<RP, 1, 4, false, false>(G, M, a.Qbar + ld.q_off, a.Pbar + ld.p_off, Pp, ld.cols, ld.r, tl.row0,
+                                             tl.nrows, col0, col1, lane);
+  } else if constexpr (MODE == kMAddFused) {
+    add_project_tile<RP, 1, 4, false, true>(G, M, a.Qbar + ld.q_off, a.Pbar + ld.p_off, Pp, ld.cols, ld.r, tl.row0,
+                                            tl.nrows, col0, col1, lane);
+  } else {
+    constexpr int RM = MODE == kMResidual ? kResidual : (MODE == kMResidualGhat ? kResidualGhat : kGhatOnly);
+    for (int c = col0 + lane; c < col1; c += kWave) {
+      float q[RP];
+      load_slice<RP, 1, false>(a.Qbar + ld.q_off, c, ld.r, q);
+      residual_rows<RP, 1, false, RM>(M, a.Pbar + ld.p_off, ghat_out, ld.cols, ld.r, tl.row0, tl.row0 + tl.nrows,
+                                      (unsigned)c * 4u, q);
+    }
+  }
+}
+
+template <int RP, int MODE>
+__global__ __launch_bounds__(256) void mfma_sweep_kernel(DevArgs a, const Tile* __restrict__ tiles, int ntiles, int reverse) {
+  __shared__ __attribute__((aligned(16))) float lds_all[4][32 * kLP];
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int lane = threadIdx.x & (kWave - 1);
+  const int t = blockIdx.x * 4 + wave;
+  if (t >= ntiles) return;
+  const Tile tl = tiles[reverse ? ntiles - 1 - t : t];
+  const int layer = tl.lw / a.W, worker = tl.lw - layer * a.W;
+  const LayerDesc& ld = a.layers[layer];
+  const float* G = (MODE == kMAdd || MODE == kMAddFused) ? a.grads[(size_t)worker * a.n_all + ld.gidx] : nullptr;
+  float* M = a.E + (size_t)worker * a.m_stride + ld.m_off;
+  float* Pp = a.Ppart + (size_t)worker * a.ppart_stride + ld.ppart_off + (size_t)tl.aux * ld.np_pad;
+  float* ghat_out = nullptr;
+  if ((MODE == kMResidualGhat || MODE == kMGhatOnly) && worker == 0 && a.ghat) ghat_out = a.ghat[ld.gidx];
+  if (MODE == kMGhatOnly && !ghat_out) return;
+  const int col0 = tl.aux * ld.segw;
+  const int col1 = min(ld.cols, col0 + ld.segw);
+  if (ld.vec != 4) {
+    mfma_mode_vector_fallback<RP, MODE>(a, ld, tl, worker, G, M, Pp, ghat_out, col0, col1, lane);
+    return;
+  }
+  float* lds = lds_all[wave];
+  if (ld.r == RP)
+    mfma_tile<RP, MODE, true>(G, M, a.Qbar + ld.q_off, a.Pbar + ld.p_off, Pp, ghat_out, ld.cols, ld.r, tl.row0,
+                              tl.nrows, col0, col1, lane, lds);
+  else
+    mfma_tile<RP, MODE, false>(G, M, a.Qbar + ld.q_off, a.Pbar + ld.p_off, Pp, ghat_out, ld.cols, ld.r, tl.row0,
+                               tl.nrows, col0, col1, lane, lds);
+}
+
 }  // namespace
 
 // ---------------------------------------------------------------------------
@@ -1256,6 +1495,27 @@ hipError_t launch_residual(int rp, int mode, const DevArgs& a, const Tile* tiles
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
+}
+
+template <int RP>
+hipError_t launch_mfma_sweep_rp(int mode, const DevArgs& a, const Tile* tiles, int ntiles, int reverse, hipStream_t s) {
+  const dim3 grid((ntiles + 3) / 4), block(256);
+  switch (mode) {
+    case kMAdd: mfma_sweep_kernel<RP, kMAdd><<<grid, block, 0, s>>>(a, tiles, ntiles, reverse); break;
+    case kMAddFused: mfma_sweep_kernel<RP, kMAddFused><<<grid, block, 0, s>>>(a, tiles, ntiles, reverse); break;
+    case kMResidual: mfma_sweep_kernel<RP, kMResidual><<<grid, block, 0, s>>>(a, tiles, ntiles, reverse); break;
+    case kMResidualGhat: mfma_sweep_kernel<RP, kMResidualGhat><<<grid, block, 0, s>>>(a, tiles, ntiles, reverse); break;
+    case kMGhatOnly: mfma_sweep_kernel<RP, kMGhatOnly><<<grid, block, 0, s>>>(a, tiles, ntiles, reverse); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_mfma_sweep(int rp, int mode, const DevArgs& a, const Tile* tiles, int ntiles, int reverse, hipStream_t s) {
+  if (ntiles <= 0) return hipSuccess;
+  if (rp == 16) return launch_mfma_sweep_rp<16>(mode, a, tiles, ntiles, reverse, s);
+  if (rp == 32) return launch_mfma_sweep_rp<32>(mode, a, tiles, ntiles, reverse, s);
+  return hipErrorInvalidValue;
 }
 
 }  // namespace lqsgd

@@ -62,7 +62,7 @@ int Plan::build(const lqsgd_config* c, const lqsgd_layer* ls, int32_t n_layers) 
   W = c->workers;
   n_all = n_layers;
   layers.clear(); vecs.clear(); kind_of.clear();
-  tilesA.clear(); tilesB.clear(); tilesBM.clear(); tilesG.clear(); tilesXP.clear(); tilesXQ.clear(); tilesRQ.clear(); tilesV.clear();
+  tilesA.clear(); tilesAG.clear(); tilesB.clear(); tilesBM.clear(); tilesG.clear(); tilesXP.clear(); tilesXQ.clear(); tilesRQ.clear(); tilesV.clear();
 
   int max_r = 1;
   max_rows = 0;
@@ -117,6 +117,7 @@ int Plan::build(const lqsgd_config* c, const lqsgd_layer* ls, int32_t n_layers) 
   V = (int32_t)vecs.size();
   RP = pad_rank(max_r);
   max_rank = max_r;
+  mfma_a = RP >= env_i64("LQSGD_MFMA_A_MIN_RP", 16);
   mfma = RP >= env_i64("LQSGD_MFMA_MIN_RP", 32);   // measured: at rank pad 16 the vector kernel is still faster
 
   // ---- tile sizes --------------------------------------------------------
@@ -138,9 +139,10 @@ int Plan::build(const lqsgd_config* c, const lqsgd_layer* ls, int32_t n_layers) 
     int nseg = (int)((d.cols + segmax - 1) / segmax);
     d.segw = (int32_t)round_up((d.cols + nseg - 1) / nseg, cw);
     d.nseg = (d.cols + d.segw - 1) / d.segw;
-    const int64_t seg_elems = (int64_t)kRowsPerGroup * std::min(d.segw, d.cols);
-    int64_t ng = std::max<int64_t>(1, (tgtA + seg_elems / 2) / seg_elems);
-    const int32_t trows = (int32_t)std::min<int64_t>(round_up(d.rows, kRowsPerGroup), ng * kRowsPerGroup);
+    const int rowgrp = mfma_a ? 32 : kRowsPerGroup;      // a matrix-core item is one 32-row tile
+    const int64_t seg_elems = (int64_t)rowgrp * std::min(d.segw, d.cols);
+    int64_t ng = mfma_a ? 1 : std::max<int64_t>(1, (tgtA + seg_elems / 2) / seg_elems);
+    const int32_t trows = (int32_t)std::min<int64_t>(round_up(d.rows, rowgrp), ng * rowgrp);
 
     // sweeps 1 / 2 on the vector units: row blocks of rbb_v rows
     int64_t rbb = std::max<int64_t>(4, round_up(std::max<int64_t>(1, tgtB / cw), 4));
@@ -173,8 +175,10 @@ int Plan::build(const lqsgd_config* c, const lqsgd_layer* ls, int32_t n_layers) 
     for (int w = 0; w < W; ++w) {
       const int32_t lw = li * W + w;
       for (int32_t row0 = 0; row0 < d.rows; row0 += trows)
-        for (int32_t s = 0; s < d.nseg; ++s)
+        for (int32_t s = 0; s < d.nseg; ++s) {
           tilesA.push_back(Tile{lw, row0, std::min(trows, d.rows - row0), s});
+          if (w == 0) tilesAG.push_back(tilesA.back());
+        }
       for (int32_t rb = 0; rb < nrb_v; ++rb)
         for (int32_t ch = 0; ch < nchunk; ++ch)
           tilesB.push_back(Tile{lw, rb * rbb_v, std::min(rbb_v, d.rows - rb * rbb_v), ch});
@@ -206,7 +210,7 @@ int Plan::build(const lqsgd_config* c, const lqsgd_layer* ls, int32_t n_layers) 
   }
   v_total = v_acc;
 
-  const int64_t tile_bytes = (int64_t)(tilesA.size() + tilesB.size() + tilesBM.size() + tilesG.size()) * sizeof(Tile) +
+  const int64_t tile_bytes = (int64_t)(tilesA.size() + tilesAG.size() + tilesB.size() + tilesBM.size() + tilesG.size()) * sizeof(Tile) +
                              (int64_t)(tilesXP.size() + tilesXQ.size()) * sizeof(XTile) +
                              (int64_t)tilesRQ.size() * sizeof(RTile) + (int64_t)tilesV.size() * sizeof(VTile);
   device_bytes = 4 * ((int64_t)W * (m_stride + 2 * p_stride + q_stride + ppart_stride + qpart_stride) +

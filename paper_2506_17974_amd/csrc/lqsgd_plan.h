@@ -64,11 +64,13 @@ struct Plan {
   int32_t RP = 0;               // register rank: smallest of 1,2,4,8,16,32 >= max layer rank
   int32_t max_rows = 0;         // largest row count of a matrix layer
   int32_t max_rank = 0;         // largest effective rank of a matrix layer
-  bool mfma = false;            // rank pad >= 16: the products run on the matrix cores
+  bool mfma = false;            // sweep 1 runs on the matrix cores (rank pad 32)
+  bool mfma_a = false;          // sweeps 0 and 2 run on the matrix cores (rank pad >= 16): 32-row work items
   std::vector<LayerDesc> layers;
   std::vector<VecDesc> vecs;
   std::vector<int32_t> kind_of;    // per caller index: >= 0 matrix index, < 0 -(vector index) - 1
   std::vector<Tile> tilesA, tilesB;
+  std::vector<Tile> tilesAG;       // worker 0's items of tilesA (G-hat pass of the matrix-core path)
   std::vector<Tile> tilesBM;       // sweep 1 on the matrix cores (rank pad >= 16): row block x 128-column group
   std::vector<Tile> tilesG;        // worker 0's items of tilesB: one pass over every layer (G-hat only)
   std::vector<XTile> tilesXP, tilesXQ;

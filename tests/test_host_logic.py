@@ -56,13 +56,14 @@ def _coverage(layers, rank, W, sweep):
     return cover
 
 
+@pytest.mark.parametrize("rank", [4, 16, 32])
 @pytest.mark.parametrize("sweep", [0, 1, 2])
-def test_work_lists_cover_each_element_once(sweep):
+def test_work_lists_cover_each_element_once(sweep, rank):
     w = wl.small_cnn()
     layers = B.layer_list(w.layers, w.vectors)
     layers += [(1, 1, 0), (3, 5000, 0), (2100, 132, 0), (64, 27, 0)]
     W = 3
-    cover = _coverage(layers, 4, W, sweep)
+    cover = _coverage(layers, rank, W, sweep)
     n_matrix = sum(1 for l in layers if l[2] == 0)
     assert len(cover) == n_matrix * W
     for key, m in cover.items():
