@@ -53,6 +53,9 @@ typedef const float __attribute__((address_space(4)))* const_fp;
 #ifndef LQSGD_RT           // rows a wavefront carries through one column pass of sweep 0 (rank <= 8)
 #define LQSGD_RT 8
 #endif
+#ifndef LQSGD_B_U          // rows a wavefront of sweep 1 has in flight
+#define LQSGD_B_U 8
+#endif
 #ifndef LQSGD_A_WAVES      // occupancy target of sweep 0 (waves per SIMD)
 #define LQSGD_A_WAVES 1
 #endif
@@ -782,7 +785,7 @@ __global__ __launch_bounds__(256) void exchange_kernel(DevArgs a, const XTile* _
 template <int RP, int VEC, bool EXACT>
 __device__ __forceinline__ void back_project_rows(const float* __restrict__ M, const float* Pb, int cols, int r,
                                                   int ra, int rb, unsigned boff, float (&acc)[VEC * RP]) {
-  constexpr int U = 8;
+  constexpr int U = LQSGD_B_U;
   int i = ra;
   for (; i + U <= rb; i += U) {
     Pk<VEC> m[U];

@@ -126,7 +126,7 @@ int Plan::build(const lqsgd_config* c, const lqsgd_layer* ls, int32_t n_layers) 
   // work lists stay small.
   const int64_t total = matrix_elements * W;
   const int64_t tgtA = env_i64("LQSGD_TILE_A", std::min<int64_t>(131072, std::max<int64_t>(4096, total / 49152)));
-  const int64_t tgtB = env_i64("LQSGD_TILE_B", std::min<int64_t>(524288, std::max<int64_t>(8192, total / 12288)));
+  const int64_t tgtB = env_i64("LQSGD_TILE_B", std::min<int64_t>(131072, std::max<int64_t>(8192, total / 2730)));
   const int64_t segmax4 = env_i64("LQSGD_SEGMAX", 1024);
 
   int64_t m_acc = 0, p_acc = 0, q_acc = 0, pp_acc = 0, qp_acc = 0;
