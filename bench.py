@@ -152,7 +152,7 @@ def main():
             achieved = alg / (kernels[dom]["avg_us"] * 1e-6) / 1e9
             roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                         "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                        "traffic": _measured_traffic(dom, w.name),
+                        "traffic": _measured_traffic(dom, "%s_r%d_b%d_W%d" % (w.name, w.rank, w.bits, W)),
                         "algorithmic_bytes_per_launch": alg,
                         "avg_launch_us": round(kernels[dom]["avg_us"], 2)}
         for n, d in kernels.items():
@@ -189,7 +189,7 @@ def main():
 
 def _measured_traffic(kernel, workload):
     """HBM bytes per launch from the committed rocprofv3 counter summary, if one
-    exists for this kernel and workload (a line `<kernel> <workload> hbm_bytes_per_launch <number>`)."""
+    exists for this kernel and workload (a line `<kernel> <workload>_r<r>_b<b>_W<W> hbm_bytes_per_launch <number>`)."""
     path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
     try:
         with open(path) as fh:
