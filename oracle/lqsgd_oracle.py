@@ -32,6 +32,12 @@ again in the design document):
       packet, then take the mean (Eq. (1)), summed in worker order.
 * R7  effective rank of a layer is min(r, rows, cols).
 * R8  b = 0 switches quantisation off (the PowerSGD baseline of Section 3.2).
+* R9  ``layer_step_aggregate_first`` is the order Section 3.2 describes for
+      PowerSGD (exchange P, orthonormalise the aggregate once, then Q); with
+      bits > 0 the un-orthonormalised P_w is what gets quantised (R4's absmax
+      scale brings it into range).
+* R10 the model update is Algorithm 1's last statement / Eq. (2), plain SGD in
+      float32 storage; eta is a float32 value.
 
 Parity pins: see tests/test_oracle_pins.py.  Unpinned: the direction of a
 Gram-Schmidt column whose residual is pure rounding noise (rank-deficient
@@ -245,6 +251,46 @@ def layer_step(G, E, Q, rank, bits_p, bits_q, alpha):
         # E <- G' - G-hat   (Eq. (8))
         out["E_new"].append((out["M"][w].astype(f64) - G_hat.astype(f64)).astype(f32))
     return out
+
+
+def layer_step_aggregate_first(G, E, Q, rank, bits_p, bits_q, alpha):
+    """The PowerSGD order (Section 3.2: P = M Q is all-reduced, *then*
+    orthonormalised, then Q = M^T P-hat is all-reduced), with the same
+    quantised exchange as Algorithm 1 in place of the plain all-reduce.
+
+    Returns M[w], P_pre[w], pkt_P[w], P_mean (aggregate before Gram-Schmidt),
+    P_bar (the orthonormalised aggregate every worker then uses), Q_w[w],
+    pkt_Q[w], Q_bar, G_hat, E_new[w]."""
+    W = len(G)
+    rows, cols = G[0].shape
+    r = min(rank, rows, cols)
+    Q = np.asarray(Q, f32)
+    assert Q.shape == (cols, r)
+    res = {"M": [], "P_pre": [], "Q_w": [], "E_new": []}
+    for w in range(W):
+        Mw = (G[w].astype(f64) + E[w].astype(f64)).astype(f32)          # Eq. (9)
+        Pw = (Mw.astype(f64) @ Q.astype(f64)).astype(f32)               # P_w = M_w Q
+        res["M"].append(Mw)
+        res["P_pre"].append(Pw)
+    # exchange the raw factors, then one Gram-Schmidt on the aggregate
+    res["P_mean"], res["pkt_P"] = exchange(res["P_pre"], bits_p, alpha)
+    P_hat = orthonormalize(res["P_mean"]).astype(f32)
+    res["P_bar"] = P_hat
+    for w in range(W):
+        res["Q_w"].append((res["M"][w].astype(f64).T @ P_hat.astype(f64)).astype(f32))
+    res["Q_bar"], res["pkt_Q"] = exchange(res["Q_w"], bits_q, alpha)
+    Gh = (P_hat.astype(f64) @ res["Q_bar"].astype(f64).T).astype(f32)   # Eq. (7)
+    res["G_hat"] = Gh
+    for w in range(W):
+        res["E_new"].append((res["M"][w].astype(f64) - Gh.astype(f64)).astype(f32))   # Eq. (8)
+    return res
+
+
+def model_update(weights, g_hat, eta):
+    """w_{t+1} = w_t - eta G-hat_t (Algorithm 1, last statement; Eq. (2)).
+    float32 storage, eta a float32 value; for a 1-D tensor g_hat is its mean."""
+    step = f64(f32(eta)) * np.asarray(g_hat, f32).astype(f64)
+    return (np.asarray(weights, f32).astype(f64) - step).astype(f32)
 
 
 def vector_mean(vs):

@@ -478,6 +478,103 @@ def check_degenerate_inputs(o):
         assert out["pkt_P"][w][2] == 0 and not out["pkt_P"][w][0].any()
 
 
+def check_aggregate_first(o):
+    """The PowerSGD order: with quantisation off the W workers act as one worker
+    holding the mean gradient, a rank-r mean is recovered exactly for any W, and
+    the aggregated P-hat is orthonormal; with quantisation on every stage still
+    obeys its definition."""
+    rng = _rng(77)
+    rows, cols, r, W = 33, 26, 3, 5
+    # distinct full-rank worker gradients whose MEAN has rank r
+    A = rng.standard_normal((rows, r)); Bm = rng.standard_normal((r, cols))
+    N = [rng.standard_normal((rows, cols)) for _ in range(W)]
+    Nbar = sum(N) / W
+    G = [(A @ Bm + (N[w] - Nbar)).astype(f32) for w in range(W)]
+    E = [np.zeros((rows, cols), f32) for _ in range(W)]
+    Q0 = rng.standard_normal((cols, r)).astype(f32)
+    Mbar = sum(g.astype(f64) for g in G) / W
+    out = o.layer_step_aggregate_first(G, E, Q0, r, 0, 0, 255.0)
+    assert np.linalg.norm(out["G_hat"] - Mbar) <= 2e-5 * np.linalg.norm(Mbar)        # exact recovery, any W
+    std = o.layer_step(G, E, Q0, r, 0, 0, 255.0)
+    assert np.linalg.norm(std["G_hat"] - Mbar) > 1e-2 * np.linalg.norm(Mbar)         # ... which Algorithm 1's order lacks
+    P = out["P_bar"].astype(f64)
+    assert np.allclose(P.T @ P, np.eye(r), atol=1e-5)
+    # the same as one worker holding the mean gradient (LAPACK projection of that mean)
+    qr, _ = np.linalg.qr(Mbar @ Q0.astype(f64))
+    assert np.linalg.norm(out["G_hat"] - qr @ (qr.T @ Mbar)) <= 2e-5 * np.linalg.norm(Mbar)
+    one = o.layer_step([Mbar.astype(f32)], [E[0]], Q0, r, 0, 0, 255.0)
+    assert np.linalg.norm(out["Q_bar"] - one["Q_bar"]) <= 1e-5 * np.linalg.norm(one["Q_bar"])
+    assert np.linalg.norm(out["P_bar"] - one["P_bar"]) <= 1e-5 * np.linalg.norm(one["P_bar"])
+    # Eq. (8) per worker and in the mean; W = 1 coincides with Algorithm 1's order
+    for w in range(W):
+        assert np.array_equal(out["M"][w], G[w])
+        assert np.allclose(out["E_new"][w].astype(f64) + out["G_hat"], out["M"][w], rtol=0, atol=1e-6)
+    G1 = [rng.standard_normal((rows, cols)).astype(f32)]
+    E1 = [(rng.standard_normal((rows, cols)) * 0.1).astype(f32)]
+    a1 = o.layer_step_aggregate_first(G1, E1, Q0, r, 0, 0, 255.0)
+    s1 = o.layer_step(G1, E1, Q0, r, 0, 0, 255.0)
+    for key in ("P_bar", "Q_bar", "G_hat"):
+        assert np.array_equal(a1[key], s1[key])
+    assert np.array_equal(a1["E_new"][0], s1["E_new"][0])
+    # quantisation on: stages against their definitions
+    bits, alpha = 8, 255.0
+    Gq = [rng.standard_normal((rows, cols)).astype(f32) for _ in range(W)]
+    Eq = [(rng.standard_normal((rows, cols)) * 0.05).astype(f32) for _ in range(W)]
+    oq = o.layer_step_aggregate_first(Gq, Eq, Q0, r, bits, 4, alpha)
+    lv = (1 << bits) - 1
+    acc = np.zeros((rows, r))
+    for w in range(W):
+        Mw = Gq[w].astype(f64) + Eq[w].astype(f64)
+        assert np.allclose(oq["M"][w], Mw, rtol=1e-7, atol=0)
+        assert np.allclose(oq["P_pre"][w], Mw @ Q0.astype(f64), rtol=0, atol=1e-5)
+        k, sg, s = oq["pkt_P"][w]
+        assert s == np.max(np.abs(oq["P_pre"][w]))          # the raw factor is what gets quantised
+        d = o.log_dequantize(k, sg, s, bits, alpha)
+        # Eq. (5)/(6): half a level in the q-domain bounds the error
+        half = 0.5 / lv
+        qx = np.log1p(alpha * np.abs(oq["P_pre"][w].astype(f64)) / s) / np.log1p(alpha)
+        hi = np.expm1(np.minimum(qx + half, 1.0) * np.log1p(alpha)) / alpha * s
+        lo = np.expm1(np.maximum(qx - half, 0.0) * np.log1p(alpha)) / alpha * s
+        assert np.all(np.abs(d) <= hi * (1 + 1e-6) + 1e-12) and np.all(np.abs(d) >= lo * (1 - 1e-6) - 1e-12)
+        acc += d
+        assert np.allclose(oq["Q_w"][w], Mw.T @ oq["P_bar"].astype(f64), rtol=0, atol=1e-5)
+        assert oq["pkt_Q"][w][0].max() <= 15
+    assert np.allclose(oq["P_mean"], acc / W, rtol=0, atol=1e-6)
+    Pq = oq["P_bar"].astype(f64)
+    assert np.allclose(Pq.T @ Pq, np.eye(r), atol=1e-5)
+    qr, rr = np.linalg.qr(oq["P_mean"].astype(f64))
+    assert np.allclose(Pq, qr * np.sign(np.diag(rr)), atol=1e-5)
+    assert np.allclose(oq["G_hat"], Pq @ oq["Q_bar"].astype(f64).T, rtol=0, atol=1e-5)
+    Ebar = sum(e.astype(f64) for e in oq["E_new"]) / W
+    Mq = sum(m.astype(f64) for m in oq["M"]) / W
+    assert np.allclose(Ebar, Mq - oq["G_hat"], rtol=0, atol=1e-6)
+
+
+def check_model_update(o):
+    """Algorithm 1's last statement.  With quantisation off, one worker and
+    rank(G) <= r the reconstruction is G itself, so the step is plain SGD, Eq. (2)."""
+    rng = _rng(88)
+    rows, cols, r = 19, 14, 2
+    G = (rng.standard_normal((rows, r)) @ rng.standard_normal((r, cols))).astype(f32)
+    w0 = rng.standard_normal((rows, cols)).astype(f32)
+    out = o.layer_step([G], [np.zeros_like(G)], rng.standard_normal((cols, r)).astype(f32), r, 0, 0, 255.0)
+    eta = 0.125                                        # a power of two: eta * g is exact
+    w1 = o.model_update(w0, out["G_hat"], eta)
+    assert w1.dtype == f32 and w1.shape == w0.shape
+    assert np.allclose(w1, w0.astype(f64) - eta * G.astype(f64), rtol=0, atol=2e-5 * np.abs(G).max())
+    # exact cases: small integers and a power-of-two eta leave no rounding at all
+    wi = np.array([[4.0, -2.0], [1.0, 8.0]], f32); gi = np.array([[2.0, 4.0], [-6.0, 0.0]], f32)
+    assert np.array_equal(o.model_update(wi, gi, 0.5), np.array([[3.0, -4.0], [4.0, 8.0]], f32))
+    assert np.array_equal(o.model_update(wi, np.zeros_like(gi), 0.3), wi)
+    assert np.array_equal(o.model_update(wi, gi, 0.0), wi)
+    # linear in eta and in g
+    a = o.model_update(wi, gi, 0.25).astype(f64); b = o.model_update(wi, gi, 0.75).astype(f64)
+    assert np.array_equal(b - a, -0.5 * gi)
+    # eta is taken as a float32 value
+    gv = rng.standard_normal(4000).astype(f32)
+    assert np.array_equal(o.model_update(np.zeros_like(gv), gv, 0.1), (-(f64(f32(0.1)) * gv.astype(f64))).astype(f32))
+
+
 def all_checks(resnet_layers, resnet_vector_elems):
     return [
         ("map_closed_forms", check_map_closed_forms),
@@ -496,4 +593,6 @@ def all_checks(resnet_layers, resnet_vector_elems):
         ("aggregation", check_aggregation),
         ("tiny_bruteforce", check_tiny_bruteforce),
         ("degenerate_inputs", check_degenerate_inputs),
+        ("aggregate_first", check_aggregate_first),
+        ("model_update", check_model_update),
     ]

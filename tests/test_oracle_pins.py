@@ -58,6 +58,19 @@ MUTANTS = [
     ("warm_start_dropped", 'Q[l] = o["Q_bar"]', "pass"),
     ("error_not_carried", 'E[w][l] = o["E_new"][w]', "pass"),
     ("vector_sum", "return (acc / len(vs)).astype(f32)", "return (acc).astype(f32)"),
+    ("agg_first_orthonormalises_too_early", 'res["P_pre"].append(Pw)', 'res["P_pre"].append(orthonormalize(Pw).astype(f32))'),
+    ("agg_first_skips_orthonormalise", 'P_hat = orthonormalize(res["P_mean"]).astype(f32)', 'P_hat = res["P_mean"]'),
+    ("agg_first_q_uses_raw_mean", '(res["M"][w].astype(f64).T @ P_hat.astype(f64)).astype(f32)',
+     '(res["M"][w].astype(f64).T @ res["P_mean"].astype(f64)).astype(f32)'),
+    ("agg_first_feedback_dropped", "Mw = (G[w].astype(f64) + E[w].astype(f64)).astype(f32)", "Mw = (G[w].astype(f64)).astype(f32)"),
+    ("agg_first_p_transposed_q", "Pw = (Mw.astype(f64) @ Q.astype(f64)).astype(f32)", "Pw = (Mw.astype(f64) @ Q.astype(f64)[:, ::-1]).astype(f32)"),
+    ("agg_first_ghat_from_mean", 'Gh = (P_hat.astype(f64) @ res["Q_bar"].astype(f64).T).astype(f32)',
+     'Gh = (res["P_mean"].astype(f64) @ res["Q_bar"].astype(f64).T).astype(f32)'),
+    ("agg_first_residual_sign", '(res["M"][w].astype(f64) - Gh.astype(f64)).astype(f32)', '(Gh.astype(f64) - res["M"][w].astype(f64)).astype(f32)'),
+    ("agg_first_q_bits", 'exchange(res["Q_w"], bits_q, alpha)', 'exchange(res["Q_w"], bits_p, alpha)'),
+    ("update_sign", "(np.asarray(weights, f32).astype(f64) - step).astype(f32)", "(np.asarray(weights, f32).astype(f64) + step).astype(f32)"),
+    ("update_forgets_eta", "step = f64(f32(eta)) * np.asarray(g_hat, f32).astype(f64)", "step = np.asarray(g_hat, f32).astype(f64)"),
+    ("update_eta_not_f32", "step = f64(f32(eta)) * np.asarray(g_hat, f32).astype(f64)", "step = f64(eta) * np.asarray(g_hat, f32).astype(f64)"),
 ]
 
 
