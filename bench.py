@@ -27,7 +27,8 @@ def sweep_bytes(kernel, w, ghat, eager):
     gradient element of one worker x elements, as the design document derives
     them (sweep 0: read G, read M/E, write M = 12 B; sweep 1: read M = 4 B;
     residual sweep: read M, write E = 8 B, plus G-hat once per layer = 4 B / W;
-    with the residual deferred only the G-hat pass remains)."""
+    with the residual deferred only the G-hat pass remains).  `ghat`: 0 = not
+    written, 1 = stored, 2 = applied to the parameters (read w, write w)."""
     e1 = w.elements_per_worker
     e = w.workers * e1
     if kernel == "add_project_kernel":
@@ -35,7 +36,7 @@ def sweep_bytes(kernel, w, ghat, eager):
     if kernel == "back_project_kernel":
         return 4.0 * e
     if kernel == "residual_kernel":
-        return (8.0 * e if eager else 0.0) + (4.0 * e1 if ghat else 0.0)
+        return (8.0 * e if eager else 0.0) + 4.0 * e1 * ghat
     return None
 
 
@@ -58,6 +59,10 @@ def main():
     ap.add_argument("--calibration-copy", action="store_true",
                     help="before the benchmark, copy a 1 GiB tensor three times (a kernel of known HBM "
                          "traffic for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
+    ap.add_argument("--aggregate-first", action="store_true",
+                    help="the PowerSGD order: exchange the raw P factors, orthonormalise the aggregate once")
+    ap.add_argument("--update", type=float, default=None, metavar="ETA",
+                    help="apply w <- w - ETA G-hat to synthetic parameters inside the step instead of storing G-hat")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (W simulated workers share it; "
@@ -107,7 +112,8 @@ def main():
     if not args.no_ghat:
         ghat = [torch.empty(s, device="cuda") for s in w.layers] + [torch.empty(n, device="cuda") for n in w.vectors]
     comp = B.Compressor(B.layer_list(w.layers, w.vectors), w.rank, w.bits, w.bits, W, w.alpha,
-                        B.FLAG_EAGER_RESIDUAL if args.eager else 0)
+                        (B.FLAG_EAGER_RESIDUAL if args.eager else 0) |
+                        (B.FLAG_AGGREGATE_FIRST if args.aggregate_first else 0))
     q0 = [wl.initial_q(w, l) for l in range(L)]
     for l in range(L):
         comp.set_q(l, q0[l])
@@ -120,6 +126,10 @@ def main():
             gt[i] = t.data_ptr()
 
     def run(n):
+        if args.update is not None and gt is not None:
+            for _ in range(n):       # `ghat` holds the parameters (whatever torch.empty left there), updated in place
+                comp._check(B.lib().lqsgd_step_update(comp._h, tab, gt, args.update))
+            return
         for _ in range(n):
             comp.step_raw(tab, gt)
 
@@ -133,6 +143,7 @@ def main():
     grad_bytes = w.gradient_bytes
     value = grad_bytes / (ms_per_step * 1e-3) / 1e9
 
+    ghat_mode = 0 if ghat is None else (2 if args.update is not None else 1)
     # ---- per-kernel durations: HIP events on the library's own stream ----
     roofline = None
     kernels = {}
@@ -147,7 +158,7 @@ def main():
                 name = B.kernel_name(k) + ("_q" if k == B.KERNEL_EXCHANGE_Q else "_p" if k == B.KERNEL_EXCHANGE_P else "")
                 kernels[name] = {"avg_us": 1e3 * ms[k] / cnt[k], "launches": cnt[k]}
         dom = max((k for k in kernels), key=lambda n: kernels[n]["avg_us"])
-        alg = sweep_bytes(dom, w, ghat is not None, args.eager)
+        alg = sweep_bytes(dom, w, ghat_mode, args.eager)
         if alg:
             achieved = alg / (kernels[dom]["avg_us"] * 1e-6) / 1e9
             roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
@@ -156,7 +167,7 @@ def main():
                         "algorithmic_bytes_per_launch": alg,
                         "avg_launch_us": round(kernels[dom]["avg_us"], 2)}
         for n, d in kernels.items():
-            alg = sweep_bytes(n, w, ghat is not None, args.eager)
+            alg = sweep_bytes(n, w, ghat_mode, args.eager)
             if alg:
                 d["hbm_frac"] = round(alg / (d["avg_us"] * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)
             d["avg_us"] = round(d["avg_us"], 2)
@@ -166,7 +177,7 @@ def main():
     if not args.no_cpu_baseline:
         cpu = _cpu_baseline(w, grads, q0)
 
-    step_bytes = sum(sweep_bytes(k, w, ghat is not None, args.eager)
+    step_bytes = sum(sweep_bytes(k, w, ghat_mode, args.eager)
                      for k in ("add_project_kernel", "back_project_kernel", "residual_kernel"))
     out = {
         "metric": "compressed gradient GB/s per LQ-SGD step (ResNet-18 set, r=4) and % HBM peak",
@@ -175,8 +186,10 @@ def main():
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": "%s: %d matrices + %d vectors, %d elements/worker, r=%d, b=%d, W=%d, alpha=%g, %s gradients, G-hat %s, residual update %s"
                    % (w.name, L, V, w.elements_per_worker, w.rank, w.bits, W, w.alpha, w.dist,
-                      "written" if ghat is not None else "not written",
+                      ("applied to parameters (eta=%g)" % args.update) if (ghat is not None and args.update is not None)
+                      else "written" if ghat is not None else "not written",
                       "at the end of each step" if args.eager else "fused into the next step's first sweep"),
+                   "order": "aggregate, then orthonormalise" if args.aggregate_first else "orthonormalise, then aggregate (Algorithm 1)",
                    "rank": w.rank, "bits": w.bits, "workers": W, "gradient_bytes_per_step": grad_bytes},
         "step_algorithmic_bytes": step_bytes,
         "step_hbm_frac": round(step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),

@@ -70,6 +70,14 @@ typedef struct {
  * lqsgd_get_state / lqsgd_set_state apply a deferred update first, so callers
  * always see E.  With this flag the update runs at the end of every iteration. */
 #define LQSGD_FLAG_EAGER_RESIDUAL 1u
+/* The PowerSGD order of Section 3.2 instead of Algorithm 1's: the workers'
+ * raw P_w = M_w Q are quantised and aggregated first, and the aggregate is
+ * orthonormalised once (Gram-Schmidt) before Q_w = M_w^T P-hat.  With
+ * bits_p = bits_q = 0 this is PowerSGD itself: W workers then act exactly like
+ * one worker holding the mean gradient.  In this order LQSGD_FACTOR_P_ORTH does
+ * not exist (EINVAL), LQSGD_FACTOR_P_MEAN is the aggregate before Gram-Schmidt
+ * and LQSGD_FACTOR_P_BAR the orthonormalised aggregate that Q_w, G-hat and E use. */
+#define LQSGD_FLAG_AGGREGATE_FIRST 2u
 
 /* The "Require" line of Algorithm 1, plus the number of simulated workers. */
 typedef struct {
@@ -97,6 +105,8 @@ typedef struct {
 #define LQSGD_FACTOR_Q_W 3     /* Q_w = M_w^T P-bar, cols x r                      (per worker) */
 #define LQSGD_FACTOR_Q_BAR 4   /* mean of the dequantised Q_w = next warm-start Q, cols x r     */
 #define LQSGD_FACTOR_VMEAN 5   /* mean over workers of a VECTOR layer, rows elements            */
+#define LQSGD_FACTOR_P_MEAN 6  /* LQSGD_FLAG_AGGREGATE_FIRST only: mean of the dequantised raw   */
+                               /* P_w before Gram-Schmidt, rows x r (shared)                      */
 
 /* ---- lifetime ----------------------------------------------------------- */
 
@@ -166,6 +176,16 @@ int lqsgd_decompress(lqsgd_ctx* ctx, int32_t phase);
  *          VECTOR layer, the mean over workers.  Must not alias any gradient. */
 int lqsgd_step(lqsgd_ctx* ctx, const float* const* grads, float* const* ghat);
 
+/* The same iteration followed by Algorithm 1's last statement, fused into the
+ * pass that would write G-hat: w <- w - eta G-hat (Eq. (2)) for every matrix
+ * layer, w <- w - eta mean_w(g_w) for every VECTOR layer.
+ *   params : host array of n_layers device pointers to the fp32 parameters
+ *            (same shapes as the gradients, 16-byte aligned, updated in
+ *            place); a NULL entry leaves that tensor alone.  Must not alias
+ *            any gradient.  G-hat itself is not stored.
+ *   eta    : learning rate, finite. */
+int lqsgd_step_update(lqsgd_ctx* ctx, const float* const* grads, float* const* params, float eta);
+
 /* ---- taps for parity checks and for a transport layer ------------------- */
 
 /* Packet of (phase, layer, worker) as unpacked codes: mag_codes[i] in
@@ -216,7 +236,8 @@ int lqsgd_plan_query(const lqsgd_config* cfg, const lqsgd_layer* layers, int32_t
                      lqsgd_plan_info* out);
 
 /* Lists the work items of streaming sweep `sweep` (0: add + P product,
- * 1: Q product, 2: residual) as 6 int32 each: layer, worker, row0, nrows,
+ * 1: Q product, 2: residual, 3: the G-hat-only pass that runs when the
+ * residual is deferred; worker 0's shapes only) as 6 int32 each: layer, worker, row0, nrows,
  * col0, ncols.  out: host pointer with room for cap items; returns the number
  * of items (or a negative status).  Pure host computation. */
 int64_t lqsgd_plan_tiles(const lqsgd_config* cfg, const lqsgd_layer* layers, int32_t n_layers,
@@ -231,7 +252,8 @@ int64_t lqsgd_plan_tiles(const lqsgd_config* cfg, const lqsgd_layer* layers, int
 #define LQSGD_KERNEL_REDUCE_Q 4      /* reduce partials, absmax           */
 #define LQSGD_KERNEL_EXCHANGE_Q 5    /* quantise / dequantise / mean of Q */
 #define LQSGD_KERNEL_RESIDUAL 6      /* E = M - P-bar Q-bar^T and / or G-hat */
-#define LQSGD_KERNEL_COUNT 7
+#define LQSGD_KERNEL_REDUCE_P 7      /* aggregate-first order: reduce of the P partials, absmax */
+#define LQSGD_KERNEL_COUNT 8
 
 /* on != 0: every kernel launched from now on is bracketed by a pair of HIP
  * events on the context's stream (this adds a little time between kernels).

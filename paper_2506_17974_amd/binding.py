@@ -15,18 +15,18 @@ LIB_PATH = os.environ.get("LQSGD_LIB") or os.path.join(_HERE, "liblqsgd.so")
 
 OK, EINVAL, ESHAPE, EUNSUPPORTED, ENOMEM, EHIP, ESTATE = 0, -1, -2, -3, -4, -5, -6
 LAYER_MATRIX, LAYER_VECTOR = 0, 1
-FLAG_NONE, FLAG_EAGER_RESIDUAL = 0, 1
+FLAG_NONE, FLAG_EAGER_RESIDUAL, FLAG_AGGREGATE_FIRST = 0, 1, 2
 PHASE_P, PHASE_Q = 0, 1
-FACTOR_P_PRE, FACTOR_P_ORTH, FACTOR_P_BAR, FACTOR_Q_W, FACTOR_Q_BAR, FACTOR_VMEAN = range(6)
+FACTOR_P_PRE, FACTOR_P_ORTH, FACTOR_P_BAR, FACTOR_Q_W, FACTOR_Q_BAR, FACTOR_VMEAN, FACTOR_P_MEAN = range(7)
 (KERNEL_ADD_PROJECT, KERNEL_ORTH, KERNEL_EXCHANGE_P, KERNEL_BACK_PROJECT, KERNEL_REDUCE_Q,
- KERNEL_EXCHANGE_Q, KERNEL_RESIDUAL) = range(7)
-KERNEL_COUNT = 7
+ KERNEL_EXCHANGE_Q, KERNEL_RESIDUAL, KERNEL_REDUCE_P) = range(8)
+KERNEL_COUNT = 8
 MAX_RANK, MAX_WORKERS = 32, 64
 
 # every symbol the header declares
 SYMBOLS = [
     "lqsgd_create", "lqsgd_destroy", "lqsgd_synchronize", "lqsgd_last_error", "lqsgd_set_q",
-    "lqsgd_get_state", "lqsgd_set_state", "lqsgd_compress", "lqsgd_decompress", "lqsgd_step",
+    "lqsgd_get_state", "lqsgd_set_state", "lqsgd_compress", "lqsgd_decompress", "lqsgd_step", "lqsgd_step_update",
     "lqsgd_get_packet", "lqsgd_set_packet", "lqsgd_get_packet_raw", "lqsgd_get_factor",
     "lqsgd_set_factor", "lqsgd_wire_bytes", "lqsgd_plan_query", "lqsgd_plan_tiles",
     "lqsgd_timing_enable", "lqsgd_timing_read", "lqsgd_kernel_name",
@@ -81,6 +81,7 @@ def lib():
     L.lqsgd_compress.argtypes = [vp, i32, C.POINTER(vp)]
     L.lqsgd_decompress.argtypes = [vp, i32]
     L.lqsgd_step.argtypes = [vp, C.POINTER(vp), C.POINTER(vp)]
+    L.lqsgd_step_update.argtypes = [vp, C.POINTER(vp), C.POINTER(vp), C.c_float]
     L.lqsgd_get_packet.argtypes = [vp, i32, i32, i32, u8p, u8p, fp]
     L.lqsgd_set_packet.argtypes = [vp, i32, i32, i32, u8p, u8p, C.c_float]
     L.lqsgd_get_packet_raw.argtypes = [vp, i32, i32, i32, u8p, C.POINTER(i64), u8p, C.POINTER(i64)]
@@ -240,6 +241,16 @@ class Compressor:
                 gt[l] = t.data_ptr() if t is not None else None
         self._keep = (grads, ghat)
         self._check(lib().lqsgd_step(self._h, tab, gt))
+
+    def step_update(self, grads, params, eta):
+        """lqsgd_step_update: the iteration plus w <- w - eta G-hat on `params`
+        (a list over layers of device tensors or None), in place."""
+        tab = self._ptr_table(grads)
+        pt = (C.c_void_p * len(self.layers))()
+        for l, t in enumerate(params):
+            pt[l] = t.data_ptr() if t is not None else None
+        self._keep = (grads, params)
+        self._check(lib().lqsgd_step_update(self._h, tab, pt, float(eta)))
 
     def step_raw(self, tab, gt=None):
         """lqsgd_step with a pointer table made earlier by pointer_table()."""

@@ -46,7 +46,7 @@ struct lqsgd_ctx {
   // device copies of the work lists
   Tile* d_tilesA = nullptr; Tile* d_tilesB = nullptr; Tile* d_tilesG = nullptr; Tile* d_tilesBM = nullptr; Tile* d_tilesAG = nullptr;
   XTile* d_tilesXP = nullptr; XTile* d_tilesXQ = nullptr;
-  RTile* d_tilesRQ = nullptr; VTile* d_tilesV = nullptr;
+  RTile* d_tilesRQ = nullptr; RTile* d_tilesRP = nullptr; VTile* d_tilesV = nullptr;
   // pointer tables
   const float** d_grads = nullptr; float** d_ghat = nullptr;
   std::vector<const float*> h_grads; std::vector<float*> h_ghat;
@@ -181,14 +181,35 @@ int run_sweep0(lqsgd_ctx* c) {
       HIP_TRY(c, launch_add_project(c->plan.RP, c->args, c->d_tilesA, (int)c->plan.tilesA.size(), c->pending ? 1 : 0,
                                     next_dir(c), c->stream)); }
   c->pending = false;
-  { Timed t(c, LQSGD_KERNEL_ORTH);
-    HIP_TRY(c, launch_orth(c->plan.RP, c->plan.max_rows, c->plan.max_rank, c->args, c->stream)); }
+  if (c->plan.agg_first) {   // the exchange comes first: only add up the partial planes (and take the absmax)
+    Timed t(c, LQSGD_KERNEL_REDUCE_P);
+    HIP_TRY(c, launch_reduce_q(0, c->args, c->d_tilesRP, (int)c->plan.tilesRP.size(), c->stream));
+  } else {
+    Timed t(c, LQSGD_KERNEL_ORTH);
+    HIP_TRY(c, launch_orth(c->plan.RP, c->plan.max_rows, c->plan.max_rank, c->args, c->stream));
+  }
+  return LQSGD_OK;
+}
+// Aggregate-first order: Gram-Schmidt once per layer, in place on the aggregated P; the aggregate
+// as it was before goes to worker 0's slot of the (otherwise unused) per-worker Gram-Schmidt output.
+int run_orth_shared(lqsgd_ctx* c) {
+  Timed t(c, LQSGD_KERNEL_ORTH);
+  DevArgs a = c->args;
+  a.W = 1;
+  a.orth_shared = 1;
+  a.Ppart = c->args.Pbar; a.ppart_stride = 0;
+  a.Ppre = c->args.Porth;
+  a.Porth = c->args.Pbar;
+  HIP_TRY(c, launch_orth(c->plan.RP, c->plan.max_rows, c->plan.max_rank, a, c->stream));
   return LQSGD_OK;
 }
 int run_exchange(lqsgd_ctx* c, int mode, int phase) {
-  Timed t(c, phase ? LQSGD_KERNEL_EXCHANGE_Q : LQSGD_KERNEL_EXCHANGE_P);
-  const auto& tl = phase ? c->plan.tilesXQ : c->plan.tilesXP;
-  HIP_TRY(c, launch_exchange(mode, phase, c->args, phase ? c->d_tilesXQ : c->d_tilesXP, (int)tl.size(), c->stream));
+  { Timed t(c, phase ? LQSGD_KERNEL_EXCHANGE_Q : LQSGD_KERNEL_EXCHANGE_P);
+    const auto& tl = phase ? c->plan.tilesXQ : c->plan.tilesXP;
+    DevArgs a = c->args;
+    if (c->plan.agg_first && phase == 0) a.Porth = c->args.Ppre;   // the raw factors are what gets quantised
+    HIP_TRY(c, launch_exchange(mode, phase, a, phase ? c->d_tilesXQ : c->d_tilesXP, (int)tl.size(), c->stream)); }
+  if (c->plan.agg_first && phase == 0 && mode != kQuantOnly) return run_orth_shared(c);
   return LQSGD_OK;
 }
 int run_sweep1(lqsgd_ctx* c, bool with_vectors) {
@@ -201,7 +222,7 @@ int run_sweep1(lqsgd_ctx* c, bool with_vectors) {
       HIP_TRY(c, launch_back_project(c->plan.RP, c->args, c->d_tilesB, (int)c->plan.tilesB.size(), c->d_tilesV, nv,
                                      next_dir(c), c->stream)); }
   { Timed t(c, LQSGD_KERNEL_REDUCE_Q);
-    HIP_TRY(c, launch_reduce_q(c->args, c->d_tilesRQ, (int)c->plan.tilesRQ.size(), c->stream)); }
+    HIP_TRY(c, launch_reduce_q(1, c->args, c->d_tilesRQ, (int)c->plan.tilesRQ.size(), c->stream)); }
   return LQSGD_OK;
 }
 // End of an iteration: either apply E = M - P-bar Q-bar^T now (eager), or leave M
@@ -295,13 +316,14 @@ int lqsgd_plan_query(const lqsgd_config* cfg, const lqsgd_layer* layers, int32_t
 
 int64_t lqsgd_plan_tiles(const lqsgd_config* cfg, const lqsgd_layer* layers, int32_t n_layers, int32_t sweep,
                          int32_t* out, int64_t cap) {
-  if (sweep < 0 || sweep > 2) return fail(nullptr, LQSGD_EINVAL, "sweep must be 0, 1 or 2");
+  if (sweep < 0 || sweep > 3) return fail(nullptr, LQSGD_EINVAL, "sweep must be 0, 1, 2 or 3");
   Plan p;
   const int rc = p.build(cfg, layers, n_layers);
   if (rc) return fail(nullptr, rc, p.err);
   const bool bm = sweep == 1 && p.mfma;
-  const bool as0 = sweep == 0 || (sweep == 2 && p.mfma_a);     // items of sweep 0's kind
-  const std::vector<Tile>& tl = as0 ? p.tilesA : (bm ? p.tilesBM : p.tilesB);
+  const bool as0 = sweep == 0 || (sweep >= 2 && p.mfma_a);     // items of sweep 0's kind
+  const std::vector<Tile>& tl = sweep == 3 ? (p.mfma_a ? p.tilesAG : p.tilesG)
+                                           : as0 ? p.tilesA : (bm ? p.tilesBM : p.tilesB);
   if (out) {
     const int64_t n = std::min<int64_t>(cap, (int64_t)tl.size());
     for (int64_t i = 0; i < n; ++i) {
@@ -356,6 +378,7 @@ int lqsgd_create(const lqsgd_config* cfg, const lqsgd_layer* layers, int32_t n_l
   DevArgs& a = c->args;
   a.W = p.W; a.L = p.L; a.n_all = p.n_all; a.bits_p = p.cfg.bits_p; a.bits_q = p.cfg.bits_q;
   a.alpha = p.cfg.alpha;
+  a.agg_first = p.agg_first ? 1 : 0; a.orth_shared = 0; a.update = 0; a.eta = 0.0f;
   a.qscale_p = (float)(((1 << p.cfg.bits_p) - 1) / std::log2(1.0 + (double)p.cfg.alpha));
   a.qscale_q = (float)(((1 << p.cfg.bits_q) - 1) / std::log2(1.0 + (double)p.cfg.alpha));
   a.m_stride = p.m_stride; a.p_stride = p.p_stride; a.q_stride = p.q_stride;
@@ -397,6 +420,7 @@ int lqsgd_create(const lqsgd_config* cfg, const lqsgd_layer* layers, int32_t n_l
   TRY_(dev_upload(c, &c->d_tilesXP, p.tilesXP));
   TRY_(dev_upload(c, &c->d_tilesXQ, p.tilesXQ));
   TRY_(dev_upload(c, &c->d_tilesRQ, p.tilesRQ));
+  TRY_(dev_upload(c, &c->d_tilesRP, p.tilesRP));
   TRY_(dev_upload(c, &c->d_tilesV, p.tilesV));
   TRY_(dev_alloc(c, &c->d_grads, W * p.n_all, true));
   TRY_(dev_alloc(c, &c->d_ghat, (size_t)p.n_all, true));
@@ -510,8 +534,29 @@ int lqsgd_decompress(lqsgd_ctx* c, int32_t phase) {
   return fail(c, LQSGD_EINVAL, "phase must be LQSGD_PHASE_P or LQSGD_PHASE_Q");
 }
 
+namespace {
+int step_impl(lqsgd_ctx* c, const float* const* grads, float* const* ghat);
+}
+
 int lqsgd_step(lqsgd_ctx* c, const float* const* grads, float* const* ghat) {
   if (!c) return fail(nullptr, LQSGD_EINVAL, "NULL context");
+  return step_impl(c, grads, ghat);
+}
+
+int lqsgd_step_update(lqsgd_ctx* c, const float* const* grads, float* const* params, float eta) {
+  if (!c) return fail(nullptr, LQSGD_EINVAL, "NULL context");
+  if (!params) return fail(c, LQSGD_EINVAL, "NULL parameter list");
+  if (!std::isfinite(eta)) return fail(c, LQSGD_EINVAL, "eta must be finite");
+  c->args.update = 1;
+  c->args.eta = eta;
+  const int rc = step_impl(c, grads, params);
+  c->args.update = 0;
+  c->args.eta = 0.0f;
+  return rc;
+}
+
+namespace {
+int step_impl(lqsgd_ctx* c, const float* const* grads, float* const* ghat) {
   if (c->state != kIdle) return fail(c, LQSGD_ESTATE, "a staged iteration is in progress");
   if (!grads) return fail(c, LQSGD_EINVAL, "NULL gradient list");
   int rc;
@@ -522,7 +567,7 @@ int lqsgd_step(lqsgd_ctx* c, const float* const* grads, float* const* ghat) {
     for (int i = 0; i < c->plan.n_all; ++i)
       if (ghat[i])
         for (size_t j = 0; j < n; ++j)
-          if (grads[j] == ghat[i]) return fail(c, LQSGD_EINVAL, "a G-hat pointer aliases a gradient");
+          if (grads[j] == ghat[i]) return fail(c, LQSGD_EINVAL, "an output pointer aliases a gradient");
   }
   if ((rc = run_sweep0(c))) return rc;
   if ((rc = run_exchange(c, kFused, 0))) return rc;
@@ -531,6 +576,7 @@ int lqsgd_step(lqsgd_ctx* c, const float* const* grads, float* const* ghat) {
   if ((rc = run_sweep2(c, ghat != nullptr))) return rc;
   return LQSGD_OK;
 }
+}  // namespace
 
 int lqsgd_get_packet_raw(lqsgd_ctx* c, int32_t phase, int32_t layer, int32_t worker, uint8_t* mag_plane,
                          int64_t* mag_len, uint8_t* sign_plane, int64_t* sign_len) {
@@ -618,7 +664,12 @@ int lqsgd_get_factor(lqsgd_ctx* c, int32_t which, int32_t layer, int32_t worker,
   size_t n = 0;
   const bool per_worker = which == LQSGD_FACTOR_P_PRE || which == LQSGD_FACTOR_P_ORTH || which == LQSGD_FACTOR_Q_W;
   if (per_worker && (rc = check_worker(c, worker))) return rc;
+  if (which == LQSGD_FACTOR_P_ORTH && c->plan.agg_first)
+    return fail(c, LQSGD_EINVAL, "no per-worker Gram-Schmidt output in the aggregate-first order");
+  if (which == LQSGD_FACTOR_P_MEAN && !c->plan.agg_first)
+    return fail(c, LQSGD_EINVAL, "LQSGD_FACTOR_P_MEAN exists in the aggregate-first order only");
   switch (which) {
+    case LQSGD_FACTOR_P_MEAN: src = a.Porth + ld->p_off; n = ld->np_el; break;
     case LQSGD_FACTOR_P_PRE: src = a.Ppre + (size_t)worker * a.p_stride + ld->p_off; n = ld->np_el; break;
     case LQSGD_FACTOR_P_ORTH: src = a.Porth + (size_t)worker * a.p_stride + ld->p_off; n = ld->np_el; break;
     case LQSGD_FACTOR_P_BAR: src = a.Pbar + ld->p_off; n = ld->np_el; break;
@@ -681,6 +732,7 @@ const char* lqsgd_kernel_name(int32_t kernel) {
     case LQSGD_KERNEL_REDUCE_Q: return "reduce_q_kernel";
     case LQSGD_KERNEL_EXCHANGE_Q: return "exchange_kernel";
     case LQSGD_KERNEL_RESIDUAL: return "residual_kernel";
+    case LQSGD_KERNEL_REDUCE_P: return "reduce_p_kernel";
     default: return "";
   }
 }

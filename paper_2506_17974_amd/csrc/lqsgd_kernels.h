@@ -33,6 +33,10 @@ struct DevArgs {
   int32_t W, L, n_all, bits_p, bits_q;
   float alpha;                 // log scale of Eq. (5)
   float qscale_p, qscale_q;    // (2^b - 1) / log2(1 + alpha) for b_p, b_q
+  int32_t agg_first;           // aggregate-first order: scaleP is an atomic-max accumulator (sweep 0 zeroes it)
+  int32_t orth_shared;         // the Gram-Schmidt kernels run once per layer, in place on the plane at Ppart + p_off
+  int32_t update;              // G-hat outputs are parameters to update: w <- w - eta G-hat
+  float eta;
 };
 
 enum ExchangeMode { kQuantOnly = 0, kMeanOnly = 1, kFused = 2 };
@@ -52,7 +56,9 @@ hipError_t launch_back_project(int RP, const DevArgs& a, const Tile* tiles, int 
 // The same sweep on the matrix cores (rank pad 16 or 32; tiles are row block x 128-column group).
 hipError_t launch_back_project_mfma(const DevArgs& a, const Tile* tiles, int ntiles, const VTile* vtiles, int nvtiles,
                                     int reverse, hipStream_t s);
-hipError_t launch_reduce_q(const DevArgs& a, const RTile* tiles, int ntiles, hipStream_t s);
+// phase 1: Q_w from sweep 1's row-block planes; phase 0: the raw P_w from sweep 0's column-segment
+// planes (aggregate-first order, where the exchange comes before Gram-Schmidt).
+hipError_t launch_reduce_q(int phase, const DevArgs& a, const RTile* tiles, int ntiles, hipStream_t s);
 // mode: 0 = residual for all workers, 1 = residual + G-hat, 2 = G-hat only (tiles of worker 0).
 hipError_t launch_residual(int RP, int mode, const DevArgs& a, const Tile* tiles, int ntiles, int reverse, hipStream_t s);
 

@@ -109,6 +109,20 @@ __device__ __forceinline__ void strow<1, true>(char* rowbase, unsigned boff, con
 
 // Factor slice of VEC consecutive columns starting at column c of a cols x r
 // row-major factor F, as s[v*RP + k].  EXACT (r == RP) is the fast path.
+// Output of the reconstruction G-hat = P-bar Q-bar^T (Eq. (7)): either stored as it is, or applied
+// to the caller's parameters, w <- w - eta G-hat (Algorithm 1, "Model update"; Eq. (2)).
+template <int V>
+__device__ __forceinline__ void emit_ghat(float* __restrict__ rowbase, unsigned boff, Pk<V> gh, int update, float eta) {
+  if (update) {
+    const Pk<V> w = ldrow<V, false>(reinterpret_cast<const char*>(rowbase), boff);
+#pragma unroll
+    for (int v = 0; v < V; ++v) gh.v[v] = fmaf(-eta, gh.v[v], w.v[v]);
+    strow<V, false>(reinterpret_cast<char*>(rowbase), boff, gh);
+  } else {
+    strow<V, true>(reinterpret_cast<char*>(rowbase), boff, gh);
+  }
+}
+
 template <int RP, int VEC, bool EXACT>
 __device__ __forceinline__ void load_slice(const float* __restrict__ F, int c, int r, float (&s)[VEC * RP]) {
   if constexpr (EXACT) {
@@ -329,6 +343,8 @@ __global__ __launch_bounds__(256, LQSGD_A_WAVES) void add_project_kernel(DevArgs
   constexpr int RT = (RP <= 8) ? LQSGD_RT : 4;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int lane = threadIdx.x & (kWave - 1);
+  if (a.agg_first && blockIdx.x == 0)   // absmax accumulators of the reduce of the P partials start from zero
+    for (int i = threadIdx.x; i < a.W * a.L; i += 256) a.scaleP[i] = 0.0f;
   const int t = blockIdx.x * 4 + wave;
   if (t >= ntiles) return;
   const Tile tl = tiles[reverse ? ntiles - 1 - t : t];
@@ -359,6 +375,9 @@ __global__ __launch_bounds__(256, LQSGD_A_WAVES) void add_project_kernel(DevArgs
 // in the same order as the left-looking form.  One workgroup per (layer,
 // worker); a lane owns rows tid, tid+256, ... through all passes, so the only
 // communication is the block-wide sums.  Ends with absmax(P_w) -> scaleP.
+// In the aggregate-first order (orth_shared) the same kernels run once per layer
+// on the aggregated factor: input = one plane at P-bar, output in place, the
+// un-orthonormalised aggregate kept where `Ppre` points, no absmax.
 // ---------------------------------------------------------------------------
 template <int RP>
 __global__ __launch_bounds__(256) void orth_kernel(DevArgs a) {
@@ -367,9 +386,9 @@ __global__ __launch_bounds__(256) void orth_kernel(DevArgs a) {
   const int lw = blockIdx.x;
   const int layer = lw / a.W, worker = lw - layer * a.W;
   const LayerDesc& ld = a.layers[layer];
-  const int rows = ld.rows, r = ld.r, nseg = ld.nseg;
+  const int rows = ld.rows, r = ld.r, nseg = a.orth_shared ? 1 : ld.nseg;
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
-  const float* Pp = a.Ppart + (size_t)worker * a.ppart_stride + ld.ppart_off;
+  const float* Pp = a.Ppart + (size_t)worker * a.ppart_stride + (a.orth_shared ? ld.p_off : ld.ppart_off);
   float* pre = a.Ppre + (size_t)worker * a.p_stride + ld.p_off;
   float* orth = a.Porth + (size_t)worker * a.p_stride + ld.p_off;
 
@@ -435,7 +454,8 @@ __global__ __launch_bounds__(256) void orth_kernel(DevArgs a) {
   mx = wave_max(mx);
   if (lane == 0) redmax[wave] = mx;
   __syncthreads();
-  if (tid == 0) a.scaleP[(size_t)worker * a.L + layer] = fmaxf(fmaxf(redmax[0], redmax[1]), fmaxf(redmax[2], redmax[3]));
+  if (tid == 0 && !a.orth_shared)
+    a.scaleP[(size_t)worker * a.L + layer] = fmaxf(fmaxf(redmax[0], redmax[1]), fmaxf(redmax[2], redmax[3]));
 }
 
 // ---------------------------------------------------------------------------
@@ -452,10 +472,10 @@ __global__ __launch_bounds__(BS) void orth_reg_kernel(DevArgs a) {
   const int lw = blockIdx.x;
   const int layer = lw / a.W, worker = lw - layer * a.W;
   const LayerDesc& ld = a.layers[layer];
-  const int rows = ld.rows, r = ld.r, nseg = ld.nseg;
+  const int rows = ld.rows, r = ld.r, nseg = a.orth_shared ? 1 : ld.nseg;
   const bool exact = (r == RP);
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
-  const float* Pp = a.Ppart + (size_t)worker * a.ppart_stride + ld.ppart_off;
+  const float* Pp = a.Ppart + (size_t)worker * a.ppart_stride + (a.orth_shared ? ld.p_off : ld.ppart_off);
   float* pre = a.Ppre + (size_t)worker * a.p_stride + ld.p_off;
   float* orth = a.Porth + (size_t)worker * a.p_stride + ld.p_off;
 
@@ -527,7 +547,7 @@ __global__ __launch_bounds__(BS) void orth_reg_kernel(DevArgs a) {
   mx = wave_max(mx);
   if (lane == 0) redmax[wave] = mx;
   __syncthreads();
-  if (tid == 0) {
+  if (tid == 0 && !a.orth_shared) {
     float m = redmax[0];
 #pragma unroll
     for (int wv = 1; wv < NW; ++wv) m = fmaxf(m, redmax[wv]);
@@ -566,10 +586,11 @@ __global__ __launch_bounds__(256) void orth_wide_kernel(DevArgs a, int j, int ns
 #pragma unroll
   for (int k = 0; k < RP; ++k) v[k] = 0.0f;
   if (j == 0) {
-    if (slice == 0 && tid == 0) a.scaleP[(size_t)worker * a.L + layer] = 0.0f;
+    if (slice == 0 && tid == 0 && !a.orth_shared) a.scaleP[(size_t)worker * a.L + layer] = 0.0f;
     if (live) {
-      const float* Pp = a.Ppart + (size_t)worker * a.ppart_stride + ld.ppart_off;
-      for (int s = 0; s < ld.nseg; ++s) {
+      const float* Pp = a.Ppart + (size_t)worker * a.ppart_stride + (a.orth_shared ? ld.p_off : ld.ppart_off);
+      const int nseg = a.orth_shared ? 1 : ld.nseg;
+      for (int s = 0; s < nseg; ++s) {
         const float* src = Pp + (size_t)s * ld.np_pad + (size_t)row * r;
 #pragma unroll
         for (int k = 0; k < RP; ++k)
@@ -639,7 +660,7 @@ __global__ __launch_bounds__(256) void orth_wide_kernel(DevArgs a, int j, int ns
     mx = wave_max(mx);
     if (lane == 0) redmax[wave] = mx;
     __syncthreads();
-    if (tid == 0) {
+    if (tid == 0 && !a.orth_shared) {
       const float m = fmaxf(fmaxf(redmax[0], redmax[1]), fmaxf(redmax[2], redmax[3]));
       atomicMax(reinterpret_cast<unsigned int*>(a.scaleP + (size_t)worker * a.L + layer), __float_as_uint(m));
     }
@@ -895,7 +916,7 @@ __device__ __forceinline__ void vector_mean_tile(const DevArgs& a, const VTile& 
       for (int w = 0; w < a.W; ++w) s += a.grads[(size_t)w * a.n_all + vd.gidx][e];
       s /= wf;
       a.vmean[vd.off + e] = s;
-      if (extra) extra[e] = s;
+      if (extra) extra[e] = a.update ? fmaf(-a.eta, s, extra[e]) : s;
     }
   }
 }
@@ -1025,7 +1046,7 @@ __global__ __launch_bounds__(256) void back_project_mfma_kernel(DevArgs a, const
 // atomic max on the float's bit pattern (non-negative floats order like
 // unsigned integers), which is exact and order-independent.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void reduce_q_kernel(DevArgs a, const RTile* __restrict__ tiles) {
+__global__ __launch_bounds__(256) void reduce_q_kernel(DevArgs a, const RTile* __restrict__ tiles, int phase) {
   __shared__ float redmax[4];
   const RTile tl = tiles[blockIdx.x];
   const int layer = tl.lw / a.W, worker = tl.lw - layer * a.W;
@@ -1033,15 +1054,22 @@ __global__ __launch_bounds__(256) void reduce_q_kernel(DevArgs a, const RTile* _
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
   const int e = tl.el0 + tid * 4;
   float mx = 0.0f;
-  if (e < ld.nq_el) {
-    const float* Qp = a.Qpart + (size_t)worker * a.qpart_stride + ld.qpart_off + e;
+  // phase 1: Q_w from the row-block planes; phase 0 (aggregate-first order only): the raw P_w from
+  // the column-segment planes, which is then what the P exchange quantises
+  const int n_el = phase ? ld.nq_el : ld.np_el;
+  if (e < n_el) {
+    const float* Qp = phase ? a.Qpart + (size_t)worker * a.qpart_stride + ld.qpart_off + e
+                            : a.Ppart + (size_t)worker * a.ppart_stride + ld.ppart_off + e;
+    const int nplanes = phase ? ld.nrb : ld.nseg;
+    const size_t pitch = phase ? ld.nq_pad : ld.np_pad;
     float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int rb = 0; rb < ld.nrb; ++rb) {
-      const float4 t = *reinterpret_cast<const float4*>(Qp + (size_t)rb * ld.nq_pad);
+    for (int rb = 0; rb < nplanes; ++rb) {
+      const float4 t = *reinterpret_cast<const float4*>(Qp + (size_t)rb * pitch);
       s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
     }
-    float* dst = a.Qw + (size_t)worker * a.q_stride + ld.q_off + e;
-    const int nv = min(4, ld.nq_el - e);
+    float* dst = phase ? a.Qw + (size_t)worker * a.q_stride + ld.q_off + e
+                       : a.Ppre + (size_t)worker * a.p_stride + ld.p_off + e;
+    const int nv = min(4, n_el - e);
     const float vals[4] = {s.x, s.y, s.z, s.w};
 #pragma unroll
     for (int i = 0; i < 4; ++i)
@@ -1055,7 +1083,8 @@ __global__ __launch_bounds__(256) void reduce_q_kernel(DevArgs a, const RTile* _
   __syncthreads();
   if (tid == 0) {
     const float m = fmaxf(fmaxf(redmax[0], redmax[1]), fmaxf(redmax[2], redmax[3]));
-    atomicMax(reinterpret_cast<unsigned int*>(a.scaleQ + (size_t)worker * a.L + layer), __float_as_uint(m));
+    atomicMax(reinterpret_cast<unsigned int*>((phase ? a.scaleQ : a.scaleP) + (size_t)worker * a.L + layer),
+              __float_as_uint(m));
   }
 }
 
@@ -1073,7 +1102,7 @@ enum ResidualMode { kResidual = 0, kResidualGhat = 1, kGhatOnly = 2 };
 template <int RP, int VEC, bool EXACT, int MODE>
 __device__ __forceinline__ void residual_rows(float* __restrict__ M, const float* Pb, float* __restrict__ ghat,
                                               int cols, int r, int ra, int rb, unsigned boff,
-                                              const float (&q)[VEC * RP]) {
+                                              const float (&q)[VEC * RP], int update, float eta) {
   constexpr int U = 8;
   for (int i = ra; i < rb; i += U) {
     const int nu = min(U, rb - i);
@@ -1083,6 +1112,17 @@ __device__ __forceinline__ void residual_rows(float* __restrict__ M, const float
       for (int u = 0; u < U; ++u) {
         if (u < nu) {
           m[u] = ldrow<VEC, LQSGD_NT_M != 0>(reinterpret_cast<const char*>(M + (size_t)(i + u) * cols), boff);
+        } else {
+#pragma unroll
+          for (int v = 0; v < VEC; ++v) m[u].v[v] = 0.0f;
+        }
+      }
+    } else if (update) {
+      // the parameters this pass updates, fetched for all U rows before the arithmetic starts
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        if (u < nu) {
+          m[u] = ldrow<VEC, true>(reinterpret_cast<const char*>(ghat + (size_t)(i + u) * cols), boff);
         } else {
 #pragma unroll
           for (int v = 0; v < VEC; ++v) m[u].v[v] = 0.0f;
@@ -1105,8 +1145,15 @@ __device__ __forceinline__ void residual_rows(float* __restrict__ M, const float
         }
         if constexpr (MODE != kGhatOnly)
           strow<VEC, LQSGD_NT_ST_C != 0>(reinterpret_cast<char*>(M + (size_t)(i + u) * cols), boff, e);
-        if (MODE == kGhatOnly || (MODE == kResidualGhat && ghat))
+        if constexpr (MODE == kGhatOnly) {
+          if (update) {
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) gh.v[v] = fmaf(-eta, gh.v[v], m[u].v[v]);
+          }
           strow<VEC, true>(reinterpret_cast<char*>(ghat + (size_t)(i + u) * cols), boff, gh);
+        } else if (MODE == kResidualGhat && ghat) {
+          emit_ghat<VEC>(ghat + (size_t)(i + u) * cols, boff, gh, update, eta);
+        }
       }
     }
   }
@@ -1126,7 +1173,7 @@ __device__ __forceinline__ void residual_tile(const DevArgs& a, const LayerDesc&
   const int rb = min(ra + per, tl.row0 + tl.nrows);
   float q[NV];
   load_slice<RP, VEC, EXACT>(a.Qbar + ld.q_off, c, r, q);
-  residual_rows<RP, VEC, EXACT, MODE>(M, Pb, ghat, cols, r, ra, rb, (unsigned)c * 4u, q);
+  residual_rows<RP, VEC, EXACT, MODE>(M, Pb, ghat, cols, r, ra, rb, (unsigned)c * 4u, q, a.update, a.eta);
 }
 
 template <int RP, int MODE>
@@ -1186,7 +1233,7 @@ template <int RP, int MODE, bool EXACT>
 __device__ __forceinline__ void mfma_tile(const float* __restrict__ G, float* __restrict__ M,
                                           const float* Q, const float* Pb, float* __restrict__ Pp,
                                           float* __restrict__ ghat_out, int cols, int r, int row0, int nrows,
-                                          int col0, int col1, int lane, float* lds) {
+                                          int col0, int col1, int lane, float* lds, int update, float eta) {
   constexpr bool ADD = (MODE == kMAdd || MODE == kMAddFused);
   constexpr bool NEEDG = (MODE != kMAdd);
   constexpr bool HASM = (MODE != kMGhatOnly);
@@ -1288,7 +1335,7 @@ __device__ __forceinline__ void mfma_tile(const float* __restrict__ G, float* __
         if (MODE == kMGhatOnly || (MODE == kMResidualGhat && ghat_out)) {
           if (colok && rr < nrows) {
             const Pk<4> o{{t.x, t.y, t.z, t.w}};
-            strow<4, true>(reinterpret_cast<char*>(ghat_out + (size_t)(row0 + rr) * cols), (unsigned)cl * 4u, o);
+            emit_ghat<4>(ghat_out + (size_t)(row0 + rr) * cols, (unsigned)cl * 4u, o, update, eta);
           }
         }
       }
@@ -1352,7 +1399,7 @@ __device__ __forceinline__ void mfma_mode_vector_fallback(const DevArgs& a, cons
       float q[RP];
       load_slice<RP, 1, false>(a.Qbar + ld.q_off, c, ld.r, q);
       residual_rows<RP, 1, false, RM>(M, a.Pbar + ld.p_off, ghat_out, ld.cols, ld.r, tl.row0, tl.row0 + tl.nrows,
-                                      (unsigned)c * 4u, q);
+                                      (unsigned)c * 4u, q, a.update, a.eta);
     }
   }
 }
@@ -1362,6 +1409,8 @@ __global__ __launch_bounds__(256) void mfma_sweep_kernel(DevArgs a, const Tile* 
   __shared__ __attribute__((aligned(16))) float lds_all[4][32 * kLP];
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int lane = threadIdx.x & (kWave - 1);
+  if ((MODE == kMAdd || MODE == kMAddFused) && a.agg_first && blockIdx.x == 0)
+    for (int i = threadIdx.x; i < a.W * a.L; i += 256) a.scaleP[i] = 0.0f;
   const int t = blockIdx.x * 4 + wave;
   if (t >= ntiles) return;
   const Tile tl = tiles[reverse ? ntiles - 1 - t : t];
@@ -1382,10 +1431,10 @@ __global__ __launch_bounds__(256) void mfma_sweep_kernel(DevArgs a, const Tile* 
   float* lds = lds_all[wave];
   if (ld.r == RP)
     mfma_tile<RP, MODE, true>(G, M, a.Qbar + ld.q_off, a.Pbar + ld.p_off, Pp, ghat_out, ld.cols, ld.r, tl.row0,
-                              tl.nrows, col0, col1, lane, lds);
+                              tl.nrows, col0, col1, lane, lds, a.update, a.eta);
   else
     mfma_tile<RP, MODE, false>(G, M, a.Qbar + ld.q_off, a.Pbar + ld.p_off, Pp, ghat_out, ld.cols, ld.r, tl.row0,
-                               tl.nrows, col0, col1, lane, lds);
+                               tl.nrows, col0, col1, lane, lds, a.update, a.eta);
 }
 
 }  // namespace
@@ -1482,9 +1531,9 @@ hipError_t launch_back_project_mfma(const DevArgs& a, const Tile* tiles, int nti
   return hipGetLastError();
 }
 
-hipError_t launch_reduce_q(const DevArgs& a, const RTile* tiles, int ntiles, hipStream_t s) {
+hipError_t launch_reduce_q(int phase, const DevArgs& a, const RTile* tiles, int ntiles, hipStream_t s) {
   if (ntiles <= 0) return hipSuccess;
-  reduce_q_kernel<<<dim3(ntiles), dim3(256), 0, s>>>(a, tiles);
+  reduce_q_kernel<<<dim3(ntiles), dim3(256), 0, s>>>(a, tiles, phase);
   return hipGetLastError();
 }
 

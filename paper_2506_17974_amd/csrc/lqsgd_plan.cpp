@@ -57,12 +57,13 @@ int Plan::build(const lqsgd_config* c, const lqsgd_layer* ls, int32_t n_layers) 
     return LQSGD_EINVAL;
   }
   if (!(c->alpha > 0.0f) || !std::isfinite(c->alpha)) { err = "alpha must be finite and > 0"; return LQSGD_EINVAL; }
-  if (c->flags & ~LQSGD_FLAG_EAGER_RESIDUAL) { err = "unknown config flags"; return LQSGD_EINVAL; }
+  if (c->flags & ~(LQSGD_FLAG_EAGER_RESIDUAL | LQSGD_FLAG_AGGREGATE_FIRST)) { err = "unknown config flags"; return LQSGD_EINVAL; }
+  agg_first = (c->flags & LQSGD_FLAG_AGGREGATE_FIRST) != 0;
   cfg = *c;
   W = c->workers;
   n_all = n_layers;
   layers.clear(); vecs.clear(); kind_of.clear();
-  tilesA.clear(); tilesAG.clear(); tilesB.clear(); tilesBM.clear(); tilesG.clear(); tilesXP.clear(); tilesXQ.clear(); tilesRQ.clear(); tilesV.clear();
+  tilesA.clear(); tilesAG.clear(); tilesB.clear(); tilesBM.clear(); tilesG.clear(); tilesXP.clear(); tilesXQ.clear(); tilesRQ.clear(); tilesRP.clear(); tilesV.clear();
 
   int max_r = 1;
   max_rows = 0;
@@ -127,6 +128,8 @@ int Plan::build(const lqsgd_config* c, const lqsgd_layer* ls, int32_t n_layers) 
   const int64_t total = matrix_elements * W;
   const int64_t tgtA = env_i64("LQSGD_TILE_A", std::min<int64_t>(131072, std::max<int64_t>(4096, total / 49152)));
   const int64_t tgtB = env_i64("LQSGD_TILE_B", std::min<int64_t>(131072, std::max<int64_t>(8192, total / 2730)));
+  // the G-hat-only pass covers one worker's worth of elements: smaller items keep its grid wide
+  const int64_t tgtG = env_i64("LQSGD_TILE_G", std::min<int64_t>(tgtB, std::max<int64_t>(4096, matrix_elements / 2730)));
   const int64_t segmax4 = env_i64("LQSGD_SEGMAX", 1024);
 
   int64_t m_acc = 0, p_acc = 0, q_acc = 0, pp_acc = 0, qp_acc = 0;
@@ -182,12 +185,19 @@ int Plan::build(const lqsgd_config* c, const lqsgd_layer* ls, int32_t n_layers) 
       for (int32_t rb = 0; rb < nrb_v; ++rb)
         for (int32_t ch = 0; ch < nchunk; ++ch)
           tilesB.push_back(Tile{lw, rb * rbb_v, std::min(rbb_v, d.rows - rb * rbb_v), ch});
-      if (w == 0) tilesG.insert(tilesG.end(), tilesB.end() - (size_t)nrb_v * nchunk, tilesB.end());
+      if (w == 0) {
+        const int32_t rbg = (int32_t)std::min<int64_t>(round_up(std::max<int64_t>(1, tgtG / cw), 4), round_up(d.rows, 4));
+        for (int32_t row0 = 0; row0 < d.rows; row0 += rbg)
+          for (int32_t ch = 0; ch < nchunk; ++ch)
+            tilesG.push_back(Tile{lw, row0, std::min(rbg, d.rows - row0), ch});
+      }
       if (mfma)
         for (int32_t rb = 0; rb < d.nrb; ++rb)
           for (int32_t cg = 0; cg < (d.cols + kMfmaCols - 1) / kMfmaCols; ++cg)
             tilesBM.push_back(Tile{lw, rb * d.rbb, std::min(d.rbb, d.rows - rb * d.rbb), cg});
       for (int32_t e = 0; e < d.nq_el; e += 1024) tilesRQ.push_back(RTile{lw, e});
+      if (agg_first)
+        for (int32_t e = 0; e < d.np_el; e += 1024) tilesRP.push_back(RTile{lw, e});
     }
     for (int32_t g = 0; g < gp; g += kXBlockGroups) tilesXP.push_back(XTile{li, g});
     for (int32_t g = 0; g < gq; g += kXBlockGroups) tilesXQ.push_back(XTile{li, g});
@@ -212,7 +222,7 @@ int Plan::build(const lqsgd_config* c, const lqsgd_layer* ls, int32_t n_layers) 
 
   const int64_t tile_bytes = (int64_t)(tilesA.size() + tilesAG.size() + tilesB.size() + tilesBM.size() + tilesG.size()) * sizeof(Tile) +
                              (int64_t)(tilesXP.size() + tilesXQ.size()) * sizeof(XTile) +
-                             (int64_t)tilesRQ.size() * sizeof(RTile) + (int64_t)tilesV.size() * sizeof(VTile);
+                             (int64_t)(tilesRQ.size() + tilesRP.size()) * sizeof(RTile) + (int64_t)tilesV.size() * sizeof(VTile);
   device_bytes = 4 * ((int64_t)W * (m_stride + 2 * p_stride + q_stride + ppart_stride + qpart_stride) +
                       p_stride + q_stride + v_total + 2 * (int64_t)W * std::max(L, 1) +
                       2 * (int64_t)W * std::max(L, 1) * ((max_rows + 255) / 256) * RP) +

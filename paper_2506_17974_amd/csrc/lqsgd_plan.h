@@ -75,6 +75,8 @@ struct Plan {
   std::vector<Tile> tilesG;        // worker 0's items of tilesB: one pass over every layer (G-hat only)
   std::vector<XTile> tilesXP, tilesXQ;
   std::vector<RTile> tilesRQ;
+  std::vector<RTile> tilesRP;      // aggregate-first order: reduce of the P partials (1024 elements each)
+  bool agg_first = false;          // LQSGD_FLAG_AGGREGATE_FIRST
   std::vector<VTile> tilesV;
   int64_t m_stride = 0, p_stride = 0, q_stride = 0, ppart_stride = 0, qpart_stride = 0;
   int64_t magp_stride = 0, sgnp_stride = 0, magq_stride = 0, sgnq_stride = 0, v_total = 0;

@@ -76,7 +76,7 @@ class StageReport:
 
 
 def staged_iteration(comp: B.Compressor, G_host, G_dev, E_host, Q_host, matrix_layers, rep: StageReport,
-                     layers_to_check=None, workers_to_check=None):
+                     layers_to_check=None, workers_to_check=None, aggregate_first=False):
     """One iteration through compress/decompress with every stage checked.
 
     G_host[w][l], E_host[w][l] (state before the iteration), Q_host[l]: numpy.
@@ -84,6 +84,8 @@ def staged_iteration(comp: B.Compressor, G_host, G_dev, E_host, Q_host, matrix_l
     G_host / E_host / Q_host are indexed by position in that list.
     layers_to_check / workers_to_check restrict the comparison (and the copies
     to the host) to a sample; entries of G_host / E_host outside it may be None.
+    aggregate_first: the compressor was created with FLAG_AGGREGATE_FIRST (the
+    raw P_w is exchanged, the aggregate is orthonormalised once).
     Returns (E_new[w][l], Q_bar[l]) as read back from the device (None outside
     the sample).
     """
@@ -99,39 +101,50 @@ def staged_iteration(comp: B.Compressor, G_host, G_dev, E_host, Q_host, matrix_l
         for w in Ws:
             m_gpu, _ = comp.get_state(l, w, want_q=False)
             M[(li, w)] = m_gpu
-            if True:
-                # G' = G + E: one IEEE addition per element, must be bit-exact
-                assert np.array_equal(m_gpu, (G_host[w][li].astype(f64) + E_host[w][li].astype(f64)).astype(f32))
-                p_pre = comp.get_factor(B.FACTOR_P_PRE, l, w)
-                want = m_gpu.astype(f64) @ Q_host[li].astype(f64)
-                rep.note("P_pre", rel_fro(p_pre, want))
-                assert rel_fro(p_pre, want) <= FP_TOL
+            # G' = G + E: one IEEE addition per element, must be bit-exact
+            assert np.array_equal(m_gpu, (G_host[w][li].astype(f64) + E_host[w][li].astype(f64)).astype(f32))
+            p_pre = comp.get_factor(B.FACTOR_P_PRE, l, w)
+            want = m_gpu.astype(f64) @ Q_host[li].astype(f64)
+            rep.note("P_pre", rel_fro(p_pre, want))
+            assert rel_fro(p_pre, want) <= FP_TOL
+            if aggregate_first:
+                sent = p_pre              # the raw factor goes on the wire, Gram-Schmidt follows the exchange
+            else:
                 p_orth = comp.get_factor(B.FACTOR_P_ORTH, l, w)
                 want = orc.orthonormalize(p_pre)
                 # columns whose residual is rounding noise have no defined direction
                 ok = _well_defined_columns(p_pre)
                 rep.note("P_orth", rel_fro(p_orth[:, ok], want[:, ok]))
                 assert rel_fro(p_orth[:, ok], want[:, ok]) <= FP_TOL
-                if bp:
-                    k, sg, sc = comp.get_packet(B.PHASE_P, l, w)
-                    rep.code_flips += check_codes(p_orth, k, sg, sc, bp, alpha)
-                    rep.code_elems += k.size
-                    mag, sgn = comp.get_packet_raw(B.PHASE_P, l, w)
-                    om, os_ = orc.pack_packet(k, sg, bp)
-                    assert np.array_equal(mag, om) and np.array_equal(sgn, os_)
+                sent = p_orth
+            if bp:
+                k, sg, sc = comp.get_packet(B.PHASE_P, l, w)
+                rep.code_flips += check_codes(sent, k, sg, sc, bp, alpha)
+                rep.code_elems += k.size
+                mag, sgn = comp.get_packet_raw(B.PHASE_P, l, w)
+                om, os_ = orc.pack_packet(k, sg, bp)
+                assert np.array_equal(mag, om) and np.array_equal(sgn, os_)
     comp.decompress(B.PHASE_P)
     Pbar = {}
     for li in Ls:
         l = matrix_layers[li]
-        pb = comp.get_factor(B.FACTOR_P_BAR, l)
-        Pbar[li] = pb
+        pb = comp.get_factor(B.FACTOR_P_MEAN if aggregate_first else B.FACTOR_P_BAR, l)
         if bp:
             pk = [comp.get_packet(B.PHASE_P, l, w) for w in range(W)]
             want = orc.mean_of_packets(pk, bp, alpha)
         else:
-            want = np.mean(np.stack([comp.get_factor(B.FACTOR_P_ORTH, l, w).astype(f64) for w in range(W)]), axis=0)
+            which = B.FACTOR_P_PRE if aggregate_first else B.FACTOR_P_ORTH
+            want = np.mean(np.stack([comp.get_factor(which, l, w).astype(f64) for w in range(W)]), axis=0)
         rep.note("P_bar", rel_fro(pb, want))
         assert rel_fro(pb, want) <= MEAN_TOL
+        if aggregate_first:
+            p_hat = comp.get_factor(B.FACTOR_P_BAR, l)
+            want = orc.orthonormalize(pb)
+            ok = _well_defined_columns(pb)
+            rep.note("P_hat", rel_fro(p_hat[:, ok], want[:, ok]))
+            assert rel_fro(p_hat[:, ok], want[:, ok]) <= FP_TOL
+            pb = p_hat
+        Pbar[li] = pb
     comp.compress(B.PHASE_Q)
     for li in Ls:
         l = matrix_layers[li]

@@ -1,0 +1,208 @@
+"""GPU parity of the two variants around Algorithm 1: the PowerSGD order of
+Section 3.2 (aggregate, then orthonormalise) and the fused model update
+w <- w - eta G-hat (Algorithm 1, last statement).  Needs a real MI355X."""
+import zlib
+
+import numpy as np
+import pytest
+
+import oracle.lqsgd_oracle as orc
+from paper_2506_17974_amd import binding as B
+from tests import parity_utils as pu
+
+pytestmark = pytest.mark.gpu
+f32, f64 = np.float32, np.float64
+
+
+def _say(*a):
+    print(*a, flush=True)
+
+
+def _inputs(rng, layers, W, scale=1e-3):
+    return [[(rng.standard_normal(s) * scale).astype(f32) for s in layers] for _ in range(W)]
+
+
+AGG_CASES = [
+    # layers, rank, bits_p, bits_q, W
+    ([(256, 128)], 2, 8, 8, 2),
+    ([(5, 3), (64, 27), (32, 25)], 4, 8, 8, 4),
+    ([(300, 260)], 3, 0, 0, 3),                      # PowerSGD itself
+    ([(300, 260)], 7, 4, 4, 5),
+    ([(17, 4100)], 4, 8, 8, 2),
+    ([(2100, 132), (1000, 68)], 8, 8, 4, 2),
+    ([(129, 1028)], 16, 8, 8, 2),                    # matrix-core sweeps 0 / 2
+    ([(100, 1100), (33, 64)], 20, 8, 8, 2),          # rank pad 32
+    ([(2304, 96)], 4, 8, 8, 1),                      # one worker, tall: many-workgroup Gram-Schmidt not needed
+    ([(4608, 64)], 32, 8, 8, 2),                     # tall + rank 32: many-workgroup Gram-Schmidt on the aggregate
+]
+
+
+@pytest.mark.parametrize("case", AGG_CASES, ids=lambda c: "%s-r%d-b%d%d-W%d" % (
+    "+".join("%dx%d" % s for s in c[0]), c[1], c[2], c[3], c[4]))
+def test_aggregate_first_staged(case):
+    layers, rank, bp, bq, W = case
+    _say("case: aggregate-first", case)
+    rng = np.random.default_rng(zlib.crc32(str(case).encode()) % 1000)
+    comp = B.Compressor(B.layer_list(layers, ()), rank, bp, bq, W, 255.0, B.FLAG_AGGREGATE_FIRST)
+    ml = list(range(len(layers)))
+    Q = [rng.standard_normal((c, min(rank, r, c))).astype(f32) for r, c in layers]
+    E = [[(rng.standard_normal(s) * 3e-4).astype(f32) for s in layers] for _ in range(W)]
+    for l in ml:
+        comp.set_q(l, Q[l])
+        for w in range(W):
+            comp.set_state(l, w, e=E[w][l])
+    rep = pu.StageReport()
+    for t in range(2):
+        G = _inputs(rng, layers, W)
+        E, Q = pu.staged_iteration(comp, G, pu.to_device(G), E, Q, ml, rep, aggregate_first=True)
+    with pytest.raises(B.LqsgdError) as ei:
+        comp.get_factor(B.FACTOR_P_ORTH, 0, 0)
+    assert ei.value.code == B.EINVAL
+    comp.close()
+    _say("  ", rep)
+
+
+def test_p_mean_needs_the_flag():
+    comp = B.Compressor(B.layer_list([(16, 8)], ()), 2, 8, 8, 2)
+    with pytest.raises(B.LqsgdError) as ei:
+        comp.get_factor(B.FACTOR_P_MEAN, 0, 0)
+    assert ei.value.code == B.EINVAL
+    comp.close()
+
+
+@pytest.mark.parametrize("rank,bits,flags", [(4, 8, 0), (4, 0, 0), (16, 8, 0), (4, 8, B.FLAG_EAGER_RESIDUAL)])
+def test_aggregate_first_fused_step_equals_staged(rank, bits, flags):
+    """lqsgd_step, the staged calls, and the deferred / eager residual schedules
+    give bit-identical state and G-hat in the aggregate-first order too."""
+    import torch
+    _say("case: aggregate-first fused vs staged", rank, bits, flags)
+    layers, vectors, W = [(128, 1152), (64, 27), (70, 200)], (33,), 4
+    rng = np.random.default_rng(rank * 10 + bits)
+    ll = B.layer_list(layers, vectors)
+    a = B.Compressor(ll, rank, bits, bits, W, 255.0, B.FLAG_AGGREGATE_FIRST | flags)
+    b = B.Compressor(ll, rank, bits, bits, W, 255.0, B.FLAG_AGGREGATE_FIRST)
+    for l, (r, c) in enumerate(layers):
+        q = rng.standard_normal((c, min(rank, r, c))).astype(f32)
+        a.set_q(l, q); b.set_q(l, q)
+    for t in range(3):
+        G = [[(rng.standard_normal(s) * 1e-3).astype(f32) for s in layers] +
+             [(rng.standard_normal(v) * 1e-3).astype(f32) for v in vectors] for _ in range(W)]
+        Gd = pu.to_device(G)
+        ghat = [torch.zeros(s, device="cuda") for s in layers] + [torch.zeros(v, device="cuda") for v in vectors]
+        a.step(Gd, ghat)
+        b.compress(B.PHASE_P, Gd); b.decompress(B.PHASE_P); b.compress(B.PHASE_Q); b.decompress(B.PHASE_Q)
+        for l in range(len(layers)):
+            pa, qa = a.get_factor(B.FACTOR_P_BAR, l), a.get_factor(B.FACTOR_Q_BAR, l)
+            assert np.array_equal(pa, b.get_factor(B.FACTOR_P_BAR, l))
+            assert np.array_equal(qa, b.get_factor(B.FACTOR_Q_BAR, l))
+            assert np.array_equal(a.get_factor(B.FACTOR_P_MEAN, l), b.get_factor(B.FACTOR_P_MEAN, l))
+            want = (pa.astype(f64) @ qa.astype(f64).T)
+            got = ghat[l].cpu().numpy()
+            assert pu.rel_fro(got, want) <= pu.FP_TOL
+            for w in range(W):
+                ea, _ = a.get_state(l, w)
+                eb, _ = b.get_state(l, w)
+                assert np.array_equal(ea, eb)
+    a.close(); b.close()
+
+
+def test_powersgd_recovers_a_low_rank_mean_for_any_w():
+    """bits = 0, aggregate-first: distinct full-rank worker gradients whose mean has
+    rank r are reconstructed exactly (the property Algorithm 1's own order gives
+    up), and the result matches the oracle run on the same inputs."""
+    import torch
+    _say("case: PowerSGD exact recovery")
+    rng = np.random.default_rng(99)
+    rows, cols, r, W = 192, 320, 4, 6
+    base = rng.standard_normal((rows, r)) @ rng.standard_normal((r, cols))
+    N = [rng.standard_normal((rows, cols)) for _ in range(W)]
+    Nbar = sum(N) / W
+    G = [[(base + N[w] - Nbar).astype(f32)] for w in range(W)]
+    Mbar = sum(g[0].astype(f64) for g in G) / W
+    q0 = rng.standard_normal((cols, r)).astype(f32)
+    comp = B.Compressor(B.layer_list([(rows, cols)], ()), r, 0, 0, W, 255.0, B.FLAG_AGGREGATE_FIRST)
+    comp.set_q(0, q0)
+    ghat = [torch.zeros((rows, cols), device="cuda")]
+    comp.step(pu.to_device(G), ghat)
+    got = ghat[0].cpu().numpy()
+    assert np.linalg.norm(got - Mbar) <= 1e-5 * np.linalg.norm(Mbar)
+    want = orc.layer_step_aggregate_first([g[0] for g in G], [np.zeros((rows, cols), f32)] * W, q0, r, 0, 0, 255.0)
+    assert pu.rel_fro(got, want["G_hat"]) <= pu.FP_TOL
+    for w in range(W):
+        e, qb = comp.get_state(0, w)
+        assert pu.rel_fro(e, want["E_new"][w]) <= pu.FP_TOL
+        assert pu.rel_fro(qb, want["Q_bar"]) <= pu.FP_TOL
+    comp.close()
+
+
+def _ulp_close(got, want, frac=1e-5):
+    """Equal up to one float32 ulp, on at most `frac` of the elements (the oracle
+    rounds a float64 result to float32, the kernel rounds a fused multiply-add once)."""
+    got = np.asarray(got, f32); want = np.asarray(want, f32)
+    diff = got != want
+    if not diff.any():
+        return True
+    ok = np.abs(got[diff].astype(f64) - want[diff].astype(f64)) <= np.spacing(np.abs(want[diff])).astype(f64)
+    return bool(ok.all() and diff.mean() <= frac)
+
+
+@pytest.mark.parametrize("layers,rank,bits,W,flags", [
+    ([(256, 128)], 2, 8, 2, 0),
+    ([(64, 576), (128, 64), (10, 512), (33, 65)], 4, 8, 4, 0),
+    ([(64, 576), (128, 64)], 4, 8, 4, B.FLAG_EAGER_RESIDUAL),
+    ([(129, 1028), (70, 200)], 16, 8, 2, 0),                       # matrix-core G-hat pass
+    ([(96, 520)], 32, 4, 2, B.FLAG_EAGER_RESIDUAL),
+    ([(300, 260)], 3, 0, 3, B.FLAG_AGGREGATE_FIRST),
+])
+def test_model_update(layers, rank, bits, W, flags):
+    """lqsgd_step_update applies w <- w - eta G-hat with the very G-hat lqsgd_step
+    writes, leaves the compressor state identical, updates 1-D tensors with their
+    mean, and skips tensors whose parameter pointer is NULL."""
+    import torch
+    _say("case: model update", layers, rank, bits, W, flags)
+    vectors = (40, 7)
+    rng = np.random.default_rng(rank + bits + W)
+    ll = B.layer_list(layers, vectors)
+    a = B.Compressor(ll, rank, bits, bits, W, 255.0, flags)
+    b = B.Compressor(ll, rank, bits, bits, W, 255.0, flags)
+    for l, (r, c) in enumerate(layers):
+        q = rng.standard_normal((c, min(rank, r, c))).astype(f32)
+        a.set_q(l, q); b.set_q(l, q)
+    shapes = list(layers) + [(v,) for v in vectors]
+    w_host = [rng.standard_normal(s).astype(f32) for s in shapes]
+    params = [torch.from_numpy(w.copy()).cuda() for w in w_host]
+    skipped = len(layers) - 1                      # this matrix keeps its parameters
+    plist = list(params)
+    plist[skipped] = None
+    for t, eta in enumerate((0.1, 0.25, 3e-2)):
+        G = [[(rng.standard_normal(s) * 1e-1).astype(f32) for s in shapes] for _ in range(W)]
+        Gd = pu.to_device(G)
+        ghat = [torch.zeros(s, device="cuda") for s in shapes]
+        b.step(Gd, ghat)
+        a.step_update(Gd, plist, eta)
+        for i, s in enumerate(shapes):
+            got = params[i].cpu().numpy()
+            if i == skipped:
+                assert np.array_equal(got, w_host[i])
+                continue
+            want = orc.model_update(w_host[i], ghat[i].cpu().numpy(), eta)
+            assert _ulp_close(got, want), "tensor %d step %d" % (i, t)
+            w_host[i] = got
+        for l in range(len(layers)):
+            for w in range(W):
+                ea, qa = a.get_state(l, w)
+                eb, qb = b.get_state(l, w)
+                assert np.array_equal(ea, eb) and np.array_equal(qa, qb)
+        for vi, v in enumerate(vectors):
+            i = len(layers) + vi
+            assert np.array_equal(a.get_factor(B.FACTOR_VMEAN, i), b.get_factor(B.FACTOR_VMEAN, i))
+    # argument errors
+    with pytest.raises(B.LqsgdError) as ei:
+        a.step_update(Gd, plist, float("nan"))
+    assert ei.value.code == B.EINVAL
+    bad = list(plist)
+    bad[0] = Gd[0][0]
+    with pytest.raises(B.LqsgdError) as ei:
+        a.step_update(Gd, bad, 0.1)
+    assert ei.value.code == B.EINVAL
+    a.close(); b.close()

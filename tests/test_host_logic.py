@@ -34,7 +34,7 @@ def test_kernel_names():
     (dict(alpha=0.0), B.EINVAL), (dict(alpha=float("nan")), B.EINVAL),
     (dict(layers=[(0, 4, 0)]), B.ESHAPE), (dict(layers=[(4, -1, 0)]), B.ESHAPE),
     (dict(layers=[(65536, 65536, 0)]), B.ESHAPE), (dict(layers=[(8, 2, B.LAYER_VECTOR)]), B.ESHAPE),
-    (dict(layers=[(8, 2, 4)]), B.EINVAL), (dict(flags=2), B.EINVAL),
+    (dict(layers=[(8, 2, 4)]), B.EINVAL), (dict(flags=4), B.EINVAL),
 ])
 def test_plan_rejects_bad_arguments(kw, code):
     args = dict(layers=[(16, 8, 0)], rank=2, bits_p=8, bits_q=8, workers=2, alpha=255.0)
@@ -68,6 +68,21 @@ def test_work_lists_cover_each_element_once(sweep, rank):
     assert len(cover) == n_matrix * W
     for key, m in cover.items():
         assert m.min() == 1 and m.max() == 1, key
+
+
+@pytest.mark.parametrize("rank", [4, 16, 32])
+def test_ghat_pass_covers_each_layer_once(rank):
+    w = wl.small_cnn()
+    layers = B.layer_list(w.layers, w.vectors)
+    layers += [(1, 1, 0), (3, 5000, 0), (2100, 132, 0), (64, 27, 0)]
+    cover = _coverage(layers, rank, 3, 3)
+    assert sorted(cover) == [(i, 0) for i, l in enumerate(layers) if l[2] == 0]
+    for key, m in cover.items():
+        assert m.min() == 1 and m.max() == 1, key
+    rn = wl.resnet18()
+    big = _coverage(B.layer_list(rn.layers, rn.vectors), rank, 8, 3)
+    assert all(m.min() == 1 and m.max() == 1 for m in big.values())
+    assert sum(m.size for m in big.values()) == rn.elements_per_worker
 
 
 def test_plan_sizes_resnet18():
