@@ -40,6 +40,8 @@ struct lqsgd_ctx {
   bool flip = true;
   bool eager = false;       // LQSGD_FLAG_EAGER_RESIDUAL
   bool pending = false;     // E buffer holds M; E = M - P-bar Q-bar^T not applied yet
+  unsigned long long orth_epoch = 0;   // cooperative Gram-Schmidt launches so far
+  int* status = nullptr;    // pinned, device-visible: non-zero once a bounded device-side wait has expired
   std::string err;
   std::vector<void*> allocs;
   DevArgs args{};
@@ -121,6 +123,14 @@ struct Timed {
   }
 };
 
+// Waits for the context's stream and reports a device-side wait that expired.
+int sync_stream(lqsgd_ctx* c) {
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  if (c->status && *static_cast<volatile int*>(c->status) != 0)
+    return fail(c, LQSGD_EHIP, "a device-side barrier wait expired; results of this context are invalid");
+  return LQSGD_OK;
+}
+
 int check_matrix_layer(lqsgd_ctx* c, int32_t layer, const LayerDesc** out) {
   if (layer < 0 || layer >= c->plan.n_all) return fail(c, LQSGD_ESHAPE, "layer index out of range");
   const int k = c->plan.kind_of[layer];
@@ -186,7 +196,7 @@ int run_sweep0(lqsgd_ctx* c) {
     HIP_TRY(c, launch_reduce_q(0, c->args, c->d_tilesRP, (int)c->plan.tilesRP.size(), c->stream));
   } else {
     Timed t(c, LQSGD_KERNEL_ORTH);
-    HIP_TRY(c, launch_orth(c->plan.RP, c->plan.max_rows, c->plan.max_rank, c->args, c->stream));
+    HIP_TRY(c, launch_orth(c->plan.RP, c->plan.max_rows, c->plan.max_rank, c->args, &c->orth_epoch, c->stream));
   }
   return LQSGD_OK;
 }
@@ -200,7 +210,7 @@ int run_orth_shared(lqsgd_ctx* c) {
   a.Ppart = c->args.Pbar; a.ppart_stride = 0;
   a.Ppre = c->args.Porth;
   a.Porth = c->args.Pbar;
-  HIP_TRY(c, launch_orth(c->plan.RP, c->plan.max_rows, c->plan.max_rank, a, c->stream));
+  HIP_TRY(c, launch_orth(c->plan.RP, c->plan.max_rows, c->plan.max_rank, a, &c->orth_epoch, c->stream));
   return LQSGD_OK;
 }
 int run_exchange(lqsgd_ctx* c, int mode, int phase) {
@@ -367,6 +377,7 @@ int lqsgd_create(const lqsgd_config* cfg, const lqsgd_layer* layers, int32_t n_l
   auto bail = [&](int code) {
     g_create_error = c->err;
     for (void* p : c->allocs) (void)hipFree(p);
+    if (c->status) (void)hipHostFree(c->status);
     delete c;
     return code;
   };
@@ -397,6 +408,15 @@ int lqsgd_create(const lqsgd_config* cfg, const lqsgd_layer* layers, int32_t n_l
   TRY_(dev_alloc(c, &a.Ppre, W * p.p_stride, true));
   TRY_(dev_alloc(c, &a.Porth, W * p.p_stride, true));
   TRY_(dev_alloc(c, &a.orth_part, 2 * W * (size_t)std::max(p.L, 1) * ((p.max_rows + 255) / 256) * p.RP, true));
+  TRY_(dev_alloc(c, &a.orth_table, 2 * W * (size_t)std::max(p.L, 1) * ((p.max_rows + 255) / 256) * p.RP, true));
+  {
+    void* hp = nullptr;
+    hipError_t e = hipHostMalloc(&hp, sizeof(int), hipHostMallocDefault);
+    if (e != hipSuccess) { fail_hip(c, e, "hipHostMalloc"); return bail(LQSGD_ENOMEM); }
+    c->status = static_cast<int*>(hp);
+    *c->status = 0;
+    a.status = c->status;
+  }
   TRY_(dev_alloc(c, &a.Pbar, (size_t)p.p_stride, true));
   TRY_(dev_alloc(c, &a.Qpart, W * p.qpart_stride, true));
   TRY_(dev_alloc(c, &a.Qw, W * p.q_stride, true));
@@ -441,6 +461,7 @@ int lqsgd_destroy(lqsgd_ctx* c) {
   (void)hipStreamSynchronize(c->stream);
   for (EventPair& e : c->events) { (void)hipEventDestroy(e.a); (void)hipEventDestroy(e.b); }
   for (void* p : c->allocs) (void)hipFree(p);
+  if (c->status) (void)hipHostFree(c->status);
   (void)hipGetLastError();
   delete c;
   return LQSGD_OK;
@@ -448,7 +469,7 @@ int lqsgd_destroy(lqsgd_ctx* c) {
 
 int lqsgd_synchronize(lqsgd_ctx* c) {
   if (!c) return fail(nullptr, LQSGD_EINVAL, "NULL context");
-  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  if (int rcs = sync_stream(c)) return rcs;
   return LQSGD_OK;
 }
 
@@ -467,7 +488,7 @@ int lqsgd_get_state(lqsgd_ctx* c, int32_t layer, int32_t worker, float* host_e, 
   if (rc) return rc;
   if ((rc = check_worker(c, worker))) return rc;
   if (host_e && (rc = materialise(c))) return rc;
-  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  if (int rcs = sync_stream(c)) return rcs;
   if (host_e)
     HIP_TRY(c, hipMemcpy(host_e, c->args.E + (size_t)worker * c->args.m_stride + ld->m_off,
                          (size_t)ld->rows * ld->cols * sizeof(float), hipMemcpyDeviceToHost));
@@ -483,7 +504,7 @@ int lqsgd_set_state(lqsgd_ctx* c, int32_t layer, int32_t worker, const float* ho
   if (rc) return rc;
   if ((rc = check_worker(c, worker))) return rc;
   if ((rc = materialise(c))) return rc;      // a deferred update depends on the old E buffer and the old Q
-  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  if (int rcs = sync_stream(c)) return rcs;
   if (host_e)
     HIP_TRY(c, hipMemcpy(c->args.E + (size_t)worker * c->args.m_stride + ld->m_off, host_e,
                          (size_t)ld->rows * ld->cols * sizeof(float), hipMemcpyHostToDevice));
@@ -587,7 +608,7 @@ int lqsgd_get_packet_raw(lqsgd_ctx* c, int32_t phase, int32_t layer, int32_t wor
   if (mag_len) *mag_len = loc.mag_len;
   if (sign_len) *sign_len = loc.sign_len;
   if (!mag_plane && !sign_plane) return LQSGD_OK;
-  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  if (int rcs = sync_stream(c)) return rcs;
   if (mag_plane) HIP_TRY(c, hipMemcpy(mag_plane, loc.mag, (size_t)loc.mag_len, hipMemcpyDeviceToHost));
   if (sign_plane) HIP_TRY(c, hipMemcpy(sign_plane, loc.sgn, (size_t)loc.sign_len, hipMemcpyDeviceToHost));
   return LQSGD_OK;
@@ -599,7 +620,7 @@ int lqsgd_get_packet(lqsgd_ctx* c, int32_t phase, int32_t layer, int32_t worker,
   PacketLoc loc{};
   int rc = locate_packet(c, phase, layer, worker, &loc);
   if (rc) return rc;
-  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  if (int rcs = sync_stream(c)) return rcs;
   if (scale) HIP_TRY(c, hipMemcpy(scale, loc.scale, sizeof(float), hipMemcpyDeviceToHost));
   if (mag_codes) {
     std::vector<uint8_t> raw((size_t)loc.mag_len);
@@ -637,7 +658,7 @@ int lqsgd_set_packet(lqsgd_ctx* c, int32_t phase, int32_t layer, int32_t worker,
     if ((bit & 7) + loc.bits > 8) mag[(size_t)(bit >> 3) + 1] |= (uint8_t)(v >> 8);
     if (sign_bits[e] & 1u) sgn[(size_t)(e >> 3)] |= (uint8_t)(1u << (e & 7));
   }
-  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  if (int rcs = sync_stream(c)) return rcs;
   HIP_TRY(c, hipMemcpy(loc.mag, mag.data(), mag.size(), hipMemcpyHostToDevice));
   HIP_TRY(c, hipMemcpy(loc.sgn, sgn.data(), sgn.size(), hipMemcpyHostToDevice));
   HIP_TRY(c, hipMemcpy(loc.scale, &scale, sizeof(float), hipMemcpyHostToDevice));
@@ -653,7 +674,7 @@ int lqsgd_get_factor(lqsgd_ctx* c, int32_t which, int32_t layer, int32_t worker,
     const int k = c->plan.kind_of[layer];
     if (k >= 0) return fail(c, LQSGD_ESHAPE, "layer is not a VECTOR layer");
     const VecDesc& vd = c->plan.vecs[-k - 1];
-    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    if (int rcs = sync_stream(c)) return rcs;
     HIP_TRY(c, hipMemcpy(host, a.vmean + vd.off, (size_t)vd.len * sizeof(float), hipMemcpyDeviceToHost));
     return LQSGD_OK;
   }
@@ -677,7 +698,7 @@ int lqsgd_get_factor(lqsgd_ctx* c, int32_t which, int32_t layer, int32_t worker,
     case LQSGD_FACTOR_Q_BAR: src = a.Qbar + ld->q_off; n = ld->nq_el; break;
     default: return fail(c, LQSGD_EINVAL, "unknown factor id");
   }
-  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  if (int rcs = sync_stream(c)) return rcs;
   HIP_TRY(c, hipMemcpy(host, src, n * sizeof(float), hipMemcpyDeviceToHost));
   return LQSGD_OK;
 }
@@ -694,7 +715,7 @@ int lqsgd_set_factor(lqsgd_ctx* c, int32_t which, int32_t layer, const float* ho
   else if (which == LQSGD_FACTOR_Q_BAR) { dst = c->args.Qbar + ld->q_off; n = ld->nq_el; }
   else return fail(c, LQSGD_EINVAL, "only P-bar and Q-bar can be set");
   if ((rc = materialise(c))) return rc;      // a deferred update is defined by the old factors
-  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  if (int rcs = sync_stream(c)) return rcs;
   HIP_TRY(c, hipMemcpy(dst, host, n * sizeof(float), hipMemcpyHostToDevice));
   return LQSGD_OK;
 }
@@ -703,7 +724,7 @@ int64_t lqsgd_wire_bytes(const lqsgd_ctx* c) { return c ? c->plan.wire_bytes : (
 
 int lqsgd_timing_enable(lqsgd_ctx* c, int32_t on) {
   if (!c) return fail(nullptr, LQSGD_EINVAL, "NULL context");
-  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  if (int rcs = sync_stream(c)) return rcs;
   c->timing = on != 0;
   c->events_used = 0;
   return LQSGD_OK;
@@ -712,7 +733,7 @@ int lqsgd_timing_enable(lqsgd_ctx* c, int32_t on) {
 int lqsgd_timing_read(lqsgd_ctx* c, double* total_ms, int64_t* launches) {
   if (!c) return fail(nullptr, LQSGD_EINVAL, "NULL context");
   if (!total_ms || !launches) return fail(c, LQSGD_EINVAL, "NULL output array");
-  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  if (int rcs = sync_stream(c)) return rcs;
   for (int k = 0; k < LQSGD_KERNEL_COUNT; ++k) { total_ms[k] = 0.0; launches[k] = 0; }
   for (size_t i = 0; i < c->events_used; ++i) {
     float ms = 0.0f;

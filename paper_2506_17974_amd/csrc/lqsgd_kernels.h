@@ -19,6 +19,8 @@ struct DevArgs {
   float* Ppre;                 // P_w before Gram-Schmidt
   float* Porth;                // P_w after Gram-Schmidt
   float* orth_part;            // [2][L*W][ceil(max_rows/256)][RP] slice partials of the many-workgroup Gram-Schmidt
+  unsigned long long* orth_table;      // [2][L*W][ceil(max_rows/256)][RP] tagged partials of its one-launch form
+  int* status;                 // pinned host word the kernels raise when a bounded device-side wait expires
   float* Pbar;                 // aggregated P (shared)
   float* Qpart;                // sweep-1 partial products, per worker
   float* Qw;                   // Q_w
@@ -48,7 +50,9 @@ enum ExchangeMode { kQuantOnly = 0, kMeanOnly = 1, kFused = 2 };
 // E = M - P-bar Q-bar^T is applied on the fly (see add_project_kernel).
 hipError_t launch_add_project(int RP, const DevArgs& a, const Tile* tiles, int ntiles, int fuse_residual, int reverse,
                               hipStream_t s);
-hipError_t launch_orth(int RP, int max_rows, int max_rank, const DevArgs& a, hipStream_t s);
+// coop_epoch: number of cooperative Gram-Schmidt launches this context has made so far (it makes the
+// tags in `a.orth_table` unique); incremented when that path is taken.  NULL disables it.
+hipError_t launch_orth(int RP, int max_rows, int max_rank, const DevArgs& a, unsigned long long* coop_epoch, hipStream_t s);
 hipError_t launch_exchange(int mode, int phase, const DevArgs& a, const XTile* tiles, int ntiles, hipStream_t s);
 // Sweep 1 also runs the plain mean of the 1-D tensors (nvtiles extra workgroups).
 hipError_t launch_back_project(int RP, const DevArgs& a, const Tile* tiles, int ntiles, const VTile* vtiles, int nvtiles,

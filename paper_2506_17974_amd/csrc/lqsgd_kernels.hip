@@ -18,7 +18,10 @@
 // All reductions have a fixed order, so results are bit-identical run to run.
 #include "lqsgd_kernels.h"
 
+#include <hip/hip_cooperative_groups.h>
+
 #include <cfloat>
+#include <cstdlib>
 
 namespace lqsgd {
 namespace {
@@ -664,6 +667,154 @@ __global__ __launch_bounds__(256) void orth_wide_kernel(DevArgs a, int j, int ns
       const float m = fmaxf(fmaxf(redmax[0], redmax[1]), fmaxf(redmax[2], redmax[3]));
       atomicMax(reinterpret_cast<unsigned int*>(a.scaleP + (size_t)worker * a.L + layer), __float_as_uint(m));
     }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// orth, many workgroups per (layer, worker), one launch: the same slicing as
+// orth_wide_kernel, but every workgroup keeps its 256 rows in registers through
+// all columns, and the slices of a (layer, worker) pair exchange their partial
+// dot products through a table in memory while the kernel runs.  The kernel is
+// launched cooperatively, so all workgroups are resident and no slice waits
+// for one that cannot start.
+// A table entry is 64 bits: the partial <column j, column k> of one slice and a
+// tag naming the launch and the column, written with ONE device-scope atomic
+// store.  A reader polls an entry until it carries the tag it expects: value
+// and "ready" arrive together, there is no counter and no fence (a device-
+// scope fence writes back and invalidates a die's whole L2: ~100 us per column
+// measured; the runtime's grid barrier ~65 us).  All entries of a pair are
+// polled in parallel (one or a few per thread), collected in LDS and added up
+// in slice order.  The table is double-buffered by column parity: a slice can
+// only write column j + 2 after it has read every slice's column j + 1, which
+// they write only after they have finished reading column j.
+// Every wait is bounded; if one ever expires the workgroup raises the status
+// word and carries on, so the kernel always ends.
+// ---------------------------------------------------------------------------
+constexpr unsigned kTablePolls = 1u << 20;
+constexpr int kCoopMaxSlices = 64;               // rows <= 16384 per factor in this form
+
+__device__ __forceinline__ unsigned long long table_load(const unsigned long long* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+template <int RP>
+__global__ __launch_bounds__(256) void orth_coop_kernel(DevArgs a, int nslice_max, int max_rank,
+                                                        unsigned long long* table, unsigned long long epoch,
+                                                        int* status) {
+  constexpr int EPT = (kCoopMaxSlices * RP + 255) / 256;     // table entries a thread collects per column
+  __shared__ float red[4][RP];
+  __shared__ float tot_s[RP];
+  __shared__ float gather_s[kCoopMaxSlices * RP];
+  __shared__ float redmax[4];
+  const int lw = blockIdx.x / nslice_max, slice = blockIdx.x - lw * nslice_max;
+  const int layer = lw / a.W, worker = lw - layer * a.W;
+  const LayerDesc& ld = a.layers[layer];
+  const int rows = ld.rows, r = ld.r;
+  const int nslice = (rows + 255) >> 8;
+  if (slice >= nslice) return;                   // workgroup-uniform
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
+  const int row = slice * 256 + tid;
+  const bool live = row < rows;
+  float* pre = a.Ppre + (size_t)worker * a.p_stride + ld.p_off;
+  float* orth = a.Porth + (size_t)worker * a.p_stride + ld.p_off;
+  const size_t pstride = (size_t)a.L * a.W * nslice_max * RP;   // [2][L*W][nslice_max][RP] entries
+  float v[RP];
+#pragma unroll
+  for (int k = 0; k < RP; ++k) v[k] = 0.0f;
+  // The absmax cell is shared by all slices: zeroed here with a device-scope store, raised with
+  // atomics at the end.  Every slice reads slice 0's first table entry before it gets there.
+  if (slice == 0 && tid == 0 && !a.orth_shared) {
+    __hip_atomic_store(a.scaleP + (size_t)worker * a.L + layer, 0.0f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0): acknowledged before this slice publishes anything
+  }
+  if (live) {
+    const float* Pp = a.Ppart + (size_t)worker * a.ppart_stride + (a.orth_shared ? ld.p_off : ld.ppart_off);
+    const int nseg = a.orth_shared ? 1 : ld.nseg;
+    for (int s = 0; s < nseg; ++s) {
+      const float* src = Pp + (size_t)s * ld.np_pad + (size_t)row * r;
+#pragma unroll
+      for (int k = 0; k < RP; ++k)
+        if (k < r) v[k] += src[k];
+    }
+#pragma unroll
+    for (int k = 0; k < RP; ++k)
+      if (k < r) pre[(size_t)row * r + k] = v[k];
+  }
+  const int nent = nslice * RP;
+  for (int j = 0; j < r; ++j) {                  // r is the same for every slice of the pair
+    const unsigned tag = (unsigned)(epoch * (unsigned long long)max_rank + (unsigned long long)(j + 1));
+    unsigned long long* tab = table + (size_t)(j & 1) * pstride + (size_t)lw * nslice_max * RP;
+    float vj = 0.0f;
+#pragma unroll
+    for (int k = 0; k < RP; ++k)
+      if (k == j) vj = v[k];
+    float s[RP];
+#pragma unroll
+    for (int k = 0; k < RP; ++k) s[k] = vj * v[k];
+    transpose_reduce<RP, RP, 32>(s, lane);
+    if ((lane & (kWave / RP - 1)) == 0) red[wave][lane >> (6 - log2c(RP))] = s[0];
+    __syncthreads();
+    if (tid < RP) {
+      const float val = (red[0][tid] + red[1][tid]) + (red[2][tid] + red[3][tid]);
+      __hip_atomic_store(tab + (size_t)slice * RP + tid, ((unsigned long long)tag << 32) | __float_as_uint(val),
+                         __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    // collect every slice's entry for this column
+    unsigned long long x[EPT];
+#pragma unroll
+    for (int i = 0; i < EPT; ++i) {
+      const int e = tid + i * 256;
+      x[i] = (e < nent) ? table_load(tab + e) : ((unsigned long long)tag << 32);
+    }
+#pragma unroll
+    for (int i = 0; i < EPT; ++i) {
+      const int e = tid + i * 256;
+      unsigned polls = 0;
+      while ((unsigned)(x[i] >> 32) != tag) {
+        if (++polls >= kTablePolls) {
+          __hip_atomic_store(status, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+          break;
+        }
+        __builtin_amdgcn_s_sleep(1);
+        x[i] = table_load(tab + e);
+      }
+      if (e < nent) gather_s[e] = __uint_as_float((unsigned)x[i]);
+    }
+    __syncthreads();
+    if (tid < RP) {
+      float t = 0.0f;
+      for (int sl = 0; sl < nslice; ++sl) t += gather_s[sl * RP + tid];
+      tot_s[tid] = t;
+    }
+    __syncthreads();
+    const float nrm2 = tot_s[j];
+    const float inv = (nrm2 > FLT_MIN) ? 1.0f / sqrtf(nrm2) : 0.0f;
+    float qv = 0.0f;
+#pragma unroll
+    for (int k = 0; k < RP; ++k)
+      if (k == j) qv = v[k] * inv;
+#pragma unroll
+    for (int k = 0; k < RP; ++k) {
+      if (k == j) v[k] = qv;
+      else if (k > j && k < r) v[k] = fmaf(-(tot_s[k] * inv), qv, v[k]);
+    }
+    __syncthreads();                             // red, gather_s and tot_s are reused by the next column
+  }
+  float mx = 0.0f;
+  if (live) {
+#pragma unroll
+    for (int k = 0; k < RP; ++k)
+      if (k < r) {
+        orth[(size_t)row * r + k] = v[k];
+        mx = fmaxf(mx, fabsf(v[k]));
+      }
+  }
+  mx = wave_max(mx);
+  if (lane == 0) redmax[wave] = mx;
+  __syncthreads();
+  if (tid == 0 && !a.orth_shared) {
+    const float m = fmaxf(fmaxf(redmax[0], redmax[1]), fmaxf(redmax[2], redmax[3]));
+    atomicMax(reinterpret_cast<unsigned int*>(a.scaleP + (size_t)worker * a.L + layer), __float_as_uint(m));
   }
 }
 
@@ -1476,7 +1627,55 @@ void launch_orth_reg(const DevArgs& a, dim3 grid, hipStream_t s) {
   }
 }
 
-hipError_t launch_orth(int rp, int max_rows, int max_rank, const DevArgs& a, hipStream_t s) {
+// One cooperative launch if every workgroup of the grid can be resident at once; returns false
+// (nothing launched) otherwise, and the caller takes the one-launch-per-column path.
+template <int RP>
+bool try_orth_coop(int nslice, int max_rank, const DevArgs& a, int nblocks, unsigned long long* epoch, hipStream_t s) {
+  static int capacity = -1;                      // resident workgroups of this kernel on the whole device
+  if (capacity < 0) {
+    int dev = 0, coop = 0, cus = 0, per_cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&coop, hipDeviceAttributeCooperativeLaunch, dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, orth_coop_kernel<RP>, 256, 0) != hipSuccess) {
+      (void)hipGetLastError();
+      capacity = 0;
+    } else {
+      capacity = coop ? cus * per_cu : 0;
+    }
+  }
+  if (nblocks > capacity) return false;
+  DevArgs args = a;
+  unsigned long long* table = a.orth_table;
+  unsigned long long n = *epoch;
+  int* status = a.status;
+  void* params[] = {&args, &nslice, &max_rank, &table, &n, &status};
+  const hipError_t e = hipLaunchCooperativeKernel(reinterpret_cast<void*>(orth_coop_kernel<RP>), dim3(nblocks), dim3(256),
+                                                  params, 0, s);
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    return false;
+  }
+  *epoch += 1;                                   // the tags of a launch are epoch * max_rank + 1 ... + max_rank
+  return true;
+}
+
+bool launch_orth_coop(int rp, int nslice, int max_rank, const DevArgs& a, int nblocks, unsigned long long* epoch,
+                      hipStream_t s) {
+  static const bool enabled = [] { const char* e = std::getenv("LQSGD_ORTH_COOP"); return !(e && e[0] == '0'); }();
+  if (!enabled || !epoch || !a.orth_table || !a.status || nslice > kCoopMaxSlices) return false;
+  switch (rp) {
+    case 1: return try_orth_coop<1>(nslice, max_rank, a, nblocks, epoch, s);
+    case 2: return try_orth_coop<2>(nslice, max_rank, a, nblocks, epoch, s);
+    case 4: return try_orth_coop<4>(nslice, max_rank, a, nblocks, epoch, s);
+    case 8: return try_orth_coop<8>(nslice, max_rank, a, nblocks, epoch, s);
+    case 16: return try_orth_coop<16>(nslice, max_rank, a, nblocks, epoch, s);
+    case 32: return try_orth_coop<32>(nslice, max_rank, a, nblocks, epoch, s);
+    default: return false;
+  }
+}
+
+hipError_t launch_orth(int rp, int max_rows, int max_rank, const DevArgs& a, unsigned long long* coop_epoch, hipStream_t s) {
   if (a.L <= 0) return hipSuccess;
   const dim3 grid(a.L * a.W);
   const int nslice = (max_rows + 255) / 256;
@@ -1485,6 +1684,7 @@ hipError_t launch_orth(int rp, int max_rows, int max_rank, const DevArgs& a, hip
   const bool reg_fits = (max_rows <= 512 && rp * 2 <= 64) || (max_rows <= 2048 && rp * 8 <= 64) ||
                         (max_rows <= 4096 && rp * 4 <= 48) || (max_rows <= 11264 && rp * 11 <= 48);
   if (a.orth_part && nslice >= 8 && ((int)grid.x < 128 || !reg_fits)) {
+    if (launch_orth_coop(rp, nslice, max_rank, a, (int)grid.x * nslice, coop_epoch, s)) return hipSuccess;
     for (int j = 0; j <= max_rank; ++j) {
       LQSGD_RP_SWITCH(rp, (orth_wide_kernel<RP><<<dim3(grid.x * nslice), dim3(256), 0, s>>>(a, j, nslice)));
     }

@@ -225,7 +225,7 @@ int Plan::build(const lqsgd_config* c, const lqsgd_layer* ls, int32_t n_layers) 
                              (int64_t)(tilesRQ.size() + tilesRP.size()) * sizeof(RTile) + (int64_t)tilesV.size() * sizeof(VTile);
   device_bytes = 4 * ((int64_t)W * (m_stride + 2 * p_stride + q_stride + ppart_stride + qpart_stride) +
                       p_stride + q_stride + v_total + 2 * (int64_t)W * std::max(L, 1) +
-                      2 * (int64_t)W * std::max(L, 1) * ((max_rows + 255) / 256) * RP) +
+                      6 * (int64_t)W * std::max(L, 1) * ((max_rows + 255) / 256) * RP) +
                  (int64_t)W * (magp_stride + sgnp_stride + magq_stride + sgnq_stride) + tile_bytes +
                  (int64_t)L * sizeof(LayerDesc) + (int64_t)V * sizeof(VecDesc) +
                  (int64_t)(W + 1) * n_all * 8 + 4 * 4 * 256;
