@@ -690,7 +690,7 @@ __global__ __launch_bounds__(256) void orth_wide_kernel(DevArgs a, int j, int ns
 // Every wait is bounded; if one ever expires the workgroup raises the status
 // word and carries on, so the kernel always ends.
 // ---------------------------------------------------------------------------
-constexpr unsigned kTablePolls = 1u << 20;
+constexpr unsigned kTablePolls = 1u << 20;      // default bound of a wait (about a second)
 constexpr int kCoopMaxSlices = 64;               // rows <= 16384 per factor in this form
 
 __device__ __forceinline__ unsigned long long table_load(const unsigned long long* p) {
@@ -700,7 +700,7 @@ __device__ __forceinline__ unsigned long long table_load(const unsigned long lon
 template <int RP>
 __global__ __launch_bounds__(256) void orth_coop_kernel(DevArgs a, int nslice_max, int max_rank,
                                                         unsigned long long* table, unsigned long long epoch,
-                                                        int* status) {
+                                                        int* status, unsigned max_polls) {
   constexpr int EPT = (kCoopMaxSlices * RP + 255) / 256;     // table entries a thread collects per column
   __shared__ float red[4][RP];
   __shared__ float tot_s[RP];
@@ -771,7 +771,7 @@ __global__ __launch_bounds__(256) void orth_coop_kernel(DevArgs a, int nslice_ma
       const int e = tid + i * 256;
       unsigned polls = 0;
       while ((unsigned)(x[i] >> 32) != tag) {
-        if (++polls >= kTablePolls) {
+        if (++polls >= max_polls) {
           __hip_atomic_store(status, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
           break;
         }
@@ -1649,7 +1649,13 @@ bool try_orth_coop(int nslice, int max_rank, const DevArgs& a, int nblocks, unsi
   unsigned long long* table = a.orth_table;
   unsigned long long n = *epoch;
   int* status = a.status;
-  void* params[] = {&args, &nslice, &max_rank, &table, &n, &status};
+  // LQSGD_TABLE_POLLS shortens the bound (a test of the expiry path sets it to 1)
+  unsigned max_polls = kTablePolls;
+  if (const char* e = std::getenv("LQSGD_TABLE_POLLS")) {
+    const long v = std::strtol(e, nullptr, 10);
+    if (v >= 1) max_polls = (unsigned)v;
+  }
+  void* params[] = {&args, &nslice, &max_rank, &table, &n, &status, &max_polls};
   const hipError_t e = hipLaunchCooperativeKernel(reinterpret_cast<void*>(orth_coop_kernel<RP>), dim3(nblocks), dim3(256),
                                                   params, 0, s);
   if (e != hipSuccess) {

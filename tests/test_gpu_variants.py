@@ -32,8 +32,8 @@ AGG_CASES = [
     ([(2100, 132), (1000, 68)], 8, 8, 4, 2),
     ([(129, 1028)], 16, 8, 8, 2),                    # matrix-core sweeps 0 / 2
     ([(100, 1100), (33, 64)], 20, 8, 8, 2),          # rank pad 32
-    ([(2304, 96)], 4, 8, 8, 1),                      # one worker, tall: many-workgroup Gram-Schmidt not needed
-    ([(4608, 64)], 32, 8, 8, 2),                     # tall + rank 32: many-workgroup Gram-Schmidt on the aggregate
+    ([(2304, 96)], 4, 8, 8, 1),                      # one worker, tall: one-launch many-workgroup Gram-Schmidt
+    ([(4608, 64)], 32, 8, 8, 2),                     # tall + rank 32: the same on the aggregate, 18 slices
 ]
 
 
@@ -206,3 +206,40 @@ def test_model_update(layers, rank, bits, W, flags):
         a.step_update(Gd, bad, 0.1)
     assert ei.value.code == B.EINVAL
     a.close(); b.close()
+
+
+def test_expired_device_wait_is_reported(monkeypatch):
+    """The one-launch Gram-Schmidt for tall factors waits for other workgroups with
+    a bounded number of polls.  With the bound forced to one poll from the host the
+    waits expire (the kernel still runs to its end), the context raises its status
+    word, and every synchronising call reports it instead of returning bad data."""
+    import torch
+    _say("case: expired device-side wait")
+    rows, cols, W, rank = 8192, 64, 4, 8
+    rng = np.random.default_rng(3)
+    G = [[torch.from_numpy((rng.standard_normal((rows, cols)) * 1e-3).astype(f32)).cuda()] for _ in range(W)]
+    q0 = rng.standard_normal((cols, rank)).astype(f32)
+    # healthy run first: same shape, default bound
+    ok = B.Compressor(B.layer_list([(rows, cols)], ()), rank, 8, 8, W)
+    ok.set_q(0, q0)
+    ok.step(G)
+    ok.synchronize()
+    p = ok.get_factor(B.FACTOR_P_ORTH, 0, 0).astype(f64)
+    assert np.allclose(p.T @ p, np.eye(rank), atol=1e-4)
+    ok.close()
+    monkeypatch.setenv("LQSGD_TABLE_POLLS", "1")
+    bad = B.Compressor(B.layer_list([(rows, cols)], ()), rank, 8, 8, W)
+    bad.set_q(0, q0)
+    raised = False
+    for _ in range(3):
+        bad.step(G)
+        try:
+            bad.synchronize()
+        except B.LqsgdError as e:
+            assert e.code == B.EHIP and "wait expired" in str(e)
+            raised = True
+            break
+    assert raised
+    with pytest.raises(B.LqsgdError):
+        bad.get_factor(B.FACTOR_P_ORTH, 0, 0)
+    bad.close()
