@@ -1349,9 +1349,14 @@ __global__ __launch_bounds__(256) void residual_kernel(DevArgs a, const Tile* __
 
 // ---------------------------------------------------------------------------
 // Sweeps 0 and 2 on the matrix cores, rank pads 16 and 32.
-// One wavefront per work item (32 rows x one column segment), 64 columns at a
-// time.  The 32 x 64 tile is loaded and stored in "row layout" (float4 per
-// lane, 16 lanes = 256 contiguous bytes of a row, 4 rows per instruction).
+// One workgroup per work item (32 rows x one column segment); its four
+// wavefronts take the 64-column blocks of the segment in turn, so that the
+// workgroup touches 1 KiB of every row at about the same time (with one item
+// per wavefront, each walking its own segment in 256-byte runs, the same data
+// movement reached only 4.3 TB/s; this order reaches 5.4-5.8), and their P
+// partials meet in LDS, added in wavefront order.  A 32 x 64 tile is loaded and
+// stored in "row layout" (float4 per lane, 16 lanes = 256 contiguous bytes of a
+// row, 4 rows per instruction).
 //
 //   G-hat tile = P-bar[32 x r] Q-bar^T[r x 64]: i = row, j = column, k = rank.
 //     Lane (i, h) holds P-bar[row i][h r/2 .. h r/2 + r/2) -- a contiguous run of
@@ -1384,7 +1389,9 @@ template <int RP, int MODE, bool EXACT>
 __device__ __forceinline__ void mfma_tile(const float* __restrict__ G, float* __restrict__ M,
                                           const float* Q, const float* Pb, float* __restrict__ Pp,
                                           float* __restrict__ ghat_out, int cols, int r, int row0, int nrows,
-                                          int col0, int col1, int lane, float* lds, int update, float eta) {
+                                          int col0, int col1, int lane, int wave, float (*lds_all)[32 * kLP],
+                                          int update, float eta) {
+  float* lds = lds_all[wave];
   constexpr bool ADD = (MODE == kMAdd || MODE == kMAddFused);
   constexpr bool NEEDG = (MODE != kMAdd);
   constexpr bool HASM = (MODE != kMGhatOnly);
@@ -1415,7 +1422,9 @@ __device__ __forceinline__ void mfma_tile(const float* __restrict__ G, float* __
 #pragma unroll
   for (int i = 0; i < 16; ++i) { accP[i] = 0.0f; accP2[i] = 0.0f; }
 
-  for (int c = col0; c < col1; c += 64) {
+  // the four wavefronts take the 64-column blocks of the segment in turn, so that together they
+  // touch 1 KiB of each row at about the same time (a wavefront on its own reads 256-byte runs)
+  for (int c = col0 + 64 * wave; c < col1; c += 256) {
     const int cl = c + c4;
     const bool colok = cl < col1;
     Pk<4> g[8], e[8];
@@ -1525,10 +1534,17 @@ __device__ __forceinline__ void mfma_tile(const float* __restrict__ G, float* __
     }
   }
   if constexpr (ADD) {
+    // P partial of the item = sum over the four wavefronts, added in wavefront order
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const int rr = 8 * (v >> 2) + 4 * h + (v & 3);
-      if (rr < nrows && li < r) Pp[(size_t)(row0 + rr) * r + li] = accP[v] + accP2[v];
+    for (int v = 0; v < 16; ++v) lds[(8 * (v >> 2) + 4 * h + (v & 3)) * kLP + li] = accP[v] + accP2[v];
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int e = (int)threadIdx.x + 256 * i;
+      const int rr = e >> 5, k = e & 31;
+      const float t = ((lds_all[0][rr * kLP + k] + lds_all[1][rr * kLP + k]) + lds_all[2][rr * kLP + k]) +
+                      lds_all[3][rr * kLP + k];
+      if (rr < nrows && k < r) Pp[(size_t)(row0 + rr) * r + k] = t;
     }
   }
 }
@@ -1555,16 +1571,16 @@ __device__ __forceinline__ void mfma_mode_vector_fallback(const DevArgs& a, cons
   }
 }
 
+// Wavefronts per SIMD the register allocation aims for: two at rank pad 16 (2.65 -> 2.47 ms on
+// 8192^2 x 16 workers), one at rank pad 32, where two would spill (3.0 -> 4.6 ms).
 template <int RP, int MODE>
-__global__ __launch_bounds__(256) void mfma_sweep_kernel(DevArgs a, const Tile* __restrict__ tiles, int ntiles, int reverse) {
+__global__ __launch_bounds__(256, RP <= 16 ? 2 : 1) void mfma_sweep_kernel(DevArgs a, const Tile* __restrict__ tiles, int ntiles, int reverse) {
   __shared__ __attribute__((aligned(16))) float lds_all[4][32 * kLP];
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int lane = threadIdx.x & (kWave - 1);
   if ((MODE == kMAdd || MODE == kMAddFused) && a.agg_first && blockIdx.x == 0)
     for (int i = threadIdx.x; i < a.W * a.L; i += 256) a.scaleP[i] = 0.0f;
-  const int t = blockIdx.x * 4 + wave;
-  if (t >= ntiles) return;
-  const Tile tl = tiles[reverse ? ntiles - 1 - t : t];
+  const Tile tl = tiles[reverse ? ntiles - 1 - (int)blockIdx.x : (int)blockIdx.x];   // one item per workgroup
   const int layer = tl.lw / a.W, worker = tl.lw - layer * a.W;
   const LayerDesc& ld = a.layers[layer];
   const float* G = (MODE == kMAdd || MODE == kMAddFused) ? a.grads[(size_t)worker * a.n_all + ld.gidx] : nullptr;
@@ -1576,16 +1592,19 @@ __global__ __launch_bounds__(256) void mfma_sweep_kernel(DevArgs a, const Tile* 
   const int col0 = tl.aux * ld.segw;
   const int col1 = min(ld.cols, col0 + ld.segw);
   if (ld.vec != 4) {
-    mfma_mode_vector_fallback<RP, MODE>(a, ld, tl, worker, G, M, Pp, ghat_out, col0, col1, lane);
+    // tiny layers: the vector code, eight of the item's rows per wavefront
+    Tile sub = tl;
+    sub.row0 = tl.row0 + 8 * wave;
+    sub.nrows = min(8, tl.nrows - 8 * wave);
+    if (sub.nrows > 0) mfma_mode_vector_fallback<RP, MODE>(a, ld, sub, worker, G, M, Pp, ghat_out, col0, col1, lane);
     return;
   }
-  float* lds = lds_all[wave];
   if (ld.r == RP)
     mfma_tile<RP, MODE, true>(G, M, a.Qbar + ld.q_off, a.Pbar + ld.p_off, Pp, ghat_out, ld.cols, ld.r, tl.row0,
-                              tl.nrows, col0, col1, lane, lds, a.update, a.eta);
+                              tl.nrows, col0, col1, lane, wave, lds_all, a.update, a.eta);
   else
     mfma_tile<RP, MODE, false>(G, M, a.Qbar + ld.q_off, a.Pbar + ld.p_off, Pp, ghat_out, ld.cols, ld.r, tl.row0,
-                               tl.nrows, col0, col1, lane, lds, a.update, a.eta);
+                               tl.nrows, col0, col1, lane, wave, lds_all, a.update, a.eta);
 }
 
 }  // namespace
@@ -1757,7 +1776,7 @@ hipError_t launch_residual(int rp, int mode, const DevArgs& a, const Tile* tiles
 
 template <int RP>
 hipError_t launch_mfma_sweep_rp(int mode, const DevArgs& a, const Tile* tiles, int ntiles, int reverse, hipStream_t s) {
-  const dim3 grid((ntiles + 3) / 4), block(256);
+  const dim3 grid(ntiles), block(256);
   switch (mode) {
     case kMAdd: mfma_sweep_kernel<RP, kMAdd><<<grid, block, 0, s>>>(a, tiles, ntiles, reverse); break;
     case kMAddFused: mfma_sweep_kernel<RP, kMAddFused><<<grid, block, 0, s>>>(a, tiles, ntiles, reverse); break;
