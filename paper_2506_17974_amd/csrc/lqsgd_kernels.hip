@@ -22,6 +22,7 @@
 
 #include <cfloat>
 #include <cstdlib>
+#include <type_traits>
 
 namespace lqsgd {
 namespace {
@@ -1424,14 +1425,17 @@ __device__ __forceinline__ void mfma_tile(const float* __restrict__ G, float* __
 
   // the four wavefronts take the 64-column blocks of the segment in turn, so that together they
   // touch 1 KiB of each row at about the same time (a wavefront on its own reads 256-byte runs)
-  for (int c = col0 + 64 * wave; c < col1; c += 256) {
+  // One 64-column block.  FULL: all 32 rows and all 64 columns of the block exist (every block of a
+  // large layer except on its edges): no bounds tests, so nothing branches around a load.
+  auto block = [&](auto full_tag, const int c) {
+    constexpr bool FULL = decltype(full_tag)::value;
     const int cl = c + c4;
-    const bool colok = cl < col1;
+    const bool colok = FULL || cl < col1;
     Pk<4> g[8], e[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int rr = 4 * i + sr;
-      const bool ok = colok && rr < nrows;
+      const bool ok = FULL || (colok && rr < nrows);
       const size_t off = (size_t)(row0 + rr) * cols;
 #pragma unroll
       for (int v = 0; v < 4; ++v) { g[i].v[v] = 0.0f; e[i].v[v] = 0.0f; }
@@ -1445,7 +1449,10 @@ __device__ __forceinline__ void mfma_tile(const float* __restrict__ G, float* __
 #pragma unroll
       for (int kk = 0; kk < 32; ++kk) {
         const int col = c + 32 * h + kk;
-        bq[kk] = (col < col1 && li < r) ? Q[(size_t)col * r + li] : 0.0f;
+        if constexpr (FULL && EXACT)
+          bq[kk] = Q[(size_t)col * RP + li];
+        else
+          bq[kk] = (col < col1 && li < r) ? Q[(size_t)col * r + li] : 0.0f;
       }
     }
     if constexpr (NEEDG) {
@@ -1454,7 +1461,7 @@ __device__ __forceinline__ void mfma_tile(const float* __restrict__ G, float* __
       for (int b = 0; b < 2; ++b) {
         const int col = c + 32 * b + li;
         if constexpr (EXACT) {
-          if (col < col1) {
+          if (FULL || col < col1) {
             const float4* src = reinterpret_cast<const float4*>(Q + (size_t)col * RP + KH * h);
 #pragma unroll
             for (int t = 0; t < KH / 4; ++t) {
@@ -1467,7 +1474,8 @@ __device__ __forceinline__ void mfma_tile(const float* __restrict__ G, float* __
           }
         } else {
 #pragma unroll
-          for (int k = 0; k < KH; ++k) qb[b][k] = (col < col1 && KH * h + k < r) ? Q[(size_t)col * r + KH * h + k] : 0.0f;
+          for (int k = 0; k < KH; ++k)
+            qb[b][k] = ((FULL || col < col1) && KH * h + k < r) ? Q[(size_t)col * r + KH * h + k] : 0.0f;
         }
       }
       // the two 32-column blocks accumulate in turn: two independent chains on the matrix pipe
@@ -1493,7 +1501,7 @@ __device__ __forceinline__ void mfma_tile(const float* __restrict__ G, float* __
           e[i].v[0] -= t.x; e[i].v[1] -= t.y; e[i].v[2] -= t.z; e[i].v[3] -= t.w;
         }
         if (MODE == kMGhatOnly || (MODE == kMResidualGhat && ghat_out)) {
-          if (colok && rr < nrows) {
+          if (FULL || (colok && rr < nrows)) {
             const Pk<4> o{{t.x, t.y, t.z, t.w}};
             emit_ghat<4>(ghat_out + (size_t)(row0 + rr) * cols, (unsigned)cl * 4u, o, update, eta);
           }
@@ -1508,7 +1516,7 @@ __device__ __forceinline__ void mfma_tile(const float* __restrict__ G, float* __
         Pk<4> m;
 #pragma unroll
         for (int v = 0; v < 4; ++v) m.v[v] = ADD ? g[i].v[v] + e[i].v[v] : e[i].v[v];
-        if (colok && rr < nrows)
+        if (FULL || (colok && rr < nrows))
           strow<4, LQSGD_NT_ST_A != 0>(reinterpret_cast<char*>(M + (size_t)(row0 + rr) * cols), (unsigned)cl * 4u, m);
         if constexpr (ADD)
           *reinterpret_cast<float4*>(lds + rr * kLP + c4) = make_float4(m.v[0], m.v[1], m.v[2], m.v[3]);
@@ -1532,6 +1540,12 @@ __device__ __forceinline__ void mfma_tile(const float* __restrict__ G, float* __
       }
       wave_lds_fence();
     }
+  };
+  for (int c = col0 + 64 * wave; c < col1; c += 256) {
+    if (nrows == 32 && c + 64 <= col1)
+      block(std::true_type{}, c);
+    else
+      block(std::false_type{}, c);
   }
   if constexpr (ADD) {
     // P partial of the item = sum over the four wavefronts, added in wavefront order
