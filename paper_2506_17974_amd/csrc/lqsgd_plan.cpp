@@ -130,7 +130,9 @@ int Plan::build(const lqsgd_config* c, const lqsgd_layer* ls, int32_t n_layers) 
   const int64_t tgtB = env_i64("LQSGD_TILE_B", std::min<int64_t>(131072, std::max<int64_t>(8192, total / 2730)));
   // the G-hat-only pass covers one worker's worth of elements: smaller items keep its grid wide
   const int64_t tgtG = env_i64("LQSGD_TILE_G", std::min<int64_t>(tgtB, std::max<int64_t>(4096, matrix_elements / 2730)));
-  const int64_t segmax4 = env_i64("LQSGD_SEGMAX", 1024);
+  // column segments: at most 1024 columns (2048 at rank pad 32, where fewer, longer segments save
+  // more in partial planes and Gram-Schmidt input than they cost in sweep 0)
+  const int64_t segmax4 = env_i64("LQSGD_SEGMAX", RP >= 32 ? 2048 : 1024);
 
   int64_t m_acc = 0, p_acc = 0, q_acc = 0, pp_acc = 0, qp_acc = 0;
   int64_t mp_acc = 0, sp_acc = 0, mq_acc = 0, sq_acc = 0;
