@@ -403,10 +403,13 @@ int lqsgd_create(const lqsgd_config* cfg, const lqsgd_layer* layers, int32_t n_l
   quantiser_tables(p.cfg.bits_p, (double)p.cfg.alpha, tP, lP);
   quantiser_tables(p.cfg.bits_q, (double)p.cfg.alpha, tQ, lQ);
 #define TRY_(x) do { if ((rc = (x))) return bail(rc); } while (0)
+  // Loaders for ranks below their register pad fetch whole padded rows and may run up to 31 floats
+  // past the last row of a factor: every factor buffer ends with this much readable slack.
+  constexpr size_t kSlack = 64;
   TRY_(dev_alloc(c, &a.E, W * p.m_stride, true));
-  TRY_(dev_alloc(c, &a.Ppart, W * p.ppart_stride, true));
-  TRY_(dev_alloc(c, &a.Ppre, W * p.p_stride, true));
-  TRY_(dev_alloc(c, &a.Porth, W * p.p_stride, true));
+  TRY_(dev_alloc(c, &a.Ppart, W * p.ppart_stride + kSlack, true));
+  TRY_(dev_alloc(c, &a.Ppre, W * p.p_stride + kSlack, true));
+  TRY_(dev_alloc(c, &a.Porth, W * p.p_stride + kSlack, true));
   TRY_(dev_alloc(c, &a.orth_part, 2 * W * (size_t)std::max(p.L, 1) * ((p.max_rows + 255) / 256) * p.RP, true));
   TRY_(dev_alloc(c, &a.orth_table, 2 * W * (size_t)std::max(p.L, 1) * ((p.max_rows + 255) / 256) * p.RP, true));
   {
@@ -417,10 +420,10 @@ int lqsgd_create(const lqsgd_config* cfg, const lqsgd_layer* layers, int32_t n_l
     *c->status = 0;
     a.status = c->status;
   }
-  TRY_(dev_alloc(c, &a.Pbar, (size_t)p.p_stride, true));
-  TRY_(dev_alloc(c, &a.Qpart, W * p.qpart_stride, true));
-  TRY_(dev_alloc(c, &a.Qw, W * p.q_stride, true));
-  TRY_(dev_alloc(c, &a.Qbar, (size_t)p.q_stride, true));
+  TRY_(dev_alloc(c, &a.Pbar, (size_t)p.p_stride + kSlack, true));
+  TRY_(dev_alloc(c, &a.Qpart, W * p.qpart_stride + kSlack, true));
+  TRY_(dev_alloc(c, &a.Qw, W * p.q_stride + kSlack, true));
+  TRY_(dev_alloc(c, &a.Qbar, (size_t)p.q_stride + kSlack, true));
   TRY_(dev_alloc(c, &a.magP, W * p.magp_stride, true));
   TRY_(dev_alloc(c, &a.sgnP, W * p.sgnp_stride, true));
   TRY_(dev_alloc(c, &a.scaleP, W * (size_t)std::max(p.L, 1), true));

@@ -127,6 +127,15 @@ __device__ __forceinline__ void emit_ghat(float* __restrict__ rowbase, unsigned 
   }
 }
 
+// x where `on`, else +0: a bit mask instead of a select, so that the compiler cannot turn the
+// unconditional load that produced x back into a branch around a conditional one
+__device__ __forceinline__ float keep_if(float x, bool on) {
+  return __uint_as_float(__float_as_uint(x) & (on ? 0xffffffffu : 0u));
+}
+
+// Ranks that do not fill their pad (r < RP): the loaders below still fetch RP values per factor
+// row, unconditionally, running up to RP - 1 elements into what follows the row (the next row, or
+// the slack the host leaves after every factor buffer), and zero the surplus afterwards.
 template <int RP, int VEC, bool EXACT>
 __device__ __forceinline__ void load_slice(const float* __restrict__ F, int c, int r, float (&s)[VEC * RP]) {
   if constexpr (EXACT) {
@@ -145,7 +154,7 @@ __device__ __forceinline__ void load_slice(const float* __restrict__ F, int c, i
 #pragma unroll
     for (int v = 0; v < VEC; ++v)
 #pragma unroll
-      for (int k = 0; k < RP; ++k) s[v * RP + k] = (k < r) ? F[(size_t)(c + v) * r + k] : 0.0f;
+      for (int k = 0; k < RP; ++k) s[v * RP + k] = keep_if(F[(size_t)(c + v) * r + k], k < r);
   }
 }
 
@@ -180,7 +189,7 @@ __device__ __forceinline__ void load_row(const float* __restrict__ F, int row, i
   } else {
     const float* b = F + (size_t)row * r;
 #pragma unroll
-    for (int k = 0; k < RP; ++k) p[k] = (k < r) ? b[k] : 0.0f;
+    for (int k = 0; k < RP; ++k) p[k] = keep_if(b[k], k < r);
   }
 }
 
@@ -193,8 +202,11 @@ __device__ __forceinline__ void load_row_uniform(const float* F, int row, int r,
     for (int k = 0; k < RP; ++k) p[k] = b[k];
   } else {
     const_fp b = (const_fp)(F + (size_t)row * r);
+    float t[RP];
 #pragma unroll
-    for (int k = 0; k < RP; ++k) p[k] = (k < r) ? b[k] : 0.0f;
+    for (int k = 0; k < RP; ++k) t[k] = b[k];
+#pragma unroll
+    for (int k = 0; k < RP; ++k) p[k] = keep_if(t[k], k < r);
   }
 }
 
