@@ -89,7 +89,7 @@ typedef struct {
   uint32_t flags;
 } lqsgd_config;
 
-#define LQSGD_MAX_RANK 32
+#define LQSGD_MAX_RANK 64
 #define LQSGD_MAX_WORKERS 64
 
 /* Phases of the staged interface: the P exchange (Algorithm 1, statements

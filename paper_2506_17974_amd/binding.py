@@ -21,7 +21,7 @@ FACTOR_P_PRE, FACTOR_P_ORTH, FACTOR_P_BAR, FACTOR_Q_W, FACTOR_Q_BAR, FACTOR_VMEA
 (KERNEL_ADD_PROJECT, KERNEL_ORTH, KERNEL_EXCHANGE_P, KERNEL_BACK_PROJECT, KERNEL_REDUCE_Q,
  KERNEL_EXCHANGE_Q, KERNEL_RESIDUAL, KERNEL_REDUCE_P) = range(8)
 KERNEL_COUNT = 8
-MAX_RANK, MAX_WORKERS = 32, 64
+MAX_RANK, MAX_WORKERS = 64, 64
 
 # every symbol the header declares
 SYMBOLS = [

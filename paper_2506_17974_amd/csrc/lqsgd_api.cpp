@@ -226,7 +226,7 @@ int run_sweep1(lqsgd_ctx* c, bool with_vectors) {
   { Timed t(c, LQSGD_KERNEL_BACK_PROJECT);
     const int nv = with_vectors ? (int)c->plan.tilesV.size() : 0;
     if (c->plan.mfma)
-      HIP_TRY(c, launch_back_project_mfma(c->args, c->d_tilesBM, (int)c->plan.tilesBM.size(), c->d_tilesV, nv,
+      HIP_TRY(c, launch_back_project_mfma(c->plan.RP, c->args, c->d_tilesBM, (int)c->plan.tilesBM.size(), c->d_tilesV, nv,
                                           next_dir(c), c->stream));
     else
       HIP_TRY(c, launch_back_project(c->plan.RP, c->args, c->d_tilesB, (int)c->plan.tilesB.size(), c->d_tilesV, nv,

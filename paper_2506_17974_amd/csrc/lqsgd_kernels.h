@@ -57,8 +57,8 @@ hipError_t launch_exchange(int mode, int phase, const DevArgs& a, const XTile* t
 // Sweep 1 also runs the plain mean of the 1-D tensors (nvtiles extra workgroups).
 hipError_t launch_back_project(int RP, const DevArgs& a, const Tile* tiles, int ntiles, const VTile* vtiles, int nvtiles,
                                int reverse, hipStream_t s);
-// The same sweep on the matrix cores (rank pad 16 or 32; tiles are row block x 128-column group).
-hipError_t launch_back_project_mfma(const DevArgs& a, const Tile* tiles, int ntiles, const VTile* vtiles, int nvtiles,
+// The same sweep on the matrix cores (rank pad 32 or 64; tiles are row block x 512-column group).
+hipError_t launch_back_project_mfma(int RP, const DevArgs& a, const Tile* tiles, int ntiles, const VTile* vtiles, int nvtiles,
                                     int reverse, hipStream_t s);
 // phase 1: Q_w from sweep 1's row-block planes; phase 0: the raw P_w from sweep 0's column-segment
 // planes (aggregate-first order, where the exchange comes before Gram-Schmidt).
@@ -66,7 +66,7 @@ hipError_t launch_reduce_q(int phase, const DevArgs& a, const RTile* tiles, int 
 // mode: 0 = residual for all workers, 1 = residual + G-hat, 2 = G-hat only (tiles of worker 0).
 hipError_t launch_residual(int RP, int mode, const DevArgs& a, const Tile* tiles, int ntiles, int reverse, hipStream_t s);
 
-// Sweeps 0 and 2 on the matrix cores (rank pad 16 or 32), over the wavefront work list of
+// Sweeps 0 and 2 on the matrix cores (rank pad 16, 32 or 64), over the work list of
 // sweep 0 (32-row items).  mode: 0 = M = G + E and P partials, 1 = the same with the deferred
 // residual applied on the fly, 2 = residual, 3 = residual + G-hat, 4 = G-hat only (worker 0's items).
 hipError_t launch_mfma_sweep(int RP, int mode, const DevArgs& a, const Tile* tiles, int ntiles, int reverse, hipStream_t s);

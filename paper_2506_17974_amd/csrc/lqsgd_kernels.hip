@@ -1184,6 +1184,72 @@ __device__ __forceinline__ void back_project_mfma_tile(const DevArgs& a, const L
     }
 }
 
+// The same with NB blocks of 32 ranks (rank pad 64: NB = 2): one pass over M feeds both blocks.
+template <bool VEC4, int NB>
+__device__ __forceinline__ void back_project_mfma_tile_nb(const DevArgs& a, const LayerDesc& ld, const Tile& tl, int worker,
+                                                       int wave, int lane) {
+  const int cols = ld.cols, r = ld.r;
+  const int c0 = tl.aux * kMfmaCols + wave * 128;
+  if (c0 >= cols) return;
+  const int li = lane & 31, h = lane >> 5;
+  const float* M = a.E + (size_t)worker * a.m_stride + ld.m_off;
+  const float* Pb = a.Pbar + ld.p_off;
+  bool rankok[NB];
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) rankok[nb] = 32 * nb + li < r;
+  const int rend = tl.row0 + tl.nrows;
+  const int cl = c0 + 4 * li;                      // first of this lane's four columns
+  v16f acc[NB][4];                                  // [block of 32 ranks][column residue]
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[nb][s][i] = 0.0f;
+  constexpr int U = 4;
+  for (int rb = tl.row0; rb < rend; rb += 2 * U) {
+    Pk<4> am[U];
+    float bp[NB][U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int row = rb + 2 * u + h;
+      const bool ok = row < rend;
+      const float* mrow = M + (size_t)row * cols;
+      if constexpr (VEC4) {
+        if (ok && cl < cols) {
+          am[u] = ldrow<4, LQSGD_NT_M != 0>(reinterpret_cast<const char*>(mrow), (unsigned)cl * 4u);
+        } else {
+#pragma unroll
+          for (int s = 0; s < 4; ++s) am[u].v[s] = 0.0f;
+        }
+      } else {
+#pragma unroll
+        for (int s = 0; s < 4; ++s) am[u].v[s] = (ok && cl + s < cols) ? mrow[cl + s] : 0.0f;
+      }
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) bp[nb][u] = (ok && rankok[nb]) ? Pb[(size_t)row * r + 32 * nb + li] : 0.0f;
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+          acc[nb][s] = __builtin_amdgcn_mfma_f32_32x32x2f32(am[u].v[s], bp[nb][u], acc[nb][s], 0, 0, 0);
+  }
+  float* Qp = a.Qpart + (size_t)worker * a.qpart_stride + ld.qpart_off + (size_t)(tl.row0 / ld.rbb) * ld.nq_pad;
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int col = c0 + 4 * (8 * (v >> 2) + 4 * h + (v & 3)) + s;
+        if (col < cols && rankok[nb]) Qp[(size_t)col * r + 32 * nb + li] = acc[nb][s][v];
+      }
+}
+
+template <int NB>
 __global__ __launch_bounds__(256) void back_project_mfma_kernel(DevArgs a, const Tile* __restrict__ tiles, int ntiles,
                                                                 const VTile* __restrict__ vtiles, int reverse) {
   if ((int)blockIdx.x >= ntiles) {
@@ -1198,10 +1264,17 @@ __global__ __launch_bounds__(256) void back_project_mfma_kernel(DevArgs a, const
   const Tile tl = tiles[reverse ? ntiles - 1 - blockIdx.x : blockIdx.x];
   const int layer = tl.lw / a.W, worker = tl.lw - layer * a.W;
   const LayerDesc& ld = a.layers[layer];
-  if (ld.vec == 4)
-    back_project_mfma_tile<true>(a, ld, tl, worker, wave, lane);
-  else
-    back_project_mfma_tile<false>(a, ld, tl, worker, wave, lane);
+  if constexpr (NB == 1) {
+    if (ld.vec == 4)
+      back_project_mfma_tile<true>(a, ld, tl, worker, wave, lane);
+    else
+      back_project_mfma_tile<false>(a, ld, tl, worker, wave, lane);
+  } else {
+    if (ld.vec == 4)
+      back_project_mfma_tile_nb<true, NB>(a, ld, tl, worker, wave, lane);
+    else
+      back_project_mfma_tile_nb<false, NB>(a, ld, tl, worker, wave, lane);
+  }
 }
 
 // ---------------------------------------------------------------------------
@@ -1409,6 +1482,7 @@ __device__ __forceinline__ void mfma_tile(const float* __restrict__ G, float* __
   constexpr bool NEEDG = (MODE != kMAdd);
   constexpr bool HASM = (MODE != kMGhatOnly);
   constexpr int KH = RP / 2;                       // ranks per half-wavefront
+  constexpr int NB = (RP + 31) / 32;               // blocks of 32 ranks in the P product (2 at rank pad 64)
   const int li = lane & 31, h = lane >> 5;
   const int sr = lane >> 4, c4 = (lane & 15) * 4;  // row layout: rows 4 i + sr, columns c4 .. c4 + 3
   float pa[KH];
@@ -1431,9 +1505,11 @@ __device__ __forceinline__ void mfma_tile(const float* __restrict__ G, float* __
       for (int k = 0; k < KH; ++k) pa[k] = (li < nrows && KH * h + k < r) ? Pb[(size_t)row * r + KH * h + k] : 0.0f;
     }
   }
-  v16f accP, accP2;
+  v16f accP[NB], accP2[NB];
 #pragma unroll
-  for (int i = 0; i < 16; ++i) { accP[i] = 0.0f; accP2[i] = 0.0f; }
+  for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) { accP[nb][i] = 0.0f; accP2[nb][i] = 0.0f; }
 
   // the four wavefronts take the 64-column blocks of the segment in turn, so that together they
   // touch 1 KiB of each row at about the same time (a wavefront on its own reads 256-byte runs)
@@ -1456,16 +1532,19 @@ __device__ __forceinline__ void mfma_tile(const float* __restrict__ G, float* __
         if constexpr (HASM) e[i] = ldrow<4, LQSGD_NT_E != 0>(reinterpret_cast<const char*>(M + off), (unsigned)cl * 4u);
       }
     }
-    float bq[32];
+    float bq[NB][32];
     if constexpr (ADD) {
 #pragma unroll
-      for (int kk = 0; kk < 32; ++kk) {
-        const int col = c + 32 * h + kk;
-        if constexpr (FULL && EXACT)
-          bq[kk] = Q[(size_t)col * RP + li];
-        else
-          bq[kk] = (col < col1 && li < r) ? Q[(size_t)col * r + li] : 0.0f;
-      }
+      for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int kk = 0; kk < 32; ++kk) {
+          const int col = c + 32 * h + kk;
+          const int rk = 32 * nb + li;
+          if constexpr (FULL && EXACT)
+            bq[nb][kk] = Q[(size_t)col * RP + rk];
+          else
+            bq[nb][kk] = (col < col1 && rk < r) ? Q[(size_t)col * r + rk] : 0.0f;
+        }
     }
     if constexpr (NEEDG) {
       float qb[2][KH];
@@ -1541,14 +1620,17 @@ __device__ __forceinline__ void mfma_tile(const float* __restrict__ G, float* __
       for (int t = 0; t < 8; t += 2) {
         const float4 a0 = *reinterpret_cast<const float4*>(lds + li * kLP + 32 * h + 4 * t);
         const float4 a1 = *reinterpret_cast<const float4*>(lds + li * kLP + 32 * h + 4 * t + 4);
-        accP = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.x, bq[4 * t + 0], accP, 0, 0, 0);
-        accP2 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.x, bq[4 * t + 4], accP2, 0, 0, 0);
-        accP = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.y, bq[4 * t + 1], accP, 0, 0, 0);
-        accP2 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.y, bq[4 * t + 5], accP2, 0, 0, 0);
-        accP = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.z, bq[4 * t + 2], accP, 0, 0, 0);
-        accP2 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.z, bq[4 * t + 6], accP2, 0, 0, 0);
-        accP = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.w, bq[4 * t + 3], accP, 0, 0, 0);
-        accP2 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.w, bq[4 * t + 7], accP2, 0, 0, 0);
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+          accP[nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.x, bq[nb][4 * t + 0], accP[nb], 0, 0, 0);
+          accP2[nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.x, bq[nb][4 * t + 4], accP2[nb], 0, 0, 0);
+          accP[nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.y, bq[nb][4 * t + 1], accP[nb], 0, 0, 0);
+          accP2[nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.y, bq[nb][4 * t + 5], accP2[nb], 0, 0, 0);
+          accP[nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.z, bq[nb][4 * t + 2], accP[nb], 0, 0, 0);
+          accP2[nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.z, bq[nb][4 * t + 6], accP2[nb], 0, 0, 0);
+          accP[nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.w, bq[nb][4 * t + 3], accP[nb], 0, 0, 0);
+          accP2[nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.w, bq[nb][4 * t + 7], accP2[nb], 0, 0, 0);
+        }
       }
       wave_lds_fence();
     }
@@ -1562,15 +1644,66 @@ __device__ __forceinline__ void mfma_tile(const float* __restrict__ G, float* __
   if constexpr (ADD) {
     // P partial of the item = sum over the four wavefronts, added in wavefront order
 #pragma unroll
-    for (int v = 0; v < 16; ++v) lds[(8 * (v >> 2) + 4 * h + (v & 3)) * kLP + li] = accP[v] + accP2[v];
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+      for (int v = 0; v < 16; ++v)
+        lds[(8 * (v >> 2) + 4 * h + (v & 3)) * kLP + 32 * nb + li] = accP[nb][v] + accP2[nb][v];
     __syncthreads();
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < 4 * NB; ++i) {
       const int e = (int)threadIdx.x + 256 * i;
-      const int rr = e >> 5, k = e & 31;
+      const int rr = e / (32 * NB), k = e % (32 * NB);
       const float t = ((lds_all[0][rr * kLP + k] + lds_all[1][rr * kLP + k]) + lds_all[2][rr * kLP + k]) +
                       lds_all[3][rr * kLP + k];
       if (rr < nrows && k < r) Pp[(size_t)(row0 + rr) * r + k] = t;
+    }
+  }
+}
+
+// Rank pad 64, rows that are not 16-byte aligned (tiny layers): a plain loop, one wavefront over
+// the rows of its share, lanes over columns; the r dot products of a row go through wave sums.
+template <int MODE>
+__device__ __forceinline__ void plain_rows_fallback(const DevArgs& a, const LayerDesc& ld, const Tile& tl,
+                                                    const float* G, float* M, float* Pp, float* ghat_out,
+                                                    int col0, int col1, int lane) {
+  constexpr bool ADD = (MODE == kMAdd || MODE == kMAddFused);
+  constexpr bool NEEDG = (MODE != kMAdd);
+  const int cols = ld.cols, r = ld.r;
+  const float* Pb = a.Pbar + ld.p_off;
+  const float* Q = a.Qbar + ld.q_off;
+  for (int row = tl.row0; row < tl.row0 + tl.nrows; ++row) {
+    for (int k0 = 0; k0 < (ADD ? r : 1); ++k0) {
+      // add modes: pass k0 forms P[row][k0]; the tile itself is updated in pass 0 only
+      float dot = 0.0f;
+      for (int c = col0 + lane; c < col1; c += kWave) {
+        float m;
+        if (k0 == 0) {
+          float gh = 0.0f;
+          if constexpr (NEEDG)
+            for (int k = 0; k < r; ++k) gh = fmaf(Pb[(size_t)row * r + k], Q[(size_t)c * r + k], gh);
+          if constexpr (MODE == kMGhatOnly) {
+            const Pk<1> o{{gh}};
+            emit_ghat<1>(ghat_out + (size_t)row * cols, (unsigned)c * 4u, o, a.update, a.eta);
+            continue;
+          } else {
+            float e = M[(size_t)row * cols + c];
+            if constexpr (NEEDG) e -= gh;
+            m = ADD ? G[(size_t)row * cols + c] + e : e;
+            M[(size_t)row * cols + c] = m;
+            if (MODE == kMResidualGhat && ghat_out) {
+              const Pk<1> o{{gh}};
+              emit_ghat<1>(ghat_out + (size_t)row * cols, (unsigned)c * 4u, o, a.update, a.eta);
+            }
+          }
+        } else {
+          m = M[(size_t)row * cols + c];            // this lane wrote it in pass 0
+        }
+        if constexpr (ADD) dot = fmaf(m, Q[(size_t)c * r + k0], dot);
+      }
+      if constexpr (ADD) {
+        dot = wave_sum(dot);
+        if (lane == 0) Pp[(size_t)row * r + k0] = dot;
+      }
     }
   }
 }
@@ -1580,19 +1713,23 @@ template <int RP, int MODE>
 __device__ __forceinline__ void mfma_mode_vector_fallback(const DevArgs& a, const LayerDesc& ld, const Tile& tl, int worker,
                                                           const float* G, float* M, float* Pp, float* ghat_out,
                                                           int col0, int col1, int lane) {
-  if constexpr (MODE == kMAdd) {
-    add_project_tile<RP, 1, 4, false, false>(G, M, a.Qbar + ld.q_off, a.Pbar + ld.p_off, Pp, ld.cols, ld.r, tl.row0,
-                                             tl.nrows, col0, col1, lane);
-  } else if constexpr (MODE == kMAddFused) {
-    add_project_tile<RP, 1, 4, false, true>(G, M, a.Qbar + ld.q_off, a.Pbar + ld.p_off, Pp, ld.cols, ld.r, tl.row0,
-                                            tl.nrows, col0, col1, lane);
+  if constexpr (RP > 32) {
+    plain_rows_fallback<MODE>(a, ld, tl, G, M, Pp, ghat_out, col0, col1, lane);
   } else {
-    constexpr int RM = MODE == kMResidual ? kResidual : (MODE == kMResidualGhat ? kResidualGhat : kGhatOnly);
-    for (int c = col0 + lane; c < col1; c += kWave) {
-      float q[RP];
-      load_slice<RP, 1, false>(a.Qbar + ld.q_off, c, ld.r, q);
-      residual_rows<RP, 1, false, RM>(M, a.Pbar + ld.p_off, ghat_out, ld.cols, ld.r, tl.row0, tl.row0 + tl.nrows,
-                                      (unsigned)c * 4u, q, a.update, a.eta);
+    if constexpr (MODE == kMAdd) {
+      add_project_tile<RP, 1, 4, false, false>(G, M, a.Qbar + ld.q_off, a.Pbar + ld.p_off, Pp, ld.cols, ld.r, tl.row0,
+                                               tl.nrows, col0, col1, lane);
+    } else if constexpr (MODE == kMAddFused) {
+      add_project_tile<RP, 1, 4, false, true>(G, M, a.Qbar + ld.q_off, a.Pbar + ld.p_off, Pp, ld.cols, ld.r, tl.row0,
+                                              tl.nrows, col0, col1, lane);
+    } else {
+      constexpr int RM = MODE == kMResidual ? kResidual : (MODE == kMResidualGhat ? kResidualGhat : kGhatOnly);
+      for (int c = col0 + lane; c < col1; c += kWave) {
+        float q[RP];
+        load_slice<RP, 1, false>(a.Qbar + ld.q_off, c, ld.r, q);
+        residual_rows<RP, 1, false, RM>(M, a.Pbar + ld.p_off, ghat_out, ld.cols, ld.r, tl.row0, tl.row0 + tl.nrows,
+                                        (unsigned)c * 4u, q, a.update, a.eta);
+      }
     }
   }
 }
@@ -1648,6 +1785,11 @@ __global__ __launch_bounds__(256, RP <= 16 ? 2 : 1) void mfma_sweep_kernel(DevAr
     case 32: { constexpr int RP = 32; CALL; } break; \
     default: return hipErrorInvalidValue;     \
   }
+
+// The Gram-Schmidt kernels also exist at rank pad 64 (the streaming sweeps run on the matrix cores there).
+#define LQSGD_RP_SWITCH_ORTH(RPV, CALL)                 \
+  if ((RPV) == 64) { constexpr int RP = 64; CALL; } else \
+    LQSGD_RP_SWITCH(RPV, CALL)
 
 hipError_t launch_add_project(int rp, const DevArgs& a, const Tile* tiles, int ntiles, int fuse_residual, int reverse,
                               hipStream_t s) {
@@ -1722,6 +1864,7 @@ bool launch_orth_coop(int rp, int nslice, int max_rank, const DevArgs& a, int nb
     case 8: return try_orth_coop<8>(nslice, max_rank, a, nblocks, epoch, s);
     case 16: return try_orth_coop<16>(nslice, max_rank, a, nblocks, epoch, s);
     case 32: return try_orth_coop<32>(nslice, max_rank, a, nblocks, epoch, s);
+    case 64: return try_orth_coop<64>(nslice, max_rank, a, nblocks, epoch, s);
     default: return false;
   }
 }
@@ -1737,20 +1880,20 @@ hipError_t launch_orth(int rp, int max_rows, int max_rank, const DevArgs& a, uns
   if (a.orth_part && nslice >= 8 && ((int)grid.x < 128 || !reg_fits)) {
     if (launch_orth_coop(rp, nslice, max_rank, a, (int)grid.x * nslice, coop_epoch, s)) return hipSuccess;
     for (int j = 0; j <= max_rank; ++j) {
-      LQSGD_RP_SWITCH(rp, (orth_wide_kernel<RP><<<dim3(grid.x * nslice), dim3(256), 0, s>>>(a, j, nslice)));
+      LQSGD_RP_SWITCH_ORTH(rp, (orth_wide_kernel<RP><<<dim3(grid.x * nslice), dim3(256), 0, s>>>(a, j, nslice)));
     }
     return hipGetLastError();
   }
   if (max_rows <= 512) {
-    LQSGD_RP_SWITCH(rp, (launch_orth_reg<RP, 2, 256>(a, grid, s)));
+    LQSGD_RP_SWITCH_ORTH(rp, (launch_orth_reg<RP, 2, 256>(a, grid, s)));
   } else if (max_rows <= 2048) {
-    LQSGD_RP_SWITCH(rp, (launch_orth_reg<RP, 8, 256>(a, grid, s)));
+    LQSGD_RP_SWITCH_ORTH(rp, (launch_orth_reg<RP, 8, 256>(a, grid, s)));
   } else if (max_rows <= 4096) {
-    LQSGD_RP_SWITCH(rp, (launch_orth_reg<RP, 4, 1024>(a, grid, s)));
+    LQSGD_RP_SWITCH_ORTH(rp, (launch_orth_reg<RP, 4, 1024>(a, grid, s)));
   } else if (max_rows <= 11264) {
-    LQSGD_RP_SWITCH(rp, (launch_orth_reg<RP, 11, 1024>(a, grid, s)));
+    LQSGD_RP_SWITCH_ORTH(rp, (launch_orth_reg<RP, 11, 1024>(a, grid, s)));
   } else {
-    LQSGD_RP_SWITCH(rp, (orth_kernel<RP><<<grid, dim3(256), 0, s>>>(a)));
+    LQSGD_RP_SWITCH_ORTH(rp, (orth_kernel<RP><<<grid, dim3(256), 0, s>>>(a)));
   }
   return hipGetLastError();
 }
@@ -1775,10 +1918,13 @@ hipError_t launch_back_project(int rp, const DevArgs& a, const Tile* tiles, int 
   return hipGetLastError();
 }
 
-hipError_t launch_back_project_mfma(const DevArgs& a, const Tile* tiles, int ntiles, const VTile* vtiles, int nvtiles,
+hipError_t launch_back_project_mfma(int rp, const DevArgs& a, const Tile* tiles, int ntiles, const VTile* vtiles, int nvtiles,
                                     int reverse, hipStream_t s) {
   if (ntiles + nvtiles <= 0) return hipSuccess;
-  back_project_mfma_kernel<<<dim3(ntiles + nvtiles), dim3(256), 0, s>>>(a, tiles, ntiles, vtiles, reverse);
+  if (rp == 64)
+    back_project_mfma_kernel<2><<<dim3(ntiles + nvtiles), dim3(256), 0, s>>>(a, tiles, ntiles, vtiles, reverse);
+  else
+    back_project_mfma_kernel<1><<<dim3(ntiles + nvtiles), dim3(256), 0, s>>>(a, tiles, ntiles, vtiles, reverse);
   return hipGetLastError();
 }
 
@@ -1818,6 +1964,7 @@ hipError_t launch_mfma_sweep(int rp, int mode, const DevArgs& a, const Tile* til
   if (ntiles <= 0) return hipSuccess;
   if (rp == 16) return launch_mfma_sweep_rp<16>(mode, a, tiles, ntiles, reverse, s);
   if (rp == 32) return launch_mfma_sweep_rp<32>(mode, a, tiles, ntiles, reverse, s);
+  if (rp == 64) return launch_mfma_sweep_rp<64>(mode, a, tiles, ntiles, reverse, s);
   return hipErrorInvalidValue;
 }
 

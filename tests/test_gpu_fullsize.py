@@ -55,7 +55,7 @@ def test_sweep_8192_full_size():
     _sampled_run(w, [0], [0, 7, 15], steps=2)
 
 
-@pytest.mark.parametrize("rank,bits", [(1, 2), (2, 4), (8, 8), (16, 4), (32, 8)])
+@pytest.mark.parametrize("rank,bits", [(1, 2), (2, 4), (8, 8), (16, 4), (32, 8), (50, 8)])
 def test_sweep_8192_other_ranks(rank, bits):
     """The other points of the rank / bit-width sweep at the full matrix size,
     with four workers (the per-worker kernels do not depend on W)."""

@@ -115,6 +115,9 @@ EDGE_CASES = [
     ([(100, 1100), (33, 64)], 20, 8, 8, 2, 255.0),         # rank 20 in a rank pad of 32
     ([(70, 200)], 12, 8, 8, 2, 255.0),                     # rank 12 in a rank pad of 16
     ([(40, 36)], 32, 8, 8, 2, 255.0),                      # rank 32 clipped to 36 cols / 40 rows
+    ([(100, 1100), (70, 200)], 50, 8, 8, 2, 255.0),        # rank 50 in a rank pad of 64 (two blocks of 32 ranks)
+    ([(96, 520)], 64, 8, 8, 2, 255.0),
+    ([(129, 131), (300, 64)], 40, 8, 4, 2, 255.0),         # pad 64 with unaligned rows (plain fallback) and a clipped rank
     ([(257, 513)], 4, 1, 1, 2, 255.0),
     ([(257, 513)], 4, 3, 5, 2, 255.0),
     ([(257, 513)], 4, 0, 0, 4, 255.0),                     # quantisation off
@@ -327,6 +330,7 @@ def test_resnet18_free_run_matches_oracle_and_is_deterministic():
     ([(96, 520)], 16, 8, 2),
     ([(96, 520), (40, 36), (70, 27), (200, 1100)], 32, 8, 2),     # matrix-core path, clipped ranks, unaligned rows
     ([(130, 260)], 20, 4, 3),                                      # rank pad 32 with rank 20
+    ([(200, 1100), (70, 27), (96, 520)], 50, 8, 2),                # rank pad 64
 ])
 def test_deferred_residual_is_bit_identical_to_eager(layers, rank, bits, W):
     import torch

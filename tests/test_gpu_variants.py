@@ -34,6 +34,7 @@ AGG_CASES = [
     ([(100, 1100), (33, 64)], 20, 8, 8, 2),          # rank pad 32
     ([(2304, 96)], 4, 8, 8, 1),                      # one worker, tall: one-launch many-workgroup Gram-Schmidt
     ([(4608, 64)], 32, 8, 8, 2),                     # tall + rank 32: the same on the aggregate, 18 slices
+    ([(2304, 72), (70, 200)], 50, 8, 8, 2),          # rank pad 64
 ]
 
 
@@ -152,6 +153,7 @@ def _ulp_close(got, want, frac=1e-5):
     ([(64, 576), (128, 64)], 4, 8, 4, B.FLAG_EAGER_RESIDUAL),
     ([(129, 1028), (70, 200)], 16, 8, 2, 0),                       # matrix-core G-hat pass
     ([(96, 520)], 32, 4, 2, B.FLAG_EAGER_RESIDUAL),
+    ([(96, 520), (129, 131)], 50, 8, 2, 0),                        # rank pad 64, with an unaligned layer
     ([(300, 260)], 3, 0, 3, B.FLAG_AGGREGATE_FIRST),
 ])
 def test_model_update(layers, rank, bits, W, flags):

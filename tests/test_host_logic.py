@@ -29,7 +29,7 @@ def test_kernel_names():
 
 
 @pytest.mark.parametrize("kw,code", [
-    (dict(rank=0), B.EINVAL), (dict(rank=33), B.EUNSUPPORTED), (dict(bits_p=9), B.EINVAL),
+    (dict(rank=0), B.EINVAL), (dict(rank=65), B.EUNSUPPORTED), (dict(bits_p=9), B.EINVAL),
     (dict(bits_q=-1), B.EINVAL), (dict(workers=0), B.EINVAL), (dict(workers=65), B.EINVAL),
     (dict(alpha=0.0), B.EINVAL), (dict(alpha=float("nan")), B.EINVAL),
     (dict(layers=[(0, 4, 0)]), B.ESHAPE), (dict(layers=[(4, -1, 0)]), B.ESHAPE),
