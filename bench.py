@@ -22,7 +22,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
 
 
-def sweep_bytes(kernel, w, ghat, eager):
+def sweep_bytes(kernel, w, ghat, eager, bf16=False):
     """Algorithmic HBM bytes of one launch of a streaming kernel: bytes per
     gradient element of one worker x elements, as the design document derives
     them (sweep 0: read G, read M/E, write M = 12 B; sweep 1: read M = 4 B;
@@ -32,7 +32,7 @@ def sweep_bytes(kernel, w, ghat, eager):
     e1 = w.elements_per_worker
     e = w.workers * e1
     if kernel == "add_project_kernel":
-        return 12.0 * e
+        return (10.0 if bf16 else 12.0) * e
     if kernel == "back_project_kernel":
         return 4.0 * e
     if kernel == "residual_kernel":
@@ -61,6 +61,8 @@ def main():
                          "traffic for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     ap.add_argument("--aggregate-first", action="store_true",
                     help="the PowerSGD order: exchange the raw P factors, orthonormalise the aggregate once")
+    ap.add_argument("--bf16-grads", action="store_true",
+                    help="hand the gradients over in bfloat16 (the first sweep then reads 10 instead of 12 bytes per element)")
     ap.add_argument("--update", type=float, default=None, metavar="ETA",
                     help="apply w <- w - ETA G-hat to synthetic parameters inside the step instead of storing G-hat")
     args = ap.parse_args()
@@ -108,12 +110,15 @@ def main():
         row = [wl.device_gradient(w, 0, l, k) for l in range(L)]
         row += [torch.from_numpy(wl.vector_gradient(w, 0, v, k)).cuda() for v in range(V)]
         grads.append(row)
+    if args.bf16_grads:
+        grads = [[t.to(torch.bfloat16) for t in row] for row in grads]
     ghat = None
     if not args.no_ghat:
         ghat = [torch.empty(s, device="cuda") for s in w.layers] + [torch.empty(n, device="cuda") for n in w.vectors]
     comp = B.Compressor(B.layer_list(w.layers, w.vectors), w.rank, w.bits, w.bits, W, w.alpha,
                         (B.FLAG_EAGER_RESIDUAL if args.eager else 0) |
-                        (B.FLAG_AGGREGATE_FIRST if args.aggregate_first else 0))
+                        (B.FLAG_AGGREGATE_FIRST if args.aggregate_first else 0) |
+                        (B.FLAG_BF16_GRADIENTS if args.bf16_grads else 0))
     q0 = [wl.initial_q(w, l) for l in range(L)]
     for l in range(L):
         comp.set_q(l, q0[l])
@@ -158,7 +163,7 @@ def main():
                 name = B.kernel_name(k) + ("_q" if k == B.KERNEL_EXCHANGE_Q else "_p" if k == B.KERNEL_EXCHANGE_P else "")
                 kernels[name] = {"avg_us": 1e3 * ms[k] / cnt[k], "launches": cnt[k]}
         dom = max((k for k in kernels), key=lambda n: kernels[n]["avg_us"])
-        alg = sweep_bytes(dom, w, ghat_mode, args.eager)
+        alg = sweep_bytes(dom, w, ghat_mode, args.eager, args.bf16_grads)
         if alg:
             achieved = alg / (kernels[dom]["avg_us"] * 1e-6) / 1e9
             roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
@@ -167,7 +172,7 @@ def main():
                         "algorithmic_bytes_per_launch": alg,
                         "avg_launch_us": round(kernels[dom]["avg_us"], 2)}
         for n, d in kernels.items():
-            alg = sweep_bytes(n, w, ghat_mode, args.eager)
+            alg = sweep_bytes(n, w, ghat_mode, args.eager, args.bf16_grads)
             if alg:
                 d["hbm_frac"] = round(alg / (d["avg_us"] * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)
             d["avg_us"] = round(d["avg_us"], 2)
@@ -177,7 +182,7 @@ def main():
     if not args.no_cpu_baseline:
         cpu = _cpu_baseline(w, grads, q0)
 
-    step_bytes = sum(sweep_bytes(k, w, ghat_mode, args.eager)
+    step_bytes = sum(sweep_bytes(k, w, ghat_mode, args.eager, args.bf16_grads)
                      for k in ("add_project_kernel", "back_project_kernel", "residual_kernel"))
     out = {
         "metric": "compressed gradient GB/s per LQ-SGD step (ResNet-18 set, r=4) and % HBM peak",
@@ -189,6 +194,7 @@ def main():
                       ("applied to parameters (eta=%g)" % args.update) if (ghat is not None and args.update is not None)
                       else "written" if ghat is not None else "not written",
                       "at the end of each step" if args.eager else "fused into the next step's first sweep"),
+                   "gradient_dtype": "bf16" if args.bf16_grads else "f32",
                    "order": "aggregate, then orthonormalise" if args.aggregate_first else "orthonormalise, then aggregate (Algorithm 1)",
                    "rank": w.rank, "bits": w.bits, "workers": W, "gradient_bytes_per_step": grad_bytes},
         "step_algorithmic_bytes": step_bytes,

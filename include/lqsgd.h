@@ -78,6 +78,13 @@ typedef struct {
  * not exist (EINVAL), LQSGD_FACTOR_P_MEAN is the aggregate before Gram-Schmidt
  * and LQSGD_FACTOR_P_BAR the orthonormalised aggregate that Q_w, G-hat and E use. */
 #define LQSGD_FLAG_AGGREGATE_FIRST 2u
+/* The gradient tensors (matrix and VECTOR layers alike) hold bfloat16 values
+ * instead of fp32: grads[w * n_layers + l] then points to rows x cols 2-byte
+ * elements, row-major, still 16-byte aligned.  Each value is widened exactly
+ * (a bfloat16 is the upper half of a float) when G' = G + E is formed;
+ * everything after that, the state and the outputs are fp32 as always.  The
+ * first sweep then reads 2 bytes per element less. */
+#define LQSGD_FLAG_BF16_GRADIENTS 4u
 
 /* The "Require" line of Algorithm 1, plus the number of simulated workers. */
 typedef struct {

@@ -15,7 +15,7 @@ LIB_PATH = os.environ.get("LQSGD_LIB") or os.path.join(_HERE, "liblqsgd.so")
 
 OK, EINVAL, ESHAPE, EUNSUPPORTED, ENOMEM, EHIP, ESTATE = 0, -1, -2, -3, -4, -5, -6
 LAYER_MATRIX, LAYER_VECTOR = 0, 1
-FLAG_NONE, FLAG_EAGER_RESIDUAL, FLAG_AGGREGATE_FIRST = 0, 1, 2
+FLAG_NONE, FLAG_EAGER_RESIDUAL, FLAG_AGGREGATE_FIRST, FLAG_BF16_GRADIENTS = 0, 1, 2, 4
 PHASE_P, PHASE_Q = 0, 1
 FACTOR_P_PRE, FACTOR_P_ORTH, FACTOR_P_BAR, FACTOR_Q_W, FACTOR_Q_BAR, FACTOR_VMEAN, FACTOR_P_MEAN = range(7)
 (KERNEL_ADD_PROJECT, KERNEL_ORTH, KERNEL_EXCHANGE_P, KERNEL_BACK_PROJECT, KERNEL_REDUCE_Q,

@@ -390,6 +390,7 @@ int lqsgd_create(const lqsgd_config* cfg, const lqsgd_layer* layers, int32_t n_l
   a.W = p.W; a.L = p.L; a.n_all = p.n_all; a.bits_p = p.cfg.bits_p; a.bits_q = p.cfg.bits_q;
   a.alpha = p.cfg.alpha;
   a.agg_first = p.agg_first ? 1 : 0; a.orth_shared = 0; a.update = 0; a.eta = 0.0f;
+  a.g_bf16 = (cfg->flags & LQSGD_FLAG_BF16_GRADIENTS) ? 1 : 0;
   a.qscale_p = (float)(((1 << p.cfg.bits_p) - 1) / std::log2(1.0 + (double)p.cfg.alpha));
   a.qscale_q = (float)(((1 << p.cfg.bits_q) - 1) / std::log2(1.0 + (double)p.cfg.alpha));
   a.m_stride = p.m_stride; a.p_stride = p.p_stride; a.q_stride = p.q_stride;

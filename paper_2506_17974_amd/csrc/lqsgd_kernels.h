@@ -12,7 +12,7 @@ namespace lqsgd {
 struct DevArgs {
   const LayerDesc* layers;
   const VecDesc* vecs;
-  const float* const* grads;   // W * n_all gradient tensors
+  const float* const* grads;   // W * n_all gradient tensors (fp32, or bfloat16 behind the same pointer type if g_bf16)
   float* const* ghat;          // n_all optional outputs (entries may be null), or null
   float* E;                    // residual / M = G + E, per worker
   float* Ppart;                // sweep-0 partial products, per worker
@@ -37,6 +37,7 @@ struct DevArgs {
   float qscale_p, qscale_q;    // (2^b - 1) / log2(1 + alpha) for b_p, b_q
   int32_t agg_first;           // aggregate-first order: scaleP is an atomic-max accumulator (sweep 0 zeroes it)
   int32_t orth_shared;         // the Gram-Schmidt kernels run once per layer, in place on the plane at Ppart + p_off
+  int32_t g_bf16;              // the gradient tensors hold bfloat16 values (G-hat / parameters stay fp32)
   int32_t update;              // G-hat outputs are parameters to update: w <- w - eta G-hat
   float eta;
 };

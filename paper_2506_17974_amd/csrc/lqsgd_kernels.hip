@@ -90,6 +90,40 @@ template <>
 __device__ __forceinline__ Pk<1> ldrow<1, true>(const char* rowbase, unsigned boff) {
   return Pk<1>{{__builtin_nontemporal_load(reinterpret_cast<const float*>(rowbase + boff))}};
 }
+// The same for a row of bfloat16 values (gradients handed over in bfloat16): boff is the byte
+// offset the fp32 loaders would use; a bfloat16 is the upper half of the float it stands for.
+typedef unsigned int v2u __attribute__((ext_vector_type(2)));
+template <int V, bool NT>
+__device__ __forceinline__ Pk<V> ldrow_bf16(const char* rowbase, unsigned boff) {
+  Pk<V> r;
+  if constexpr (V == 4) {
+    const v2u* p = reinterpret_cast<const v2u*>(rowbase + (boff >> 1));
+    const v2u t = NT ? __builtin_nontemporal_load(p) : *p;
+    r.v[0] = __uint_as_float(t.x << 16); r.v[1] = __uint_as_float(t.x & 0xffff0000u);
+    r.v[2] = __uint_as_float(t.y << 16); r.v[3] = __uint_as_float(t.y & 0xffff0000u);
+  } else {
+    const unsigned short t = *reinterpret_cast<const unsigned short*>(rowbase + (boff >> 1));
+    r.v[0] = __uint_as_float((unsigned)t << 16);
+  }
+  return r;
+}
+// Gradient row in either format.
+template <int V, bool NT, bool GB16>
+__device__ __forceinline__ Pk<V> ldgrad(const char* rowbase, unsigned boff) {
+  if constexpr (GB16) return ldrow_bf16<V, NT>(rowbase, boff);
+  else return ldrow<V, NT>(rowbase, boff);
+}
+// Start of gradient row `off / cols` given its element offset.
+template <bool GB16>
+__device__ __forceinline__ const char* grad_row(const float* G, size_t off) {
+  return reinterpret_cast<const char*>(G) + off * (GB16 ? 2 : 4);
+}
+template <bool GB16>
+__device__ __forceinline__ float grad_elem(const float* G, size_t idx) {
+  if constexpr (GB16) return __uint_as_float((unsigned)reinterpret_cast<const unsigned short*>(G)[idx] << 16);
+  else return G[idx];
+}
+
 template <int V, bool NT>
 __device__ __forceinline__ void strow(char* rowbase, unsigned boff, const Pk<V>& x);
 template <>
@@ -254,7 +288,7 @@ constexpr int log2c(int n) { return n <= 1 ? 0 : 1 + log2c(n / 2); }
 // RT rows at a time; a lane accumulates RT x r partial dot products over its
 // columns, one butterfly per row group adds them over the lanes.
 // ---------------------------------------------------------------------------
-template <int RP, int VEC, int RT, bool EXACT, bool FULL, bool FUSE>
+template <int RP, int VEC, int RT, bool EXACT, bool FULL, bool FUSE, bool GB16>
 __device__ __forceinline__ void add_project_cols(const char* const (&gr)[RT], char* const (&mr)[RT],
                                                  const float* __restrict__ Q, const float (&pb)[RT * RP], int r, int nr,
                                                  int cbeg, int cend, float (&acc)[RT * RP]) {
@@ -266,7 +300,7 @@ __device__ __forceinline__ void add_project_cols(const char* const (&gr)[RT], ch
 #pragma unroll
     for (int t = 0; t < RT; ++t) {
       if (FULL || t < nr) {
-        g[t] = ldrow<VEC, LQSGD_NT_G != 0>(gr[t], boff);
+        g[t] = ldgrad<VEC, LQSGD_NT_G != 0, GB16>(gr[t], boff);
         e[t] = ldrow<VEC, LQSGD_NT_E != 0>(mr[t], boff);
       } else {
 #pragma unroll
@@ -298,7 +332,7 @@ __device__ __forceinline__ void add_project_cols(const char* const (&gr)[RT], ch
   }
 }
 
-template <int RP, int VEC, int RT, bool EXACT, bool FUSE>
+template <int RP, int VEC, int RT, bool EXACT, bool FUSE, bool GB16 = false>
 __device__ __forceinline__ void add_project_tile(const float* __restrict__ G, float* __restrict__ M,
                                                  const float* __restrict__ Q, const float* Pb,
                                                  float* __restrict__ Pp, int cols, int r, int row0, int nrows,
@@ -316,7 +350,7 @@ __device__ __forceinline__ void add_project_tile(const float* __restrict__ G, fl
     for (int t = 0; t < RT; ++t) {
       const int row = row0 + rg + min(t, nr - 1);
       const size_t off = (size_t)row * cols;
-      gr[t] = reinterpret_cast<const char*>(G + off);
+      gr[t] = grad_row<GB16>(G, off);
       mr[t] = reinterpret_cast<char*>(M + off);
       if constexpr (FUSE) {
         float p[RP];
@@ -329,9 +363,9 @@ __device__ __forceinline__ void add_project_tile(const float* __restrict__ G, fl
       }
     }
     if (nr == RT)
-      add_project_cols<RP, VEC, RT, EXACT, true, FUSE>(gr, mr, Q, pb, r, nr, col0 + lane * VEC, col1, acc);
+      add_project_cols<RP, VEC, RT, EXACT, true, FUSE, GB16>(gr, mr, Q, pb, r, nr, col0 + lane * VEC, col1, acc);
     else
-      add_project_cols<RP, VEC, RT, EXACT, false, FUSE>(gr, mr, Q, pb, r, nr, col0 + lane * VEC, col1, acc);
+      add_project_cols<RP, VEC, RT, EXACT, false, FUSE, GB16>(gr, mr, Q, pb, r, nr, col0 + lane * VEC, col1, acc);
     transpose_reduce<N, N, 32>(acc, lane);
     constexpr int NPL = (N >= kWave) ? N / kWave : 1;
 #pragma unroll
@@ -354,7 +388,7 @@ __device__ __forceinline__ void add_project_tile(const float* __restrict__ G, fl
 // FUSE: the residual update of the previous iteration has been deferred; the
 // buffer holds M_{t-1} and this sweep forms E_{t-1} = M_{t-1} - P-bar Q-bar^T on
 // the fly (Q-bar is the warm-start Q this sweep multiplies by anyway).
-template <int RP, bool FUSE>
+template <int RP, bool FUSE, bool GB16>
 __global__ __launch_bounds__(256, LQSGD_A_WAVES) void add_project_kernel(DevArgs a, const Tile* __restrict__ tiles, int ntiles, int reverse) {
   constexpr int RT = (RP <= 8) ? LQSGD_RT : 4;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -375,12 +409,12 @@ __global__ __launch_bounds__(256, LQSGD_A_WAVES) void add_project_kernel(DevArgs
   const int col1 = min(ld.cols, col0 + ld.segw);
   if (ld.vec == 4) {
     if (ld.r == RP)
-      add_project_tile<RP, 4, RT, true, FUSE>(G, M, Q, Pb, Pp, ld.cols, ld.r, tl.row0, tl.nrows, col0, col1, lane);
+      add_project_tile<RP, 4, RT, true, FUSE, GB16>(G, M, Q, Pb, Pp, ld.cols, ld.r, tl.row0, tl.nrows, col0, col1, lane);
     else
-      add_project_tile<RP, 4, RT, false, FUSE>(G, M, Q, Pb, Pp, ld.cols, ld.r, tl.row0, tl.nrows, col0, col1, lane);
+      add_project_tile<RP, 4, RT, false, FUSE, GB16>(G, M, Q, Pb, Pp, ld.cols, ld.r, tl.row0, tl.nrows, col0, col1, lane);
   } else {
     // rows that are not 16-byte aligned (cols % 4 != 0): tiny layers, one generic path
-    add_project_tile<RP, 1, RT, false, FUSE>(G, M, Q, Pb, Pp, ld.cols, ld.r, tl.row0, tl.nrows, col0, col1, lane);
+    add_project_tile<RP, 1, RT, false, FUSE, GB16>(G, M, Q, Pb, Pp, ld.cols, ld.r, tl.row0, tl.nrows, col0, col1, lane);
   }
 }
 
@@ -1077,7 +1111,11 @@ __device__ __forceinline__ void vector_mean_tile(const DevArgs& a, const VTile& 
     const int e = tl.el0 + i * 256 + threadIdx.x;
     if (e < vd.len) {
       float s = 0.0f;
-      for (int w = 0; w < a.W; ++w) s += a.grads[(size_t)w * a.n_all + vd.gidx][e];
+      if (a.g_bf16) {
+        for (int w = 0; w < a.W; ++w) s += grad_elem<true>(a.grads[(size_t)w * a.n_all + vd.gidx], (size_t)e);
+      } else {
+        for (int w = 0; w < a.W; ++w) s += a.grads[(size_t)w * a.n_all + vd.gidx][e];
+      }
       s /= wf;
       a.vmean[vd.off + e] = s;
       if (extra) extra[e] = a.update ? fmaf(-a.eta, s, extra[e]) : s;
@@ -1471,7 +1509,7 @@ __device__ __forceinline__ void wave_lds_fence() {
   __builtin_amdgcn_wave_barrier();
 }
 
-template <int RP, int MODE, bool EXACT>
+template <int RP, int MODE, bool EXACT, bool GB16>
 __device__ __forceinline__ void mfma_tile(const float* __restrict__ G, float* __restrict__ M,
                                           const float* Q, const float* Pb, float* __restrict__ Pp,
                                           float* __restrict__ ghat_out, int cols, int r, int row0, int nrows,
@@ -1528,7 +1566,7 @@ __device__ __forceinline__ void mfma_tile(const float* __restrict__ G, float* __
 #pragma unroll
       for (int v = 0; v < 4; ++v) { g[i].v[v] = 0.0f; e[i].v[v] = 0.0f; }
       if (ok) {
-        if constexpr (ADD) g[i] = ldrow<4, LQSGD_NT_G != 0>(reinterpret_cast<const char*>(G + off), (unsigned)cl * 4u);
+        if constexpr (ADD) g[i] = ldgrad<4, LQSGD_NT_G != 0, GB16>(grad_row<GB16>(G, off), (unsigned)cl * 4u);
         if constexpr (HASM) e[i] = ldrow<4, LQSGD_NT_E != 0>(reinterpret_cast<const char*>(M + off), (unsigned)cl * 4u);
       }
     }
@@ -1662,7 +1700,7 @@ __device__ __forceinline__ void mfma_tile(const float* __restrict__ G, float* __
 
 // Rank pad 64, rows that are not 16-byte aligned (tiny layers): a plain loop, one wavefront over
 // the rows of its share, lanes over columns; the r dot products of a row go through wave sums.
-template <int MODE>
+template <int MODE, bool GB16>
 __device__ __forceinline__ void plain_rows_fallback(const DevArgs& a, const LayerDesc& ld, const Tile& tl,
                                                     const float* G, float* M, float* Pp, float* ghat_out,
                                                     int col0, int col1, int lane) {
@@ -1688,7 +1726,7 @@ __device__ __forceinline__ void plain_rows_fallback(const DevArgs& a, const Laye
           } else {
             float e = M[(size_t)row * cols + c];
             if constexpr (NEEDG) e -= gh;
-            m = ADD ? G[(size_t)row * cols + c] + e : e;
+            m = ADD ? grad_elem<GB16>(G, (size_t)row * cols + c) + e : e;
             M[(size_t)row * cols + c] = m;
             if (MODE == kMResidualGhat && ghat_out) {
               const Pk<1> o{{gh}};
@@ -1709,18 +1747,18 @@ __device__ __forceinline__ void plain_rows_fallback(const DevArgs& a, const Laye
 }
 
 // rows that are not 16-byte aligned (cols % 4 != 0; tiny layers): vector units
-template <int RP, int MODE>
+template <int RP, int MODE, bool GB16>
 __device__ __forceinline__ void mfma_mode_vector_fallback(const DevArgs& a, const LayerDesc& ld, const Tile& tl, int worker,
                                                           const float* G, float* M, float* Pp, float* ghat_out,
                                                           int col0, int col1, int lane) {
   if constexpr (RP > 32) {
-    plain_rows_fallback<MODE>(a, ld, tl, G, M, Pp, ghat_out, col0, col1, lane);
+    plain_rows_fallback<MODE, GB16>(a, ld, tl, G, M, Pp, ghat_out, col0, col1, lane);
   } else {
     if constexpr (MODE == kMAdd) {
-      add_project_tile<RP, 1, 4, false, false>(G, M, a.Qbar + ld.q_off, a.Pbar + ld.p_off, Pp, ld.cols, ld.r, tl.row0,
+      add_project_tile<RP, 1, 4, false, false, GB16>(G, M, a.Qbar + ld.q_off, a.Pbar + ld.p_off, Pp, ld.cols, ld.r, tl.row0,
                                                tl.nrows, col0, col1, lane);
     } else if constexpr (MODE == kMAddFused) {
-      add_project_tile<RP, 1, 4, false, true>(G, M, a.Qbar + ld.q_off, a.Pbar + ld.p_off, Pp, ld.cols, ld.r, tl.row0,
+      add_project_tile<RP, 1, 4, false, true, GB16>(G, M, a.Qbar + ld.q_off, a.Pbar + ld.p_off, Pp, ld.cols, ld.r, tl.row0,
                                               tl.nrows, col0, col1, lane);
     } else {
       constexpr int RM = MODE == kMResidual ? kResidual : (MODE == kMResidualGhat ? kResidualGhat : kGhatOnly);
@@ -1736,7 +1774,7 @@ __device__ __forceinline__ void mfma_mode_vector_fallback(const DevArgs& a, cons
 
 // Wavefronts per SIMD the register allocation aims for: two at rank pad 16 (2.65 -> 2.47 ms on
 // 8192^2 x 16 workers), one at rank pad 32, where two would spill (3.0 -> 4.6 ms).
-template <int RP, int MODE>
+template <int RP, int MODE, bool GB16 = false>
 __global__ __launch_bounds__(256, RP <= 16 ? 2 : 1) void mfma_sweep_kernel(DevArgs a, const Tile* __restrict__ tiles, int ntiles, int reverse) {
   __shared__ __attribute__((aligned(16))) float lds_all[4][32 * kLP];
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -1759,14 +1797,14 @@ __global__ __launch_bounds__(256, RP <= 16 ? 2 : 1) void mfma_sweep_kernel(DevAr
     Tile sub = tl;
     sub.row0 = tl.row0 + 8 * wave;
     sub.nrows = min(8, tl.nrows - 8 * wave);
-    if (sub.nrows > 0) mfma_mode_vector_fallback<RP, MODE>(a, ld, sub, worker, G, M, Pp, ghat_out, col0, col1, lane);
+    if (sub.nrows > 0) mfma_mode_vector_fallback<RP, MODE, GB16>(a, ld, sub, worker, G, M, Pp, ghat_out, col0, col1, lane);
     return;
   }
   if (ld.r == RP)
-    mfma_tile<RP, MODE, true>(G, M, a.Qbar + ld.q_off, a.Pbar + ld.p_off, Pp, ghat_out, ld.cols, ld.r, tl.row0,
+    mfma_tile<RP, MODE, true, GB16>(G, M, a.Qbar + ld.q_off, a.Pbar + ld.p_off, Pp, ghat_out, ld.cols, ld.r, tl.row0,
                               tl.nrows, col0, col1, lane, wave, lds_all, a.update, a.eta);
   else
-    mfma_tile<RP, MODE, false>(G, M, a.Qbar + ld.q_off, a.Pbar + ld.p_off, Pp, ghat_out, ld.cols, ld.r, tl.row0,
+    mfma_tile<RP, MODE, false, GB16>(G, M, a.Qbar + ld.q_off, a.Pbar + ld.p_off, Pp, ghat_out, ld.cols, ld.r, tl.row0,
                                tl.nrows, col0, col1, lane, wave, lds_all, a.update, a.eta);
 }
 
@@ -1795,10 +1833,16 @@ hipError_t launch_add_project(int rp, const DevArgs& a, const Tile* tiles, int n
                               hipStream_t s) {
   if (ntiles <= 0) return hipSuccess;
   const dim3 grid((ntiles + 3) / 4), block(256);
-  if (fuse_residual) {
-    LQSGD_RP_SWITCH(rp, (add_project_kernel<RP, true><<<grid, block, 0, s>>>(a, tiles, ntiles, reverse)));
+  if (a.g_bf16) {
+    if (fuse_residual) {
+      LQSGD_RP_SWITCH(rp, (add_project_kernel<RP, true, true><<<grid, block, 0, s>>>(a, tiles, ntiles, reverse)));
+    } else {
+      LQSGD_RP_SWITCH(rp, (add_project_kernel<RP, false, true><<<grid, block, 0, s>>>(a, tiles, ntiles, reverse)));
+    }
+  } else if (fuse_residual) {
+    LQSGD_RP_SWITCH(rp, (add_project_kernel<RP, true, false><<<grid, block, 0, s>>>(a, tiles, ntiles, reverse)));
   } else {
-    LQSGD_RP_SWITCH(rp, (add_project_kernel<RP, false><<<grid, block, 0, s>>>(a, tiles, ntiles, reverse)));
+    LQSGD_RP_SWITCH(rp, (add_project_kernel<RP, false, false><<<grid, block, 0, s>>>(a, tiles, ntiles, reverse)));
   }
   return hipGetLastError();
 }
@@ -1950,8 +1994,14 @@ template <int RP>
 hipError_t launch_mfma_sweep_rp(int mode, const DevArgs& a, const Tile* tiles, int ntiles, int reverse, hipStream_t s) {
   const dim3 grid(ntiles), block(256);
   switch (mode) {
-    case kMAdd: mfma_sweep_kernel<RP, kMAdd><<<grid, block, 0, s>>>(a, tiles, ntiles, reverse); break;
-    case kMAddFused: mfma_sweep_kernel<RP, kMAddFused><<<grid, block, 0, s>>>(a, tiles, ntiles, reverse); break;
+    case kMAdd:
+      if (a.g_bf16) mfma_sweep_kernel<RP, kMAdd, true><<<grid, block, 0, s>>>(a, tiles, ntiles, reverse);
+      else mfma_sweep_kernel<RP, kMAdd><<<grid, block, 0, s>>>(a, tiles, ntiles, reverse);
+      break;
+    case kMAddFused:
+      if (a.g_bf16) mfma_sweep_kernel<RP, kMAddFused, true><<<grid, block, 0, s>>>(a, tiles, ntiles, reverse);
+      else mfma_sweep_kernel<RP, kMAddFused><<<grid, block, 0, s>>>(a, tiles, ntiles, reverse);
+      break;
     case kMResidual: mfma_sweep_kernel<RP, kMResidual><<<grid, block, 0, s>>>(a, tiles, ntiles, reverse); break;
     case kMResidualGhat: mfma_sweep_kernel<RP, kMResidualGhat><<<grid, block, 0, s>>>(a, tiles, ntiles, reverse); break;
     case kMGhatOnly: mfma_sweep_kernel<RP, kMGhatOnly><<<grid, block, 0, s>>>(a, tiles, ntiles, reverse); break;

@@ -57,7 +57,7 @@ int Plan::build(const lqsgd_config* c, const lqsgd_layer* ls, int32_t n_layers) 
     return LQSGD_EINVAL;
   }
   if (!(c->alpha > 0.0f) || !std::isfinite(c->alpha)) { err = "alpha must be finite and > 0"; return LQSGD_EINVAL; }
-  if (c->flags & ~(LQSGD_FLAG_EAGER_RESIDUAL | LQSGD_FLAG_AGGREGATE_FIRST)) { err = "unknown config flags"; return LQSGD_EINVAL; }
+  if (c->flags & ~(LQSGD_FLAG_EAGER_RESIDUAL | LQSGD_FLAG_AGGREGATE_FIRST | LQSGD_FLAG_BF16_GRADIENTS)) { err = "unknown config flags"; return LQSGD_EINVAL; }
   agg_first = (c->flags & LQSGD_FLAG_AGGREGATE_FIRST) != 0;
   cfg = *c;
   W = c->workers;

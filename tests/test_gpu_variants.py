@@ -245,3 +245,58 @@ def test_expired_device_wait_is_reported(monkeypatch):
     with pytest.raises(B.LqsgdError):
         bad.get_factor(B.FACTOR_P_ORTH, 0, 0)
     bad.close()
+
+
+BF16_CASES = [
+    # layers, vectors, rank, bits, W, flags
+    ([(256, 128)], (), 2, 8, 2, 0),
+    ([(64, 576), (128, 64), (64, 27), (33, 65)], (40,), 4, 8, 4, 0),          # aligned and unaligned rows
+    ([(300, 260)], (), 7, 4, 3, B.FLAG_EAGER_RESIDUAL),
+    ([(129, 1028), (70, 27)], (9,), 16, 8, 2, 0),                             # matrix-core sweep 0
+    ([(200, 1100), (96, 520)], (), 32, 8, 2, 0),
+    ([(100, 1100), (129, 131)], (), 50, 8, 2, B.FLAG_AGGREGATE_FIRST),        # rank pad 64 and its plain fallback
+]
+
+
+@pytest.mark.parametrize("layers,vectors,rank,bits,W,flags", BF16_CASES)
+def test_bf16_gradients(layers, vectors, rank, bits, W, flags):
+    """Gradients handed over in bfloat16: the HIP path widens each value exactly,
+    so every stage must agree with the oracle fed the widened values (G' = G + E
+    bit-exact), over three steps with the error feedback carried."""
+    import torch
+    _say("case: bf16 gradients", layers, vectors, rank, bits, W, flags)
+    rng = np.random.default_rng(rank * 7 + W)
+    comp = B.Compressor(B.layer_list(layers, vectors), rank, bits, bits, W, 255.0, flags | B.FLAG_BF16_GRADIENTS)
+    ml = list(range(len(layers)))
+    Q = [rng.standard_normal((c, min(rank, r, c))).astype(f32) for r, c in layers]
+    E = [[np.zeros(s, f32) for s in layers] for _ in range(W)]
+    for l in ml:
+        comp.set_q(l, Q[l])
+    rep = pu.StageReport()
+    shapes = list(layers) + [(v,) for v in vectors]
+    for t in range(3):
+        raw = [[torch.from_numpy((rng.standard_normal(s) * 1e-3).astype(f32)) for s in shapes] for _ in range(W)]
+        Gd = [[x.to(torch.bfloat16).cuda() for x in row] for row in raw]          # what the library is given
+        Gh = [[x.float().cpu().numpy() for x in row] for row in Gd]               # the same values, widened
+        assert any(not np.array_equal(Gh[0][i], raw[0][i].numpy()) for i in range(len(shapes)))
+        if t < 2:
+            E, Q = pu.staged_iteration(comp, Gh, Gd, E, Q, ml, rep, aggregate_first=bool(flags & B.FLAG_AGGREGATE_FIRST))
+        else:
+            # fused step with G-hat and the 1-D means; compared with the oracle on the device's own state
+            ghat = [torch.zeros(s, device="cuda") for s in shapes]
+            comp.step(Gd, ghat)
+            step = orc.layer_step_aggregate_first if flags & B.FLAG_AGGREGATE_FIRST else orc.layer_step
+            for l in ml:
+                want = step([Gh[w][l] for w in range(W)], [E[w][l] for w in range(W)], Q[l], rank, bits, bits, 255.0)
+                got = ghat[l].cpu().numpy()
+                assert pu.rel_fro(got, want["G_hat"]) <= 5e-2 if bits else pu.rel_fro(got, want["G_hat"]) <= pu.FP_TOL
+                m0, _ = comp.get_state(l, 0, want_q=False)
+                pb, qb = comp.get_factor(B.FACTOR_P_BAR, l), comp.get_factor(B.FACTOR_Q_BAR, l)
+                mine = (Gh[0][l].astype(f64) + E[0][l].astype(f64)).astype(f32).astype(f64) - pb.astype(f64) @ qb.astype(f64).T
+                assert pu.rel_fro(m0, mine) <= pu.FP_TOL
+            for vi, v in enumerate(vectors):
+                i = len(layers) + vi
+                want = orc.vector_mean([Gh[w][i] for w in range(W)])
+                assert np.allclose(ghat[i].cpu().numpy(), want, rtol=1e-6, atol=1e-9)
+    comp.close()
+    _say("  ", rep)

@@ -34,7 +34,7 @@ def test_kernel_names():
     (dict(alpha=0.0), B.EINVAL), (dict(alpha=float("nan")), B.EINVAL),
     (dict(layers=[(0, 4, 0)]), B.ESHAPE), (dict(layers=[(4, -1, 0)]), B.ESHAPE),
     (dict(layers=[(65536, 65536, 0)]), B.ESHAPE), (dict(layers=[(8, 2, B.LAYER_VECTOR)]), B.ESHAPE),
-    (dict(layers=[(8, 2, 4)]), B.EINVAL), (dict(flags=4), B.EINVAL),
+    (dict(layers=[(8, 2, 4)]), B.EINVAL), (dict(flags=8), B.EINVAL),
 ])
 def test_plan_rejects_bad_arguments(kw, code):
     args = dict(layers=[(16, 8, 0)], rank=2, bits_p=8, bits_q=8, workers=2, alpha=255.0)
