@@ -24,8 +24,7 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
 
 def sweep_bytes(kernel, w, ghat, eager, bf16=False):
     """Algorithmic HBM bytes of one launch of a streaming kernel: bytes per
-    gradient element of one worker x elements, as the design document derives
-    them (sweep 0: read G, read M/E, write M = 12 B; sweep 1: read M = 4 B;
+    gradient element of one worker x elements (sweep 0: read G, read M/E, write M = 12 B; sweep 1: read M = 4 B;
     residual sweep: read M, write E = 8 B, plus G-hat once per layer = 4 B / W;
     with the residual deferred only the G-hat pass remains).  `ghat`: 0 = not
     written, 1 = stored, 2 = applied to the parameters (read w, write w)."""

@@ -14,8 +14,7 @@ Notation (the paper swaps the letters n and m between its Section 3.2 and
 Section 4 / Algorithm 1, so neither is used here): a layer gradient is
 ``rows x cols``; P is ``rows x r``; Q is ``cols x r``; W workers.
 
-Readings of the paper where it is silent or ambiguous (each one is listed
-again in the design document):
+Readings of the paper where it is silent or ambiguous:
 
 * R1  per-worker: G_w, E_w, M_w = G_w + E_w, P_w, Q_w.  Shared by all
       workers: the warm-start Q, the aggregated P-bar, Q-bar and G-hat.
