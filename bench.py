@@ -64,6 +64,9 @@ def main():
                     help="hand the gradients over in bfloat16 (the first sweep then reads 10 instead of 12 bytes per element)")
     ap.add_argument("--update", type=float, default=None, metavar="ETA",
                     help="apply w <- w - ETA G-hat to synthetic parameters inside the step instead of storing G-hat")
+    ap.add_argument("--rank-sweep", action="store_true",
+                    help="after the main measurement, time every point of the rank / bit-width sweep on the "
+                         "8192 x 8192 matrix (r in 1..32, b in 2, 4, 8, W = 16) and add the table to the JSON line")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (W simulated workers share it; "
@@ -200,9 +203,66 @@ def main():
         "step_hbm_frac": round(step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
         "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels,
         "wire_bytes_per_worker_step": comp.wire_bytes(),
+        "matrix_cores": _matrix_cores(B, w, W),
+        "paper_context": PAPER_CONTEXT,
     }
     comp.close()
+    if args.rank_sweep:
+        del grads, ghat
+        torch.cuda.empty_cache()
+        out["rank_sweep"] = _rank_sweep(B, wl, torch)
     print(json.dumps(out))
+
+
+# Table 1 of the paper (the only timing it prints): whole-epoch figures on other hardware.
+PAPER_CONTEXT = ("paper, Table 1: ResNet-18 / CIFAR-10, compression rank 1, 5 x RTX 4090 workers + 1 central node, "
+                 "precision unstated: computing time per EPOCH (communication excluded) 2.5714 s LQ-SGD, 2.3359 s PowerSGD, "
+                 "2.2937 s SGD; 3 / 14 / 3325 MB sent per epoch.  Context only: no per-step or per-kernel figure is published.")
+
+
+def _matrix_cores(B, w, W):
+    """Which sweeps of this configuration run on the matrix cores (decided by the rank pad)."""
+    info = B.plan_query(B.layer_list(w.layers, w.vectors), w.rank, w.bits, w.bits, W, w.alpha)
+    return {"rank_pad": int(info.rank_pad), "sweeps_0_and_2": bool(info.rank_pad >= 16), "sweep_1": bool(info.rank_pad >= 32)}
+
+
+def _rank_sweep(B, wl, torch):
+    """Every point of the rank / bit-width sweep on one 8192 x 8192 matrix, W = 16: step time, gradient
+    GB/s, the fraction of the HBM peak the first sweep reaches (12 B per element), matrix-core use."""
+    rows = []
+    base = wl.sweep_8192()
+    W = base.workers
+    grads = [[wl.device_gradient(base, 0, 0, k)] for k in range(W)]
+    ghat = [torch.empty(base.layers[0], device="cuda")]
+    elems = W * base.elements_per_worker
+    for r in (1, 2, 4, 8, 16, 32):
+        for b in (2, 4, 8):
+            w = wl.scaled(base, rank=r, bits=b)
+            comp = B.Compressor(B.layer_list(w.layers, w.vectors), r, b, b, W, w.alpha)
+            comp.set_q(0, wl.initial_q(w, 0))
+            for _ in range(2):
+                comp.step(grads, ghat)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(5):
+                comp.step(grads, ghat)
+            torch.cuda.synchronize()
+            ms = (time.perf_counter() - t0) * 1e3 / 5
+            comp.timing_enable(True)
+            for _ in range(5):
+                comp.step(grads, ghat)
+            tms, cnt = comp.timing_read()
+            comp.timing_enable(False)
+            a_us = 1e3 * tms[B.KERNEL_ADD_PROJECT] / max(1, cnt[B.KERNEL_ADD_PROJECT])
+            mc = _matrix_cores(B, w, W)
+            rows.append({"rank": r, "bits": b, "ms_per_step": round(ms, 4),
+                         "gradient_GBps": round(4.0 * elems / (ms * 1e-3) / 1e9, 1),
+                         "sweep0_us": round(a_us, 1), "sweep0_hbm_frac": round(12.0 * elems / (a_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
+                         "step_hbm_frac": round((16.0 * elems + 4.0 * base.elements_per_worker) / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                         "matrix_cores_sweeps_0_2": mc["sweeps_0_and_2"], "matrix_cores_sweep_1": mc["sweep_1"]})
+            comp.close()
+            print("rank_sweep r=%d b=%d: %.3f ms" % (r, b, ms), file=sys.stderr, flush=True)
+    return rows
 
 
 def _measured_traffic(kernel, workload):
