@@ -447,3 +447,53 @@ def test_packet_injection_round_trip():
     got = comp.get_factor(B.FACTOR_P_BAR, 0)
     assert pu.rel_fro(got, orc.mean_of_packets(pk, bits, 255.0)) <= pu.MEAN_TOL
     comp.close()
+
+
+def test_two_contexts_on_their_own_streams():
+    """Contexts are independent: two of them, each on a stream of its own, stepping
+    in turn without host synchronisation in between, give bit for bit what a context
+    on the default stream gives when run alone."""
+    import torch
+    _say("case: two contexts on two streams")
+    layers, vectors, W, rank = [(128, 1152), (64, 27), (2304, 96)], (33,), 4, 4
+    rng = np.random.default_rng(17)
+    ll = B.layer_list(layers, vectors)
+    shapes = list(layers) + [(v,) for v in vectors]
+    q0 = [rng.standard_normal((c, min(rank, r, c))).astype(f32) for r, c in layers]
+    steps = [[[torch.from_numpy((rng.standard_normal(s) * 1e-3).astype(f32)).cuda() for s in shapes] for _ in range(W)]
+             for _ in range(3)]
+    torch.cuda.synchronize()
+
+    def make(stream):
+        c = B.Compressor(ll, rank, 8, 8, W, 255.0, 0, stream=stream)
+        for l in range(len(layers)):
+            c.set_q(l, q0[l])
+        return c
+
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    a, b = make(s1.cuda_stream), make(s2.cuda_stream)
+    ga = [torch.zeros(s, device="cuda") for s in shapes]
+    gb = [torch.zeros(s, device="cuda") for s in shapes]
+    for t in range(3):
+        a.step(steps[t], ga)
+        b.step(steps[2 - t], gb)          # a different order of inputs on the second context
+    a.synchronize(); b.synchronize()
+    ref = make(None)
+    gr = [torch.zeros(s, device="cuda") for s in shapes]
+    for t in range(3):
+        ref.step(steps[t], gr)
+    ref.synchronize()
+    for l in range(len(layers)):
+        assert torch.equal(ga[l], gr[l])
+        for w in range(W):
+            ea, qa = a.get_state(l, w)
+            er, qr = ref.get_state(l, w)
+            assert np.array_equal(ea, er) and np.array_equal(qa, qr)
+    ref2 = make(None)
+    for t in range(3):
+        ref2.step(steps[2 - t], gr)
+    ref2.synchronize()
+    for l in range(len(layers)):
+        assert torch.equal(gb[l], gr[l])
+    for c in (a, b, ref, ref2):
+        c.close()
