@@ -64,6 +64,8 @@ def main():
                     help="hand the gradients over in bfloat16 (the first sweep then reads 10 instead of 12 bytes per element)")
     ap.add_argument("--update", type=float, default=None, metavar="ETA",
                     help="apply w <- w - ETA G-hat to synthetic parameters inside the step instead of storing G-hat")
+    ap.add_argument("--graph", action="store_true",
+                    help="record one step into a HIP graph and time replays of it (for the small, launch-bound sets)")
     ap.add_argument("--rank-sweep", action="store_true",
                     help="after the main measurement, time every point of the rank / bit-width sweep on the "
                          "8192 x 8192 matrix (r in 1..32, b in 2, 4, 8, W = 16) and add the table to the JSON line")
@@ -117,10 +119,13 @@ def main():
     ghat = None
     if not args.no_ghat:
         ghat = [torch.empty(s, device="cuda") for s in w.layers] + [torch.empty(n, device="cuda") for n in w.vectors]
+    side = torch.cuda.Stream() if args.graph else None      # a graph cannot be recorded on the default stream
+    torch.cuda.synchronize()
     comp = B.Compressor(B.layer_list(w.layers, w.vectors), w.rank, w.bits, w.bits, W, w.alpha,
                         (B.FLAG_EAGER_RESIDUAL if args.eager else 0) |
                         (B.FLAG_AGGREGATE_FIRST if args.aggregate_first else 0) |
-                        (B.FLAG_BF16_GRADIENTS if args.bf16_grads else 0))
+                        (B.FLAG_BF16_GRADIENTS if args.bf16_grads else 0),
+                        stream=side.cuda_stream if side is not None else None)
     q0 = [wl.initial_q(w, l) for l in range(L)]
     for l in range(L):
         comp.set_q(l, q0[l])
@@ -140,10 +145,22 @@ def main():
         for _ in range(n):
             comp.step_raw(tab, gt)
 
-    run(args.warmup)
+    run(max(args.warmup, 2 if args.graph else 0))
     torch.cuda.synchronize()
+    timed = run
+    if args.graph:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            run(1)
+        torch.cuda.synchronize()
+
+        def timed(n):
+            for _ in range(n):
+                graph.replay()
+        timed(2)
+        torch.cuda.synchronize()
     t0 = time.perf_counter()
-    run(args.steps)
+    timed(args.steps)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
@@ -197,6 +214,7 @@ def main():
                       else "written" if ghat is not None else "not written",
                       "at the end of each step" if args.eager else "fused into the next step's first sweep"),
                    "gradient_dtype": "bf16" if args.bf16_grads else "f32",
+                   "launch": "replays of a HIP graph holding one step" if args.graph else "eager launches",
                    "order": "aggregate, then orthonormalise" if args.aggregate_first else "orthonormalise, then aggregate (Algorithm 1)",
                    "rank": w.rank, "bits": w.bits, "workers": W, "gradient_bytes_per_step": grad_bytes},
         "step_algorithmic_bytes": step_bytes,

@@ -182,6 +182,13 @@ int lqsgd_decompress(lqsgd_ctx* ctx, int32_t phase);
  *          quantity Algorithm 1 applies in "w <- w - eta G-hat") or, for a
  *          VECTOR layer, the mean over workers.  Must not alias any gradient. */
 int lqsgd_step(lqsgd_ctx* ctx, const float* const* grads, float* const* ghat);
+/* Stream capture: once the same grads / ghat pointer lists have been used in an
+ * ordinary call (so that their device copies exist) and at least one iteration
+ * has run (so that the deferred residual is in its steady state), lqsgd_step
+ * and lqsgd_step_update enqueue kernels only -- no copies, no memsets, no
+ * synchronisation -- and may be recorded into a HIP graph on the context's
+ * stream.  Every replay is then one iteration on whatever the recorded buffers
+ * hold at that time.  Per-kernel timing must be off while recording. */
 
 /* The same iteration followed by Algorithm 1's last statement, fused into the
  * pass that would write G-hat: w <- w - eta G-hat (Eq. (2)) for every matrix

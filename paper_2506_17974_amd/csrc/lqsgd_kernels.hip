@@ -1901,6 +1901,14 @@ bool launch_orth_coop(int rp, int nslice, int max_rank, const DevArgs& a, int nb
                       hipStream_t s) {
   static const bool enabled = [] { const char* e = std::getenv("LQSGD_ORTH_COOP"); return !(e && e[0] == '0'); }();
   if (!enabled || !epoch || !a.orth_table || !a.status || nslice > kCoopMaxSlices) return false;
+  // Under stream capture the launch would be replayed with this launch's epoch baked in, and the
+  // tags of one replay would be indistinguishable from the next one's: take the per-column path.
+  hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(s, &cap) != hipSuccess) {
+    (void)hipGetLastError();
+    return false;
+  }
+  if (cap != hipStreamCaptureStatusNone) return false;
   switch (rp) {
     case 1: return try_orth_coop<1>(nslice, max_rank, a, nblocks, epoch, s);
     case 2: return try_orth_coop<2>(nslice, max_rank, a, nblocks, epoch, s);

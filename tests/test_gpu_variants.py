@@ -300,3 +300,74 @@ def test_bf16_gradients(layers, vectors, rank, bits, W, flags):
                 assert np.allclose(ghat[i].cpu().numpy(), want, rtol=1e-6, atol=1e-9)
     comp.close()
     _say("  ", rep)
+
+
+@pytest.mark.parametrize("layers,rank,W", [
+    ([(32, 25), (64, 800), (1024, 3136), (10, 1024)], 4, 4),        # the small-CNN set: launch-bound
+    ([(2304, 96), (129, 1028)], 16, 2),                             # tall factor: Gram-Schmidt must not take its one-launch form
+])
+def test_step_recorded_into_a_graph(layers, rank, W):
+    """lqsgd_step recorded into a HIP graph on the context's stream: every replay,
+    with fresh gradient values in the recorded buffers and eager work and
+    synchronisation in between, gives bit for bit what an eager context gives."""
+    import torch
+    _say("case: step in a HIP graph", layers, rank, W)
+    vectors = (32, 10)
+    rng = np.random.default_rng(23)
+    ll = B.layer_list(layers, vectors)
+    shapes = list(layers) + [(v,) for v in vectors]
+    q0 = [rng.standard_normal((c, min(rank, r, c))).astype(f32) for r, c in layers]
+
+    def fresh():
+        return [[torch.from_numpy((rng.standard_normal(s) * 1e-3).astype(f32)).cuda() for s in shapes] for _ in range(W)]
+
+    s = torch.cuda.Stream()
+    rec = B.Compressor(ll, rank, 8, 8, W, 255.0, 0, stream=s.cuda_stream)
+    ref = B.Compressor(ll, rank, 8, 8, W, 255.0, 0)
+    for l in range(len(layers)):
+        rec.set_q(l, q0[l]); ref.set_q(l, q0[l])
+    buf = fresh()                                   # the buffers the graph will read
+    out_rec = [torch.zeros(sh, device="cuda") for sh in shapes]
+    out_ref = [torch.zeros(sh, device="cuda") for sh in shapes]
+    torch.cuda.synchronize()
+    # two ordinary iterations: pointer lists bound, deferred residual in its steady state
+    for _ in range(2):
+        vals = fresh()
+        torch.cuda.synchronize()
+        for w in range(W):
+            for i in range(len(shapes)):
+                buf[w][i].copy_(vals[w][i])
+        torch.cuda.synchronize()
+        rec.step(buf, out_rec); ref.step(buf, out_ref)
+        rec.synchronize(); ref.synchronize()
+    tab = rec.pointer_table(buf)
+    import ctypes as C
+    gt = (C.c_void_p * len(shapes))()
+    for i, t in enumerate(out_rec):
+        gt[i] = t.data_ptr()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=s):
+        rec.step_raw(tab, gt)
+    torch.cuda.synchronize()
+    # the recording itself ran nothing: bring the reference to the same point by replaying once first
+    for rep_i in range(4):
+        vals = fresh()
+        torch.cuda.synchronize()
+        for w in range(W):
+            for i in range(len(shapes)):
+                buf[w][i].copy_(vals[w][i])
+        scratch = torch.randn(1 << 16, device="cuda").sum()          # unrelated eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        ref.step(buf, out_ref)
+        torch.cuda.synchronize()
+        for i in range(len(shapes)):
+            assert torch.equal(out_rec[i], out_ref[i]), "replay %d tensor %d" % (rep_i, i)
+        del scratch
+    # the context's host-side bookkeeping did not see the replays; its device state did: compare it
+    for l in range(len(layers)):
+        for w in range(W):
+            ea, qa = rec.get_state(l, w)
+            eb, qb = ref.get_state(l, w)
+            assert np.array_equal(qa, qb) and np.array_equal(ea, eb)
+    rec.close(); ref.close()
