@@ -116,3 +116,31 @@ def test_compressor_refuses_to_run_without_gpu():
         pytest.skip("a GPU is visible")
     with pytest.raises(RuntimeError):
         B.Compressor([(4, 4, 0)], 1)
+
+
+@pytest.mark.parametrize("flags", [0, B.FLAG_EAGER_RESIDUAL, B.FLAG_AGGREGATE_FIRST, B.FLAG_BF16_GRADIENTS,
+                                   B.FLAG_EAGER_RESIDUAL | B.FLAG_AGGREGATE_FIRST | B.FLAG_BF16_GRADIENTS])
+def test_plan_accepts_every_flag_combination(flags):
+    w = wl.small_cnn()
+    info = B.plan_query(B.layer_list(w.layers, w.vectors), 4, 8, 8, 4, flags=flags)
+    assert info.n_matrix == 4 and info.n_vector == 4 and info.rank_pad == 4
+
+
+@pytest.mark.parametrize("rank,pad", [(1, 1), (3, 4), (7, 8), (12, 16), (30, 32), (33, 64), (50, 64), (64, 64)])
+def test_rank_pad(rank, pad):
+    info = B.plan_query([(128, 256, 0)], rank, 8, 8, 2)
+    assert info.rank_pad == pad
+    # the pad follows the largest EFFECTIVE rank: a 10-row layer clips rank 50 to 10
+    assert B.plan_query([(10, 256, 0)], 50, 8, 8, 2).rank_pad == 16
+
+
+@pytest.mark.parametrize("rank", [40, 64])
+@pytest.mark.parametrize("sweep", [0, 1, 2, 3])
+def test_work_lists_cover_each_element_once_at_rank_pad_64(sweep, rank):
+    layers = [(96, 520, 0), (129, 131, 0), (2100, 132, 0), (64, 27, 0), (7, 1, B.LAYER_VECTOR)]
+    W = 2
+    cover = _coverage(layers, rank, W, sweep)
+    want = [(i, w) for i, l in enumerate(layers) if l[2] == 0 for w in range(1 if sweep == 3 else W)]
+    assert sorted(cover) == want
+    for key, m in cover.items():
+        assert m.min() == 1 and m.max() == 1, key
