@@ -133,7 +133,12 @@ int lqsgd_create(const lqsgd_config* cfg, const lqsgd_layer* layers, int32_t n_l
 /* Frees everything; NULL is accepted.  Synchronises the stream first. */
 int lqsgd_destroy(lqsgd_ctx* ctx);
 
-/* Waits until all work enqueued by this context has finished. */
+/* Waits until all work enqueued by this context has finished.
+ * One kernel (Gram-Schmidt of tall factors, launched cooperatively) has
+ * workgroups wait for each other on the device; those waits are bounded, and if
+ * one ever expires the kernel still runs to its end but the context's results
+ * are invalid from then on: this call, and every other call that synchronises,
+ * then returns LQSGD_EHIP with a text saying so. */
 int lqsgd_synchronize(lqsgd_ctx* ctx);
 
 /* Text for the most recent error on ctx (or for a failed lqsgd_create when
