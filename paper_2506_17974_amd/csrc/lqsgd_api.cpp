@@ -185,7 +185,7 @@ int next_dir(lqsgd_ctx* c) {
 int run_sweep0(lqsgd_ctx* c) {
   { Timed t(c, LQSGD_KERNEL_ADD_PROJECT);
     if (c->plan.mfma_a)
-      HIP_TRY(c, launch_mfma_sweep(c->plan.RP, c->pending ? 1 : 0, c->args, c->d_tilesA, (int)c->plan.tilesA.size(),
+      HIP_TRY(c, launch_mfma_sweep(c->plan.RP, c->pending ? 1 : 0, (c->plan.max_rank == c->plan.RP) ? 1 : 0, c->args, c->d_tilesA, (int)c->plan.tilesA.size(),
                                    next_dir(c), c->stream));
     else
       HIP_TRY(c, launch_add_project(c->plan.RP, c->args, c->d_tilesA, (int)c->plan.tilesA.size(), c->pending ? 1 : 0,
@@ -243,13 +243,13 @@ int run_sweep2(lqsgd_ctx* c, bool write_ghat) {
   const Plan& p = c->plan;
   if (c->eager) {
     if (p.mfma_a)
-      HIP_TRY(c, launch_mfma_sweep(p.RP, write_ghat ? 3 : 2, c->args, c->d_tilesA, (int)p.tilesA.size(), next_dir(c), c->stream));
+      HIP_TRY(c, launch_mfma_sweep(p.RP, write_ghat ? 3 : 2, (c->plan.max_rank == c->plan.RP) ? 1 : 0, c->args, c->d_tilesA, (int)p.tilesA.size(), next_dir(c), c->stream));
     else
       HIP_TRY(c, launch_residual(p.RP, write_ghat ? 1 : 0, c->args, c->d_tilesB, (int)p.tilesB.size(), next_dir(c), c->stream));
   } else {
     if (write_ghat) {
       if (p.mfma_a)
-        HIP_TRY(c, launch_mfma_sweep(p.RP, 4, c->args, c->d_tilesAG, (int)p.tilesAG.size(), 0, c->stream));
+        HIP_TRY(c, launch_mfma_sweep(p.RP, 4, (c->plan.max_rank == c->plan.RP) ? 1 : 0, c->args, c->d_tilesAG, (int)p.tilesAG.size(), 0, c->stream));
       else
         HIP_TRY(c, launch_residual(p.RP, 2, c->args, c->d_tilesG, (int)p.tilesG.size(), 0, c->stream));
     }
@@ -263,7 +263,7 @@ int materialise(lqsgd_ctx* c) {
   Timed t(c, LQSGD_KERNEL_RESIDUAL);
   const Plan& p = c->plan;
   if (p.mfma_a)
-    HIP_TRY(c, launch_mfma_sweep(p.RP, 2, c->args, c->d_tilesA, (int)p.tilesA.size(), next_dir(c), c->stream));
+    HIP_TRY(c, launch_mfma_sweep(p.RP, 2, (c->plan.max_rank == c->plan.RP) ? 1 : 0, c->args, c->d_tilesA, (int)p.tilesA.size(), next_dir(c), c->stream));
   else
     HIP_TRY(c, launch_residual(p.RP, 0, c->args, c->d_tilesB, (int)p.tilesB.size(), next_dir(c), c->stream));
   c->pending = false;

@@ -70,6 +70,8 @@ hipError_t launch_residual(int RP, int mode, const DevArgs& a, const Tile* tiles
 // Sweeps 0 and 2 on the matrix cores (rank pad 16, 32 or 64), over the work list of
 // sweep 0 (32-row items).  mode: 0 = M = G + E and P partials, 1 = the same with the deferred
 // residual applied on the fly, 2 = residual, 3 = residual + G-hat, 4 = G-hat only (worker 0's items).
-hipError_t launch_mfma_sweep(int RP, int mode, const DevArgs& a, const Tile* tiles, int ntiles, int reverse, hipStream_t s);
+// full_rank: the largest effective rank of the layers equals RP (chooses between two forms of the fused add mode).
+hipError_t launch_mfma_sweep(int RP, int mode, int full_rank, const DevArgs& a, const Tile* tiles, int ntiles, int reverse,
+                             hipStream_t s);
 
 }  // namespace lqsgd

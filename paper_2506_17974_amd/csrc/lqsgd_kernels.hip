@@ -1698,8 +1698,176 @@ __device__ __forceinline__ void mfma_tile(const float* __restrict__ G, float* __
   }
 }
 
-// Rank pad 64, rows that are not 16-byte aligned (tiny layers): a plain loop, one wavefront over
-// the rows of its share, lanes over columns; the r dot products of a row go through wave sums.
+// ---------------------------------------------------------------------------
+// The add modes at rank pad 32 in a narrower form: a wavefront takes 32 rows x 32
+// columns per step instead of 32 x 64, which halves the registers of the
+// streamed tile, of the G-hat operands and of the Q slice, so that two
+// wavefronts fit on a SIMD (with 32 x 64 the fused mode needs more than half
+// the register file and runs one wavefront per SIMD, every load exposed).
+// Eight wavefronts per workgroup keep the 1 KiB-per-row access of the
+// workgroup.  Row layout here: 8 lanes = 128 contiguous bytes of a row, 8 rows
+// per instruction.  G-hat elements come out of the same sequence of matrix
+// instructions as in the 32 x 64 form (the contraction over the ranks does not
+// depend on the column blocking), so the residual modes, which keep that form,
+// still match bit for bit.
+// ---------------------------------------------------------------------------
+constexpr int kLP32 = 36;   // LDS pitch (floats) of a 32 x 32 tile: 16-byte aligned rows
+
+template <int RP, int MODE, bool EXACT, bool GB16>
+__device__ __forceinline__ void mfma_tile32(const float* __restrict__ G, float* __restrict__ M,
+                                            const float* Q, const float* Pb, float* __restrict__ Pp,
+                                            int cols, int r, int row0, int nrows, int col0, int col1,
+                                            int lane, int wave, float (*lds_all)[32 * kLP32]) {
+  static_assert(RP == 32 && (MODE == kMAdd || MODE == kMAddFused), "narrow form: add modes at rank pad 32");
+  float* lds = lds_all[wave];
+  constexpr bool NEEDG = (MODE != kMAdd);
+  constexpr int KH = RP / 2;
+  const int li = lane & 31, h = lane >> 5;
+  const int sr = lane >> 3, c4 = (lane & 7) * 4;   // row layout: rows 8 i + sr, columns c4 .. c4 + 3
+  float pa[KH];
+  if constexpr (NEEDG) {
+    const int row = row0 + li;
+    if constexpr (EXACT) {
+      if (li < nrows) {
+        const float4* src = reinterpret_cast<const float4*>(Pb + (size_t)row * RP + KH * h);
+#pragma unroll
+        for (int t = 0; t < KH / 4; ++t) {
+          const float4 x = src[t];
+          pa[4 * t] = x.x; pa[4 * t + 1] = x.y; pa[4 * t + 2] = x.z; pa[4 * t + 3] = x.w;
+        }
+      } else {
+#pragma unroll
+        for (int k = 0; k < KH; ++k) pa[k] = 0.0f;
+      }
+    } else {
+#pragma unroll
+      for (int k = 0; k < KH; ++k) pa[k] = (li < nrows && KH * h + k < r) ? Pb[(size_t)row * r + KH * h + k] : 0.0f;
+    }
+  }
+  v16f accP, accP2;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) { accP[i] = 0.0f; accP2[i] = 0.0f; }
+
+  auto block = [&](auto full_tag, const int c) {
+    constexpr bool FULL = decltype(full_tag)::value;
+    const int cl = c + c4;
+    const bool colok = FULL || cl < col1;
+    Pk<4> g[4], e[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int rr = 8 * i + sr;
+      const bool ok = FULL || (colok && rr < nrows);
+      const size_t off = (size_t)(row0 + rr) * cols;
+#pragma unroll
+      for (int v = 0; v < 4; ++v) { g[i].v[v] = 0.0f; e[i].v[v] = 0.0f; }
+      if (ok) {
+        g[i] = ldgrad<4, LQSGD_NT_G != 0, GB16>(grad_row<GB16>(G, off), (unsigned)cl * 4u);
+        e[i] = ldrow<4, LQSGD_NT_E != 0>(reinterpret_cast<const char*>(M + off), (unsigned)cl * 4u);
+      }
+    }
+    if constexpr (NEEDG) {
+      float qb[KH];
+      const int col = c + li;
+      if constexpr (EXACT) {
+        if (FULL || col < col1) {
+          const float4* src = reinterpret_cast<const float4*>(Q + (size_t)col * RP + KH * h);
+#pragma unroll
+          for (int t = 0; t < KH / 4; ++t) {
+            const float4 x = src[t];
+            qb[4 * t] = x.x; qb[4 * t + 1] = x.y; qb[4 * t + 2] = x.z; qb[4 * t + 3] = x.w;
+          }
+        } else {
+#pragma unroll
+          for (int k = 0; k < KH; ++k) qb[k] = 0.0f;
+        }
+      } else {
+#pragma unroll
+        for (int k = 0; k < KH; ++k)
+          qb[k] = ((FULL || col < col1) && KH * h + k < r) ? Q[(size_t)col * r + KH * h + k] : 0.0f;
+      }
+      v16f gh;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) gh[i] = 0.0f;
+#pragma unroll
+      for (int k = 0; k < KH; ++k) gh = __builtin_amdgcn_mfma_f32_32x32x2f32(pa[k], qb[k], gh, 0, 0, 0);
+#pragma unroll
+      for (int v = 0; v < 16; ++v) lds[(8 * (v >> 2) + 4 * h + (v & 3)) * kLP32 + li] = gh[v];
+      wave_lds_fence();
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float4 t = *reinterpret_cast<const float4*>(lds + (8 * i + sr) * kLP32 + c4);
+        e[i].v[0] -= t.x; e[i].v[1] -= t.y; e[i].v[2] -= t.z; e[i].v[3] -= t.w;
+      }
+      wave_lds_fence();
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int rr = 8 * i + sr;
+      Pk<4> m;
+#pragma unroll
+      for (int v = 0; v < 4; ++v) m.v[v] = g[i].v[v] + e[i].v[v];
+      if (FULL || (colok && rr < nrows))
+        strow<4, LQSGD_NT_ST_A != 0>(reinterpret_cast<char*>(M + (size_t)(row0 + rr) * cols), (unsigned)cl * 4u, m);
+      *reinterpret_cast<float4*>(lds + rr * kLP32 + c4) = make_float4(m.v[0], m.v[1], m.v[2], m.v[3]);
+    }
+    // the Q slice of the P product is fetched only now: the registers of the G-hat operands are free again
+    float bq[16];
+#pragma unroll
+    for (int kk = 0; kk < 16; ++kk) {
+      const int col = c + 16 * h + kk;
+      if constexpr (FULL && EXACT)
+        bq[kk] = Q[(size_t)col * RP + li];
+      else
+        bq[kk] = (col < col1 && li < r) ? Q[(size_t)col * r + li] : 0.0f;
+    }
+    wave_lds_fence();
+    {
+      const float4 a0 = *reinterpret_cast<const float4*>(lds + li * kLP32 + 16 * h);
+      const float4 a1 = *reinterpret_cast<const float4*>(lds + li * kLP32 + 16 * h + 4);
+      const float4 a2 = *reinterpret_cast<const float4*>(lds + li * kLP32 + 16 * h + 8);
+      const float4 a3 = *reinterpret_cast<const float4*>(lds + li * kLP32 + 16 * h + 12);
+      accP = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.x, bq[0], accP, 0, 0, 0);
+      accP2 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.x, bq[4], accP2, 0, 0, 0);
+      accP = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.y, bq[1], accP, 0, 0, 0);
+      accP2 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.y, bq[5], accP2, 0, 0, 0);
+      accP = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.z, bq[2], accP, 0, 0, 0);
+      accP2 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.z, bq[6], accP2, 0, 0, 0);
+      accP = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.w, bq[3], accP, 0, 0, 0);
+      accP2 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.w, bq[7], accP2, 0, 0, 0);
+      accP = __builtin_amdgcn_mfma_f32_32x32x2f32(a2.x, bq[8], accP, 0, 0, 0);
+      accP2 = __builtin_amdgcn_mfma_f32_32x32x2f32(a3.x, bq[12], accP2, 0, 0, 0);
+      accP = __builtin_amdgcn_mfma_f32_32x32x2f32(a2.y, bq[9], accP, 0, 0, 0);
+      accP2 = __builtin_amdgcn_mfma_f32_32x32x2f32(a3.y, bq[13], accP2, 0, 0, 0);
+      accP = __builtin_amdgcn_mfma_f32_32x32x2f32(a2.z, bq[10], accP, 0, 0, 0);
+      accP2 = __builtin_amdgcn_mfma_f32_32x32x2f32(a3.z, bq[14], accP2, 0, 0, 0);
+      accP = __builtin_amdgcn_mfma_f32_32x32x2f32(a2.w, bq[11], accP, 0, 0, 0);
+      accP2 = __builtin_amdgcn_mfma_f32_32x32x2f32(a3.w, bq[15], accP2, 0, 0, 0);
+    }
+    wave_lds_fence();
+  };
+  for (int c = col0 + 32 * wave; c < col1; c += 256) {
+    if (nrows == 32 && c + 32 <= col1)
+      block(std::true_type{}, c);
+    else
+      block(std::false_type{}, c);
+  }
+  // P partial of the item = sum over the eight wavefronts, added in wavefront order
+#pragma unroll
+  for (int v = 0; v < 16; ++v) lds[(8 * (v >> 2) + 4 * h + (v & 3)) * kLP32 + li] = accP[v] + accP2[v];
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int e = (int)threadIdx.x + 512 * i;
+    const int rr = e >> 5, k = e & 31;
+    float t = lds_all[0][rr * kLP32 + k];
+#pragma unroll
+    for (int wv = 1; wv < 8; ++wv) t += lds_all[wv][rr * kLP32 + k];
+    if (rr < nrows && k < r) Pp[(size_t)(row0 + rr) * r + k] = t;
+  }
+}
+
+// Rows that are not 16-byte aligned (tiny layers): a plain loop, one wavefront over the rows of its
+// share, lanes over columns; the r dot products of a row go through wave sums.
 template <int MODE, bool GB16>
 __device__ __forceinline__ void plain_rows_fallback(const DevArgs& a, const LayerDesc& ld, const Tile& tl,
                                                     const float* G, float* M, float* Pp, float* ghat_out,
@@ -1746,30 +1914,14 @@ __device__ __forceinline__ void plain_rows_fallback(const DevArgs& a, const Laye
   }
 }
 
-// rows that are not 16-byte aligned (cols % 4 != 0; tiny layers): vector units
+// Rows that are not 16-byte aligned (cols % 4 != 0; tiny layers) take the plain loop: the register-
+// tiled vector code would set the register count of the whole kernel (rank pad x 4 accumulators and
+// as many factor values per lane) and with it the number of wavefronts per SIMD of the main path.
 template <int RP, int MODE, bool GB16>
 __device__ __forceinline__ void mfma_mode_vector_fallback(const DevArgs& a, const LayerDesc& ld, const Tile& tl, int worker,
                                                           const float* G, float* M, float* Pp, float* ghat_out,
                                                           int col0, int col1, int lane) {
-  if constexpr (RP > 32) {
-    plain_rows_fallback<MODE, GB16>(a, ld, tl, G, M, Pp, ghat_out, col0, col1, lane);
-  } else {
-    if constexpr (MODE == kMAdd) {
-      add_project_tile<RP, 1, 4, false, false, GB16>(G, M, a.Qbar + ld.q_off, a.Pbar + ld.p_off, Pp, ld.cols, ld.r, tl.row0,
-                                               tl.nrows, col0, col1, lane);
-    } else if constexpr (MODE == kMAddFused) {
-      add_project_tile<RP, 1, 4, false, true, GB16>(G, M, a.Qbar + ld.q_off, a.Pbar + ld.p_off, Pp, ld.cols, ld.r, tl.row0,
-                                              tl.nrows, col0, col1, lane);
-    } else {
-      constexpr int RM = MODE == kMResidual ? kResidual : (MODE == kMResidualGhat ? kResidualGhat : kGhatOnly);
-      for (int c = col0 + lane; c < col1; c += kWave) {
-        float q[RP];
-        load_slice<RP, 1, false>(a.Qbar + ld.q_off, c, ld.r, q);
-        residual_rows<RP, 1, false, RM>(M, a.Pbar + ld.p_off, ghat_out, ld.cols, ld.r, tl.row0, tl.row0 + tl.nrows,
-                                        (unsigned)c * 4u, q, a.update, a.eta);
-      }
-    }
-  }
+  plain_rows_fallback<MODE, GB16>(a, ld, tl, G, M, Pp, ghat_out, col0, col1, lane);
 }
 
 // Wavefronts per SIMD the register allocation aims for: two at rank pad 16 (2.65 -> 2.47 ms on
@@ -1806,6 +1958,37 @@ __global__ __launch_bounds__(256, RP <= 16 ? 2 : 1) void mfma_sweep_kernel(DevAr
   else
     mfma_tile<RP, MODE, false, GB16>(G, M, a.Qbar + ld.q_off, a.Pbar + ld.p_off, Pp, ghat_out, ld.cols, ld.r, tl.row0,
                                tl.nrows, col0, col1, lane, wave, lds_all, a.update, a.eta);
+}
+
+template <int RP, int MODE, bool GB16>
+__global__ __launch_bounds__(512, 2) void mfma_sweep32_kernel(DevArgs a, const Tile* __restrict__ tiles, int ntiles, int reverse) {
+  __shared__ __attribute__((aligned(16))) float lds_all[8][32 * kLP32];
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int lane = threadIdx.x & (kWave - 1);
+  if (a.agg_first && blockIdx.x == 0)
+    for (int i = threadIdx.x; i < a.W * a.L; i += 512) a.scaleP[i] = 0.0f;
+  const Tile tl = tiles[reverse ? ntiles - 1 - (int)blockIdx.x : (int)blockIdx.x];   // one item per workgroup
+  const int layer = tl.lw / a.W, worker = tl.lw - layer * a.W;
+  const LayerDesc& ld = a.layers[layer];
+  const float* G = a.grads[(size_t)worker * a.n_all + ld.gidx];
+  float* M = a.E + (size_t)worker * a.m_stride + ld.m_off;
+  float* Pp = a.Ppart + (size_t)worker * a.ppart_stride + ld.ppart_off + (size_t)tl.aux * ld.np_pad;
+  const int col0 = tl.aux * ld.segw;
+  const int col1 = min(ld.cols, col0 + ld.segw);
+  if (ld.vec != 4) {
+    // tiny layers: the vector code, four of the item's rows per wavefront
+    Tile sub = tl;
+    sub.row0 = tl.row0 + 4 * wave;
+    sub.nrows = min(4, tl.nrows - 4 * wave);
+    if (sub.nrows > 0) mfma_mode_vector_fallback<RP, MODE, GB16>(a, ld, sub, worker, G, M, Pp, nullptr, col0, col1, lane);
+    return;
+  }
+  if (ld.r == RP)
+    mfma_tile32<RP, MODE, true, GB16>(G, M, a.Qbar + ld.q_off, a.Pbar + ld.p_off, Pp, ld.cols, ld.r, tl.row0, tl.nrows,
+                                      col0, col1, lane, wave, lds_all);
+  else
+    mfma_tile32<RP, MODE, false, GB16>(G, M, a.Qbar + ld.q_off, a.Pbar + ld.p_off, Pp, ld.cols, ld.r, tl.row0, tl.nrows,
+                                       col0, col1, lane, wave, lds_all);
 }
 
 }  // namespace
@@ -1998,15 +2181,41 @@ hipError_t launch_residual(int rp, int mode, const DevArgs& a, const Tile* tiles
   return hipGetLastError();
 }
 
+// LQSGD_MFMA_NARROW32=0 keeps the 32 x 64 form at rank pad 32 (for comparisons).
+static bool narrow32() {
+  static const bool on = [] { const char* e = std::getenv("LQSGD_MFMA_NARROW32"); return !(e && e[0] == '0'); }();
+  return on;
+}
+
 template <int RP>
-hipError_t launch_mfma_sweep_rp(int mode, const DevArgs& a, const Tile* tiles, int ntiles, int reverse, hipStream_t s) {
+hipError_t launch_mfma_sweep_rp(int mode, int full_rank, const DevArgs& a, const Tile* tiles, int ntiles, int reverse,
+                                hipStream_t s) {
   const dim3 grid(ntiles), block(256);
   switch (mode) {
     case kMAdd:
+      // same form as the fused mode below, so that P comes out of one summation order whether or
+      // not the residual update is deferred
+      if constexpr (RP == 32) {
+        if (narrow32() && full_rank) {
+          if (a.g_bf16) mfma_sweep32_kernel<32, kMAdd, true><<<grid, dim3(512), 0, s>>>(a, tiles, ntiles, reverse);
+          else mfma_sweep32_kernel<32, kMAdd, false><<<grid, dim3(512), 0, s>>>(a, tiles, ntiles, reverse);
+          break;
+        }
+      }
       if (a.g_bf16) mfma_sweep_kernel<RP, kMAdd, true><<<grid, block, 0, s>>>(a, tiles, ntiles, reverse);
       else mfma_sweep_kernel<RP, kMAdd><<<grid, block, 0, s>>>(a, tiles, ntiles, reverse);
       break;
     case kMAddFused:
+      // the narrow form pays where the fused mode would otherwise run one wavefront per SIMD and every
+      // layer fills the rank pad (measured on 8192^2 x 16: r = 32 2.77 -> 2.60 ms; at r = 30 it costs
+      // 3.11 -> 3.22 ms, so ranks below the pad stay with the 32 x 64 form)
+      if constexpr (RP == 32) {
+        if (narrow32() && full_rank) {
+          if (a.g_bf16) mfma_sweep32_kernel<32, kMAddFused, true><<<grid, dim3(512), 0, s>>>(a, tiles, ntiles, reverse);
+          else mfma_sweep32_kernel<32, kMAddFused, false><<<grid, dim3(512), 0, s>>>(a, tiles, ntiles, reverse);
+          break;
+        }
+      }
       if (a.g_bf16) mfma_sweep_kernel<RP, kMAddFused, true><<<grid, block, 0, s>>>(a, tiles, ntiles, reverse);
       else mfma_sweep_kernel<RP, kMAddFused><<<grid, block, 0, s>>>(a, tiles, ntiles, reverse);
       break;
@@ -2018,11 +2227,12 @@ hipError_t launch_mfma_sweep_rp(int mode, const DevArgs& a, const Tile* tiles, i
   return hipGetLastError();
 }
 
-hipError_t launch_mfma_sweep(int rp, int mode, const DevArgs& a, const Tile* tiles, int ntiles, int reverse, hipStream_t s) {
+hipError_t launch_mfma_sweep(int rp, int mode, int full_rank, const DevArgs& a, const Tile* tiles, int ntiles, int reverse,
+                             hipStream_t s) {
   if (ntiles <= 0) return hipSuccess;
-  if (rp == 16) return launch_mfma_sweep_rp<16>(mode, a, tiles, ntiles, reverse, s);
-  if (rp == 32) return launch_mfma_sweep_rp<32>(mode, a, tiles, ntiles, reverse, s);
-  if (rp == 64) return launch_mfma_sweep_rp<64>(mode, a, tiles, ntiles, reverse, s);
+  if (rp == 16) return launch_mfma_sweep_rp<16>(mode, full_rank, a, tiles, ntiles, reverse, s);
+  if (rp == 32) return launch_mfma_sweep_rp<32>(mode, full_rank, a, tiles, ntiles, reverse, s);
+  if (rp == 64) return launch_mfma_sweep_rp<64>(mode, full_rank, a, tiles, ntiles, reverse, s);
   return hipErrorInvalidValue;
 }
 
