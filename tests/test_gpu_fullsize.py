@@ -78,3 +78,42 @@ def test_llm_stack_full_size():
     _say("case: llm_stack 32 layers W=4 full size")
     sample = [0, 4, 5, 6 * 15 + 2, 6 * 15 + 5, 6 * 31 + 3, 6 * 31 + 4]
     _sampled_run(w, sample, [0, 3], steps=2)
+
+
+@pytest.mark.parametrize("rank", [4, 32])
+def test_sweep_8192_fused_step_equals_staged_at_full_size(rank):
+    """The call the benchmark times (lqsgd_step with G-hat, residual deferred) at the full
+    8192 x 8192, W = 16 size: two iterations leave bit for bit the state that the staged
+    calls (checked stage by stage against the oracle above) leave, and G-hat is the product
+    of the aggregated factors."""
+    import torch
+    w = wl.sweep_8192(rank, 8)
+    _say("case: sweep_8192 r=%d W=16, fused step vs staged calls" % rank)
+    W = w.workers
+    layers = B.layer_list(w.layers)
+    fused = B.Compressor(layers, w.rank, w.bits, w.bits, W, w.alpha)
+    staged = B.Compressor(layers, w.rank, w.bits, w.bits, W, w.alpha)
+    q0 = wl.initial_q(w, 0)
+    fused.set_q(0, q0); staged.set_q(0, q0)
+    ghat = [torch.empty(w.layers[0], device="cuda")]
+    for t in range(2):
+        Gd = [[wl.device_gradient(w, t, 0, k)] for k in range(W)]
+        torch.cuda.synchronize()
+        fused.step(Gd, ghat)
+        staged.compress(B.PHASE_P, Gd); staged.decompress(B.PHASE_P)
+        staged.compress(B.PHASE_Q); staged.decompress(B.PHASE_Q)
+        fused.synchronize(); staged.synchronize()
+        del Gd
+    pb, qb = fused.get_factor(B.FACTOR_P_BAR, 0), fused.get_factor(B.FACTOR_Q_BAR, 0)
+    assert np.array_equal(pb, staged.get_factor(B.FACTOR_P_BAR, 0))
+    assert np.array_equal(qb, staged.get_factor(B.FACTOR_Q_BAR, 0))
+    for k in (0, 9, 15):
+        ef, _ = fused.get_state(0, k)
+        es, _ = staged.get_state(0, k)
+        assert np.array_equal(ef, es), "worker %d" % k
+        del ef, es
+    rows = np.array([0, 1, 4095, 8191])
+    got = ghat[0][torch.from_numpy(rows).cuda()].cpu().numpy()
+    want = pb[rows].astype(np.float64) @ qb.astype(np.float64).T
+    assert pu.rel_fro(got, want) <= pu.FP_TOL
+    fused.close(); staged.close()
