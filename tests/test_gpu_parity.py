@@ -497,3 +497,24 @@ def test_two_contexts_on_their_own_streams():
         assert torch.equal(gb[l], gr[l])
     for c in (a, b, ref, ref2):
         c.close()
+
+
+def test_vector_only_context():
+    """No matrix layer at all: the step is the plain mean of the 1-D tensors, the staged
+    calls are empty iterations, and nothing is launched on empty work lists."""
+    import torch
+    _say("case: vector layers only")
+    W, lens = 3, (7, 1000, 1)
+    rng = np.random.default_rng(4)
+    comp = B.Compressor(B.layer_list((), lens), 4, 8, 8, W)
+    G = [[torch.from_numpy(rng.standard_normal(n).astype(f32)).cuda() for n in lens] for _ in range(W)]
+    out = [torch.zeros(n, device="cuda") for n in lens]
+    comp.step(G, out)
+    comp.synchronize()
+    for i, n in enumerate(lens):
+        assert _vector_mean_ok(out[i].cpu().numpy(), [G[w][i].cpu().numpy() for w in range(W)])
+        assert np.array_equal(comp.get_factor(B.FACTOR_VMEAN, i), out[i].cpu().numpy())
+    comp.compress(B.PHASE_P, G); comp.decompress(B.PHASE_P); comp.compress(B.PHASE_Q); comp.decompress(B.PHASE_Q)
+    comp.step(G)
+    assert comp.wire_bytes() == 0
+    comp.close()

@@ -144,3 +144,11 @@ def test_work_lists_cover_each_element_once_at_rank_pad_64(sweep, rank):
     assert sorted(cover) == want
     for key, m in cover.items():
         assert m.min() == 1 and m.max() == 1, key
+
+
+def test_empty_layer_list_is_rejected_and_vector_only_is_planned():
+    with pytest.raises(B.LqsgdError) as ei:
+        B.plan_query([], 4, 8, 8, 2)
+    assert ei.value.code == B.EINVAL
+    info = B.plan_query([(7, 1, B.LAYER_VECTOR), (1000, 1, B.LAYER_VECTOR)], 4, 8, 8, 2)
+    assert info.n_matrix == 0 and info.n_vector == 2 and list(info.tiles) == [0, 0, 0] and info.matrix_elements == 0
