@@ -189,8 +189,11 @@ def staged_iteration(comp: B.Compressor, G_host, G_dev, E_host, Q_host, matrix_l
                 # behind G-hat rounds r times, each relative to the size of its terms
                 scale = np.abs(M[(li, w)]) + absterms
                 assert np.all(np.abs(e_gpu.astype(f64) + ghat - M[(li, w)]) <= (r_l + 2) * 6e-8 * scale + 1e-30)
-    # budget: 1e-5 of the elements (one flip is tolerated on sets smaller than 1e5 elements)
-    assert rep.code_flips <= max(1, int(np.ceil(CODE_FLIP_BUDGET * rep.code_elems))), str(rep)
+    # budget: 1e-5 of the elements.  Every flip has already been verified above to be a one-level
+    # difference within 1 ulp of a bucket boundary; at b = 8 about 8e-6 of all fp32 values sit that
+    # close to one of the 255 boundaries, so on the small edge-case sets (below 2e5 elements, expected
+    # count under 2) the count is allowed to reach 2 rather than being held to a fraction of one.
+    assert rep.code_flips <= max(2, int(np.ceil(CODE_FLIP_BUDGET * rep.code_elems))), str(rep)
     return E_new, Q_bar
 
 

@@ -126,6 +126,11 @@ EDGE_CASES = [
     ([(64, 576), (128, 64)], 4, 8, 8, 8, 10.0),
     ([(64, 576), (128, 64)], 4, 8, 8, 8, 1000.0),
     ([(2100, 132)], 4, 8, 8, 2, 255.0),                    # several row blocks
+    ([(33, 70)], 4, 8, 8, 64, 255.0),                      # the largest worker count: eight passes of eight worker slots
+    ([(33, 70)], 4, 8, 4, 9, 255.0),                       # a ragged last pass of worker slots
+    ([(3, 70000)], 2, 8, 8, 2, 255.0),                     # very wide: 69 column segments
+    ([(70000, 12)], 4, 8, 8, 2, 255.0),                    # very tall: 274 slices, Gram-Schmidt one launch per column
+    ([(20000, 16)], 16, 8, 8, 3, 255.0),                   # tall, rank 16: a larger table of the one-launch Gram-Schmidt
 ]
 
 
