@@ -152,3 +152,32 @@ def test_empty_layer_list_is_rejected_and_vector_only_is_planned():
     assert ei.value.code == B.EINVAL
     info = B.plan_query([(7, 1, B.LAYER_VECTOR), (1000, 1, B.LAYER_VECTOR)], 4, 8, 8, 2)
     assert info.n_matrix == 0 and info.n_vector == 2 and list(info.tiles) == [0, 0, 0] and info.matrix_elements == 0
+
+
+def test_header_is_plain_c(tmp_path):
+    """The boundary is a C ABI: the header compiles as C99 with pedantic warnings as errors,
+    and a C program can link against the library and call a host-only entry point."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    src = tmp_path / "use_lqsgd.c"
+    src.write_text(
+        '#include <stdio.h>\n#include "lqsgd.h"\n'
+        "int main(void) {\n"
+        "  lqsgd_config cfg = {4, 8, 8, 2, 255.0f, LQSGD_FLAG_NONE};\n"
+        "  lqsgd_layer layers[2] = {{64, 576, LQSGD_LAYER_MATRIX}, {10, 1, LQSGD_LAYER_VECTOR}};\n"
+        "  lqsgd_plan_info info;\n"
+        "  int rc = lqsgd_plan_query(&cfg, layers, 2, &info);\n"
+        '  printf("%d %d %d %lld\\n", rc, (int)info.n_matrix, (int)info.n_vector, (long long)info.matrix_elements);\n'
+        "  return rc;\n}\n")
+    subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", os.path.join(root, "include"),
+                    "-fsyntax-only", str(src)], check=True)
+    exe = tmp_path / "use_lqsgd"
+    libdir = os.path.dirname(B.LIB_PATH)
+    subprocess.run([gcc, "-std=c99", "-I", os.path.join(root, "include"), str(src), "-o", str(exe),
+                    "-L", libdir, "-l:" + os.path.basename(B.LIB_PATH), "-Wl,-rpath," + libdir], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()
+    assert out == ["0", "1", "1", str(64 * 576)]
