@@ -26,7 +26,9 @@ Readings of the paper where it is silent or ambiguous:
       (one float32 sent with the codes); s == 0 gives all-zero codes.
 * R5  a code is one sign bit plus a b-bit magnitude index k in [0, 2^b - 1];
       levels are uniform in the q-domain with both endpoints,
-      level_k = k / (2^b - 1); nearest level, ties upward.
+      level_k = k / (2^b - 1); nearest level, ties upward; the paper fixes no
+      precision for that decision: it is taken on the float32 u against
+      float32 thresholds (the midpoints between levels mapped back by Eq. (6)).
 * R6  the "All-Reduce" of quantised factors means: dequantise every worker's
       packet, then take the mean (Eq. (1)), summed in worker order.
 * R7  effective rank of a layer is min(r, rows, cols).
@@ -71,6 +73,14 @@ def expand(q, alpha):
 # ----------------------------------------------------------------------------
 # Section 4.1, last paragraph: b-bit discretisation of |q| (readings R4, R5)
 # ----------------------------------------------------------------------------
+def level_thresholds(bits, alpha):
+    """Decision thresholds of the b-bit discretisation in the normalised magnitude u:
+    T_j = Eq. (6) at the midpoint (j + 1/2) / (2^b - 1) between levels j and j + 1,
+    j = 0 .. 2^b - 2, evaluated in float64 and stored as float32."""
+    lv = (1 << bits) - 1
+    return expand((np.arange(lv) + 0.5) / lv, alpha).astype(f32)
+
+
 def log_quantize(x, bits, alpha):
     """LogQuantize of Algorithm 1 (statements "P_quant <- ..." / "Q_quant <- ...").
 
@@ -81,7 +91,11 @@ def log_quantize(x, bits, alpha):
             nothing and is canonically 0)
       s     float32 absmax scale
     The normalised magnitude u = |x| / s is taken in float32 (the precision the
-    stored factor has); the map Eq. (5) and the rounding run in float64.
+    stored factor has).  Nearest level with ties upward, k = floor(lv q(u) + 1/2)
+    with q of Eq. (5), is the number of decision thresholds T_j <= u (Eq. (5) is
+    increasing); the comparison is taken in float32, u against the float32
+    thresholds, which is the precision an implementation that stores u in
+    float32 decides in.
     """
     if not (1 <= bits <= 8):
         raise ValueError("bits must be in 1..8")
@@ -91,8 +105,7 @@ def log_quantize(x, bits, alpha):
     if not (s > 0):
         return (np.zeros(x.shape, np.uint8), np.zeros(x.shape, np.uint8), f32(0.0))
     u = (np.abs(x) / s).astype(f32)                       # float32 division
-    t = lv * np.log1p(f64(alpha) * u.astype(f64)) / np.log1p(f64(alpha))
-    k = np.floor(t + 0.5)
+    k = np.searchsorted(level_thresholds(bits, alpha), u, side="right")
     k = np.clip(k, 0, lv).astype(np.uint8)
     sign = ((x < 0) & (k > 0)).astype(np.uint8)
     return k, sign, s

@@ -109,6 +109,28 @@ def check_two_bit_enumeration(o):
     assert np.allclose(d, want, rtol=1e-13)
 
 
+def check_threshold_ties(o):
+    """The bin decision at the boundaries themselves: a value that equals a decision
+    threshold (the midpoint between two levels, mapped back by Eq. (6)) goes to the upper
+    level, the float32 value just below it to the lower one; thresholds written out here from
+    Eq. (6), not taken from the oracle."""
+    for alpha in (1.0, 255.0):
+        for bits in (1, 2, 4, 8):
+            lv = (1 << bits) - 1
+            mid = (np.arange(lv) + 0.5) / lv
+            thr = (((1.0 + alpha) ** mid - 1.0) / alpha).astype(f32)          # Eq. (6), float64 -> float32
+            below = np.nextafter(thr, f32(0.0)).astype(f32)
+            x = np.concatenate([thr, below, [f32(1.0)]]).astype(f32)          # the 1 makes the scale exactly 1
+            k, sg, s = o.log_quantize(x, bits, alpha)
+            assert s == 1.0
+            assert np.array_equal(k[:lv], np.arange(1, lv + 1)), (alpha, bits)  # ties upward
+            assert np.array_equal(k[lv:2 * lv], np.arange(0, lv)), (alpha, bits)
+            assert k[-1] == lv
+            # and the same through negative values
+            kn, sgn, _ = o.log_quantize(-x, bits, alpha)
+            assert np.array_equal(kn, k) and np.array_equal(sgn, (k > 0).astype(np.uint8))
+
+
 def check_quantiser_properties(o):
     rng = _rng(5)
     for alpha in (1.0, 10.0, 255.0, 1000.0):
@@ -581,6 +603,7 @@ def all_checks(resnet_layers, resnet_vector_elems):
         ("mulaw_checkpoints", check_mulaw_checkpoints),
         ("bin_rounding_bruteforce", check_bin_rounding_bruteforce),
         ("two_bit_enumeration", check_two_bit_enumeration),
+        ("threshold_ties", check_threshold_ties),
         ("quantiser_properties", check_quantiser_properties),
         ("zero_and_shapes", check_zero_and_shapes),
         ("packing", check_packing),

@@ -19,7 +19,10 @@ from paper_2506_17974_amd import binding as B
 f32, f64 = np.float32, np.float64
 FP_TOL = 1e-4          # relative Frobenius error allowed on fp32 factors and residuals
 MEAN_TOL = 2e-6        # dequantise-and-mean: a handful of fp32 roundings
-CODE_FLIP_BUDGET = 1e-5
+# Codes: both sides take the bin decision in float32 (u against float32 thresholds), so the codes
+# of the HIP path must equal the oracle's on the same factor, all of them.  (The bar the task
+# states is looser: differences within 1 ulp of a bucket boundary on at most 1e-5 of the elements.)
+CODE_FLIP_BUDGET = 0.0
 
 
 def rel_fro(a, b):
@@ -37,8 +40,9 @@ def to_device(arrs):
 
 def check_codes(x_gpu, k_gpu, s_gpu, scale_gpu, bits, alpha):
     """Oracle quantiser applied to the HIP path's own pre-quantisation tensor.
-    Returns the number of elements whose code differs; each of those must sit
-    within one fp32 ulp of a bucket boundary and differ by exactly one level."""
+    Returns the number of elements whose code differs (the caller requires zero); should one
+    ever differ, it is first classified here: anything but a one-level difference within one
+    fp32 ulp of a bucket boundary fails at once with that message."""
     k, sg, s = orc.log_quantize(x_gpu, bits, alpha)
     assert f32(scale_gpu) == s, "absmax scale differs: %r vs %r" % (scale_gpu, s)
     diff = k.astype(np.int32) != k_gpu.astype(np.int32)
@@ -189,11 +193,7 @@ def staged_iteration(comp: B.Compressor, G_host, G_dev, E_host, Q_host, matrix_l
                 # behind G-hat rounds r times, each relative to the size of its terms
                 scale = np.abs(M[(li, w)]) + absterms
                 assert np.all(np.abs(e_gpu.astype(f64) + ghat - M[(li, w)]) <= (r_l + 2) * 6e-8 * scale + 1e-30)
-    # budget: 1e-5 of the elements.  Every flip has already been verified above to be a one-level
-    # difference within 1 ulp of a bucket boundary; at b = 8 about 8e-6 of all fp32 values sit that
-    # close to one of the 255 boundaries, so on the small edge-case sets (below 2e5 elements, expected
-    # count under 2) the count is allowed to reach 2 rather than being held to a fraction of one.
-    assert rep.code_flips <= max(2, int(np.ceil(CODE_FLIP_BUDGET * rep.code_elems))), str(rep)
+    assert rep.code_flips <= CODE_FLIP_BUDGET * rep.code_elems, str(rep)
     return E_new, Q_bar
 
 
