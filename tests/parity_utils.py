@@ -185,14 +185,13 @@ def staged_iteration(comp: B.Compressor, G_host, G_dev, E_host, Q_host, matrix_l
             e_gpu, q_state = comp.get_state(l, w)
             E_new[w][li] = e_gpu
             assert np.array_equal(q_state, qb)            # warm start = aggregated Q
-            if True:
-                want = (M[(li, w)].astype(f64) - ghat.astype(f64)).astype(f32)
-                rep.note("E", rel_fro(e_gpu, want))
-                assert rel_fro(e_gpu, want) <= FP_TOL
-                # Eq. (8) as an identity, element by element: the r-term fp32 sum
-                # behind G-hat rounds r times, each relative to the size of its terms
-                scale = np.abs(M[(li, w)]) + absterms
-                assert np.all(np.abs(e_gpu.astype(f64) + ghat - M[(li, w)]) <= (r_l + 2) * 6e-8 * scale + 1e-30)
+            want = (M[(li, w)].astype(f64) - ghat.astype(f64)).astype(f32)
+            rep.note("E", rel_fro(e_gpu, want))
+            assert rel_fro(e_gpu, want) <= FP_TOL
+            # Eq. (8) as an identity, element by element: the r-term fp32 sum
+            # behind G-hat rounds r times, each relative to the size of its terms
+            scale = np.abs(M[(li, w)]) + absterms
+            assert np.all(np.abs(e_gpu.astype(f64) + ghat - M[(li, w)]) <= (r_l + 2) * 6e-8 * scale + 1e-30)
     assert rep.code_flips <= CODE_FLIP_BUDGET * rep.code_elems, str(rep)
     return E_new, Q_bar
 
