@@ -57,6 +57,9 @@ typedef const float __attribute__((address_space(4)))* const_fp;
 #ifndef LQSGD_RT           // rows a wavefront carries through one column pass of sweep 0 (rank <= 8)
 #define LQSGD_RT 8
 #endif
+#ifndef LQSGD_BM_U
+#define LQSGD_BM_U 8   // pairs of rows per step of the matrix-core sweep 1 (4: 829 us, 8: 750 us, 16: 833 us at 8192^2 x 16)
+#endif
 #ifndef LQSGD_B_U          // rows a wavefront of sweep 1 has in flight
 #define LQSGD_B_U 8
 #endif
@@ -1185,8 +1188,44 @@ __device__ __forceinline__ void back_project_mfma_tile(const DevArgs& a, const L
   for (int s = 0; s < 4; ++s)
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[s][i] = 0.0f;
-  constexpr int U = 4;
-  for (int rb = tl.row0; rb < rend; rb += 2 * U) {
+  constexpr int UI = LQSGD_BM_U;   // pairs of rows per step on interior strips
+  constexpr int U = 4;             // ... and on the bounds-tested path
+  int rb = tl.row0;
+  if constexpr (VEC4) {
+    // Interior strips (all 128 columns exist): whole groups of 2 UI rows with no bounds
+    // tests, and the next group's loads are issued before this group's matrix instructions, so that a
+    // wavefront overlaps its own loads with its own arithmetic (the last prefetch re-reads the last
+    // group: every load stays unconditional and in bounds).
+    if (c0 + 128 <= cols && rend - rb >= 2 * UI) {
+      const int last = rb + ((rend - rb) / (2 * UI) - 1) * (2 * UI);   // first row of the last whole group
+      Pk<4> am[UI], an[UI];
+      float bp[UI], bn[UI];
+      const int lic = min(li, r - 1);      // ranks beyond r: read a valid element, masked below
+#pragma unroll
+      for (int u = 0; u < UI; ++u) {
+        const int row = rb + 2 * u + h;
+        am[u] = ldrow<4, LQSGD_NT_M != 0>(reinterpret_cast<const char*>(M + (size_t)row * cols), (unsigned)cl * 4u);
+        bp[u] = Pb[(size_t)row * r + lic];
+      }
+      for (; rb <= last; rb += 2 * UI) {
+        const int nb = min(rb + 2 * UI, last);
+#pragma unroll
+        for (int u = 0; u < UI; ++u) {
+          const int row = nb + 2 * u + h;
+          an[u] = ldrow<4, LQSGD_NT_M != 0>(reinterpret_cast<const char*>(M + (size_t)row * cols), (unsigned)cl * 4u);
+          bn[u] = Pb[(size_t)row * r + lic];
+        }
+#pragma unroll
+        for (int u = 0; u < UI; ++u)
+#pragma unroll
+          for (int s = 0; s < 4; ++s)
+            acc[s] = __builtin_amdgcn_mfma_f32_32x32x2f32(am[u].v[s], keep_if(bp[u], rankok), acc[s], 0, 0, 0);
+#pragma unroll
+        for (int u = 0; u < UI; ++u) { am[u] = an[u]; bp[u] = bn[u]; }
+      }
+    }
+  }
+  for (; rb < rend; rb += 2 * U) {
     Pk<4> am[U];
     float bp[U];
 #pragma unroll
@@ -1245,7 +1284,53 @@ __device__ __forceinline__ void back_project_mfma_tile_nb(const DevArgs& a, cons
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[nb][s][i] = 0.0f;
   constexpr int U = 4;
-  for (int rb = tl.row0; rb < rend; rb += 2 * U) {
+  int rb = tl.row0;
+  if constexpr (VEC4) {
+    // interior strips: as in the one-block form, whole groups of rows without bounds tests and the
+    // next group's loads ahead of this group's matrix instructions; ranks beyond r are read from a
+    // clamped index and masked
+    if (c0 + 128 <= cols && rend - rb >= 2 * U) {
+      const int last = rb + ((rend - rb) / (2 * U) - 1) * (2 * U);
+      Pk<4> am[U], an[U];
+      float bp[NB][U], bn[NB][U];
+      int rkc[NB];
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) rkc[nb] = min(32 * nb + li, r - 1);
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int row = rb + 2 * u + h;
+        am[u] = ldrow<4, LQSGD_NT_M != 0>(reinterpret_cast<const char*>(M + (size_t)row * cols), (unsigned)cl * 4u);
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) bp[nb][u] = Pb[(size_t)row * r + rkc[nb]];
+      }
+      for (; rb <= last; rb += 2 * U) {
+        const int nxt = min(rb + 2 * U, last);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          const int row = nxt + 2 * u + h;
+          an[u] = ldrow<4, LQSGD_NT_M != 0>(reinterpret_cast<const char*>(M + (size_t)row * cols), (unsigned)cl * 4u);
+#pragma unroll
+          for (int nb = 0; nb < NB; ++nb) bn[nb][u] = Pb[(size_t)row * r + rkc[nb]];
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+          for (int nb = 0; nb < NB; ++nb) {
+            const float bv = keep_if(bp[nb][u], rankok[nb]);
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+              acc[nb][s] = __builtin_amdgcn_mfma_f32_32x32x2f32(am[u].v[s], bv, acc[nb][s], 0, 0, 0);
+          }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          am[u] = an[u];
+#pragma unroll
+          for (int nb = 0; nb < NB; ++nb) bp[nb][u] = bn[nb][u];
+        }
+      }
+    }
+  }
+  for (; rb < rend; rb += 2 * U) {
     Pk<4> am[U];
     float bp[NB][U];
 #pragma unroll
