@@ -16,6 +16,8 @@
  *     Section 3.2; neither letter is used here.)
  *   - "device pointer" = memory of the GPU that was current at lqsgd_create;
  *     "host pointer" = ordinary process memory.  Every pointer says which.
+ *     The caller keeps that GPU current in every later call on the context
+ *     (the library never switches devices).
  *   - Every function returns LQSGD_OK (0) or a negative lqsgd_status; nothing
  *     throws or aborts.  Arguments are validated on the host before any
  *     kernel is launched.  lqsgd_last_error() gives a text for the last

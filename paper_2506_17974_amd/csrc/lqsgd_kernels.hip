@@ -72,26 +72,39 @@ struct Pk {
   float v[V];
 };
 
+// Every tensor the kernels touch lives in device memory, but a pointer fetched from a pointer table
+// (the caller's gradient and output tensors) is a generic one as far as the compiler knows, and it
+// would use flat-address instructions for it, which complete out of order with the global ones and
+// force every wait to be a wait for everything.  The streaming loads and stores say "global" outright.
+template <typename T>
+__device__ __forceinline__ const T __attribute__((address_space(1)))* gptr(const void* p) {
+  return (const T __attribute__((address_space(1)))*)p;
+}
+template <typename T>
+__device__ __forceinline__ T __attribute__((address_space(1)))* gptr(void* p) {
+  return (T __attribute__((address_space(1)))*)p;
+}
+
 // VEC floats at (wave-uniform row base) + (per-lane byte offset).
 template <int V, bool NT>
 __device__ __forceinline__ Pk<V> ldrow(const char* rowbase, unsigned boff);
 template <>
 __device__ __forceinline__ Pk<4> ldrow<4, false>(const char* rowbase, unsigned boff) {
-  const v4f t = *reinterpret_cast<const v4f*>(rowbase + boff);
+  const v4f t = *gptr<v4f>(rowbase + boff);
   return Pk<4>{{t.x, t.y, t.z, t.w}};
 }
 template <>
 __device__ __forceinline__ Pk<4> ldrow<4, true>(const char* rowbase, unsigned boff) {
-  const v4f t = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(rowbase + boff));
+  const v4f t = __builtin_nontemporal_load(gptr<v4f>(rowbase + boff));
   return Pk<4>{{t.x, t.y, t.z, t.w}};
 }
 template <>
 __device__ __forceinline__ Pk<1> ldrow<1, false>(const char* rowbase, unsigned boff) {
-  return Pk<1>{{*reinterpret_cast<const float*>(rowbase + boff)}};
+  return Pk<1>{{*gptr<float>(rowbase + boff)}};
 }
 template <>
 __device__ __forceinline__ Pk<1> ldrow<1, true>(const char* rowbase, unsigned boff) {
-  return Pk<1>{{__builtin_nontemporal_load(reinterpret_cast<const float*>(rowbase + boff))}};
+  return Pk<1>{{__builtin_nontemporal_load(gptr<float>(rowbase + boff))}};
 }
 // The same for a row of bfloat16 values (gradients handed over in bfloat16): boff is the byte
 // offset the fp32 loaders would use; a bfloat16 is the upper half of the float it stands for.
@@ -100,12 +113,12 @@ template <int V, bool NT>
 __device__ __forceinline__ Pk<V> ldrow_bf16(const char* rowbase, unsigned boff) {
   Pk<V> r;
   if constexpr (V == 4) {
-    const v2u* p = reinterpret_cast<const v2u*>(rowbase + (boff >> 1));
+    const auto* p = gptr<v2u>(rowbase + (boff >> 1));
     const v2u t = NT ? __builtin_nontemporal_load(p) : *p;
     r.v[0] = __uint_as_float(t.x << 16); r.v[1] = __uint_as_float(t.x & 0xffff0000u);
     r.v[2] = __uint_as_float(t.y << 16); r.v[3] = __uint_as_float(t.y & 0xffff0000u);
   } else {
-    const unsigned short t = *reinterpret_cast<const unsigned short*>(rowbase + (boff >> 1));
+    const unsigned short t = *gptr<unsigned short>(rowbase + (boff >> 1));
     r.v[0] = __uint_as_float((unsigned)t << 16);
   }
   return r;
@@ -123,8 +136,8 @@ __device__ __forceinline__ const char* grad_row(const float* G, size_t off) {
 }
 template <bool GB16>
 __device__ __forceinline__ float grad_elem(const float* G, size_t idx) {
-  if constexpr (GB16) return __uint_as_float((unsigned)reinterpret_cast<const unsigned short*>(G)[idx] << 16);
-  else return G[idx];
+  if constexpr (GB16) return __uint_as_float((unsigned)gptr<unsigned short>(G)[idx] << 16);
+  else return gptr<float>(G)[idx];
 }
 
 template <int V, bool NT>
@@ -132,20 +145,20 @@ __device__ __forceinline__ void strow(char* rowbase, unsigned boff, const Pk<V>&
 template <>
 __device__ __forceinline__ void strow<4, false>(char* rowbase, unsigned boff, const Pk<4>& x) {
   const v4f t = {x.v[0], x.v[1], x.v[2], x.v[3]};
-  *reinterpret_cast<v4f*>(rowbase + boff) = t;
+  *gptr<v4f>(rowbase + boff) = t;
 }
 template <>
 __device__ __forceinline__ void strow<4, true>(char* rowbase, unsigned boff, const Pk<4>& x) {
   const v4f t = {x.v[0], x.v[1], x.v[2], x.v[3]};
-  __builtin_nontemporal_store(t, reinterpret_cast<v4f*>(rowbase + boff));
+  __builtin_nontemporal_store(t, gptr<v4f>(rowbase + boff));
 }
 template <>
 __device__ __forceinline__ void strow<1, false>(char* rowbase, unsigned boff, const Pk<1>& x) {
-  *reinterpret_cast<float*>(rowbase + boff) = x.v[0];
+  *gptr<float>(rowbase + boff) = x.v[0];
 }
 template <>
 __device__ __forceinline__ void strow<1, true>(char* rowbase, unsigned boff, const Pk<1>& x) {
-  __builtin_nontemporal_store(x.v[0], reinterpret_cast<float*>(rowbase + boff));
+  __builtin_nontemporal_store(x.v[0], gptr<float>(rowbase + boff));
 }
 
 // Factor slice of VEC consecutive columns starting at column c of a cols x r
@@ -1108,7 +1121,7 @@ __device__ __forceinline__ void back_project_tile(const DevArgs& a, const LayerD
 // ---------------------------------------------------------------------------
 __device__ __forceinline__ void vector_mean_tile(const DevArgs& a, const VTile& tl) {
   const VecDesc& vd = a.vecs[tl.vec];
-  float* extra = a.ghat ? a.ghat[vd.gidx] : nullptr;
+  auto* extra = gptr<float>(a.ghat ? a.ghat[vd.gidx] : nullptr);
   const float wf = (float)a.W;
   for (int i = 0; i < 4; ++i) {
     const int e = tl.el0 + i * 256 + threadIdx.x;
@@ -1117,7 +1130,7 @@ __device__ __forceinline__ void vector_mean_tile(const DevArgs& a, const VTile& 
       if (a.g_bf16) {
         for (int w = 0; w < a.W; ++w) s += grad_elem<true>(a.grads[(size_t)w * a.n_all + vd.gidx], (size_t)e);
       } else {
-        for (int w = 0; w < a.W; ++w) s += a.grads[(size_t)w * a.n_all + vd.gidx][e];
+        for (int w = 0; w < a.W; ++w) s += grad_elem<false>(a.grads[(size_t)w * a.n_all + vd.gidx], (size_t)e);
       }
       s /= wf;
       a.vmean[vd.off + e] = s;
@@ -1833,11 +1846,11 @@ __device__ __forceinline__ void mfma_tile32(const float* __restrict__ G, float* 
 #pragma unroll
   for (int i = 0; i < 16; ++i) { accP[i] = 0.0f; accP2[i] = 0.0f; }
 
-  auto block = [&](auto full_tag, const int c) {
+  // the G and E (or old M) values of one 32 x 32 block
+  auto fetch = [&](auto full_tag, const int c, Pk<4>* g, Pk<4>* e) {
     constexpr bool FULL = decltype(full_tag)::value;
     const int cl = c + c4;
     const bool colok = FULL || cl < col1;
-    Pk<4> g[4], e[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int rr = 8 * i + sr;
@@ -1850,6 +1863,11 @@ __device__ __forceinline__ void mfma_tile32(const float* __restrict__ G, float* 
         e[i] = ldrow<4, LQSGD_NT_E != 0>(reinterpret_cast<const char*>(M + off), (unsigned)cl * 4u);
       }
     }
+  };
+  auto block = [&](auto full_tag, const int c, Pk<4>* g, Pk<4>* e) {
+    constexpr bool FULL = decltype(full_tag)::value;
+    const int cl = c + c4;
+    const bool colok = FULL || cl < col1;
     if constexpr (NEEDG) {
       float qb[KH];
       const int col = c + li;
@@ -1930,11 +1948,145 @@ __device__ __forceinline__ void mfma_tile32(const float* __restrict__ G, float* 
     }
     wave_lds_fence();
   };
-  for (int c = col0 + 32 * wave; c < col1; c += 256) {
-    if (nrows == 32 && c + 32 <= col1)
-      block(std::true_type{}, c);
-    else
-      block(std::false_type{}, c);
+  // Interior blocks (all 32 rows and 32 columns exist) run without bounds tests, as a software
+  // pipeline inside the wavefront: the next block's G and E are requested before this block's matrix
+  // instructions, and the next block's G-hat operand from Q as soon as this block's G-hat is done.
+  // Requests complete in order, so everything a block waits for is requested before the prefetch.
+  int c = col0 + 32 * wave;
+  if (nrows == 32 && c + 32 <= col1 && cols < (1 << 26)) {   // (byte offsets within 8 rows fit 32 bits)
+    const int last = c + ((col1 - 32 - c) / 256) * 256;   // this wavefront's last whole block
+    Pk<4> g[4], e[4], gn[4], en[4];
+    if constexpr (EXACT) {
+      float qb[KH], bq[16];
+      // Addresses are a wave-uniform base (scalar registers, advanced by scalar adds) plus a byte
+      // offset per lane that does not change from block to block.
+      const unsigned goff = (unsigned)(sr * cols + c4) * 4u;      // lane's place in a slab of 8 rows
+      const unsigned qboff = (unsigned)(li * RP + KH * h) * 4u;   // ... in 32 rows of Q (G-hat operand)
+      const unsigned bqoff = (unsigned)(16 * h * RP + li) * 4u;   // ... in 32 rows of Q (P operand)
+      auto fetch_ge = [&](const int cb, Pk<4>* gg, Pk<4>* ee) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const size_t off = (size_t)(row0 + 8 * i) * cols + cb;
+          if constexpr (GB16) {   // kept packed (two registers) until the block is worked on
+            const auto* p = gptr<v2u>(grad_row<GB16>(G, off) + (goff >> 1));
+            const v2u t = LQSGD_NT_G ? __builtin_nontemporal_load(p) : *p;
+            gg[i].v[0] = __uint_as_float(t.x); gg[i].v[1] = __uint_as_float(t.y);
+          } else {
+            gg[i] = ldgrad<4, LQSGD_NT_G != 0, GB16>(grad_row<GB16>(G, off), goff);
+          }
+          ee[i] = ldrow<4, LQSGD_NT_E != 0>(reinterpret_cast<const char*>(M + off), goff);
+        }
+      };
+      auto fetch_qb = [&](const int cb) {
+        const char* base = reinterpret_cast<const char*>(Q + (size_t)cb * RP);
+#pragma unroll
+        for (int t = 0; t < KH / 4; ++t) {
+          const Pk<4> x = ldrow<4, false>(base + 16 * t, qboff);
+          qb[4 * t] = x.v[0]; qb[4 * t + 1] = x.v[1]; qb[4 * t + 2] = x.v[2]; qb[4 * t + 3] = x.v[3];
+        }
+      };
+      fetch_ge(c, g, e);
+      if constexpr (NEEDG) fetch_qb(c);
+      // one block; MORE: another whole block follows (a constant, so that no branch joins two
+      // request histories and every wait counts exactly)
+      auto step = [&](auto more_tag, const int c, Pk<4>* g, Pk<4>* e, Pk<4>* gn, Pk<4>* en) {
+        constexpr bool more = decltype(more_tag)::value;
+        {
+          const char* base = reinterpret_cast<const char*>(Q + (size_t)c * RP);
+#pragma unroll
+          for (int kk = 0; kk < 16; ++kk) bq[kk] = ldrow<1, false>(base + kk * RP * 4, bqoff).v[0];
+        }
+        if constexpr (more) fetch_ge(c + 256, gn, en);
+        __builtin_amdgcn_sched_barrier(0);   // the requests above stay ahead of the arithmetic below
+        if constexpr (NEEDG) {
+          v16f gh;
+#pragma unroll
+          for (int i = 0; i < 16; ++i) gh[i] = 0.0f;
+#pragma unroll
+          for (int k = 0; k < KH; ++k) gh = __builtin_amdgcn_mfma_f32_32x32x2f32(pa[k], qb[k], gh, 0, 0, 0);
+          __builtin_amdgcn_sched_barrier(0);
+          if constexpr (more) fetch_qb(c + 256);
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int v = 0; v < 16; ++v) lds[(8 * (v >> 2) + 4 * h + (v & 3)) * kLP32 + li] = gh[v];
+          wave_lds_fence();
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const float4 t = *reinterpret_cast<const float4*>(lds + (8 * i + sr) * kLP32 + c4);
+            e[i].v[0] -= t.x; e[i].v[1] -= t.y; e[i].v[2] -= t.z; e[i].v[3] -= t.w;
+          }
+          wave_lds_fence();
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int rr = 8 * i + sr;
+          Pk<4> m, gv = g[i];
+          if constexpr (GB16) {
+            const unsigned x = __float_as_uint(g[i].v[0]), y = __float_as_uint(g[i].v[1]);
+            gv.v[0] = __uint_as_float(x << 16); gv.v[1] = __uint_as_float(x & 0xffff0000u);
+            gv.v[2] = __uint_as_float(y << 16); gv.v[3] = __uint_as_float(y & 0xffff0000u);
+          }
+#pragma unroll
+          for (int v = 0; v < 4; ++v) m.v[v] = gv.v[v] + e[i].v[v];
+          strow<4, LQSGD_NT_ST_A != 0>(reinterpret_cast<char*>(M + (size_t)(row0 + 8 * i) * cols + c), goff, m);
+          *reinterpret_cast<float4*>(lds + rr * kLP32 + c4) = make_float4(m.v[0], m.v[1], m.v[2], m.v[3]);
+        }
+        wave_lds_fence();
+        {
+          const float4 a0 = *reinterpret_cast<const float4*>(lds + li * kLP32 + 16 * h);
+          const float4 a1 = *reinterpret_cast<const float4*>(lds + li * kLP32 + 16 * h + 4);
+          const float4 a2 = *reinterpret_cast<const float4*>(lds + li * kLP32 + 16 * h + 8);
+          const float4 a3 = *reinterpret_cast<const float4*>(lds + li * kLP32 + 16 * h + 12);
+          accP = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.x, bq[0], accP, 0, 0, 0);
+          accP2 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.x, bq[4], accP2, 0, 0, 0);
+          accP = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.y, bq[1], accP, 0, 0, 0);
+          accP2 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.y, bq[5], accP2, 0, 0, 0);
+          accP = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.z, bq[2], accP, 0, 0, 0);
+          accP2 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.z, bq[6], accP2, 0, 0, 0);
+          accP = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.w, bq[3], accP, 0, 0, 0);
+          accP2 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.w, bq[7], accP2, 0, 0, 0);
+          accP = __builtin_amdgcn_mfma_f32_32x32x2f32(a2.x, bq[8], accP, 0, 0, 0);
+          accP2 = __builtin_amdgcn_mfma_f32_32x32x2f32(a3.x, bq[12], accP2, 0, 0, 0);
+          accP = __builtin_amdgcn_mfma_f32_32x32x2f32(a2.y, bq[9], accP, 0, 0, 0);
+          accP2 = __builtin_amdgcn_mfma_f32_32x32x2f32(a3.y, bq[13], accP2, 0, 0, 0);
+          accP = __builtin_amdgcn_mfma_f32_32x32x2f32(a2.z, bq[10], accP, 0, 0, 0);
+          accP2 = __builtin_amdgcn_mfma_f32_32x32x2f32(a3.z, bq[14], accP2, 0, 0, 0);
+          accP = __builtin_amdgcn_mfma_f32_32x32x2f32(a2.w, bq[11], accP, 0, 0, 0);
+          accP2 = __builtin_amdgcn_mfma_f32_32x32x2f32(a3.w, bq[15], accP2, 0, 0, 0);
+        }
+        wave_lds_fence();
+      };
+      // two blocks per trip, the two register sets changing roles (no copies, so nothing waits for
+      // a prefetch before its values are needed)
+      for (; c + 256 < last; c += 512) {
+        step(std::true_type{}, c, g, e, gn, en);
+        step(std::true_type{}, c + 256, gn, en, g, e);
+      }
+      if (c < last) {
+        step(std::true_type{}, c, g, e, gn, en);
+        step(std::false_type{}, c + 256, gn, en, g, e);
+        c += 512;
+      } else {
+        step(std::false_type{}, c, g, e, gn, en);
+        c += 256;
+      }
+    } else {
+      fetch(std::true_type{}, c, g, e);
+      for (; c <= last; c += 256) {
+        const bool more = c < last;
+        if (more) fetch(std::true_type{}, c + 256, gn, en);
+        block(std::true_type{}, c, g, e);
+        if (more) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) { g[i] = gn[i]; e[i] = en[i]; }
+        }
+      }
+    }
+  }
+  for (; c < col1; c += 256) {
+    Pk<4> g[4], e[4];
+    fetch(std::false_type{}, c, g, e);
+    block(std::false_type{}, c, g, e);
   }
   // P partial of the item = sum over the eight wavefronts, added in wavefront order
 #pragma unroll
