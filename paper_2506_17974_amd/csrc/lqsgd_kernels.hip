@@ -1656,16 +1656,20 @@ __device__ __forceinline__ void mfma_tile(const float* __restrict__ G, float* __
     const int cl = c + c4;
     const bool colok = FULL || cl < col1;
     Pk<4> g[8], e[8];
+    // FULL blocks address memory as a wave-uniform base (scalar registers) plus one byte offset per
+    // lane that is the same for every row group and block: lo = this lane's place in 4 rows.
+    const unsigned lo = (unsigned)(sr * cols + c4) * 4u;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int rr = 4 * i + sr;
       const bool ok = FULL || (colok && rr < nrows);
-      const size_t off = (size_t)(row0 + rr) * cols;
+      const size_t off = FULL ? (size_t)(row0 + 4 * i) * cols + c : (size_t)(row0 + rr) * cols;
+      const unsigned bo = FULL ? lo : (unsigned)cl * 4u;
 #pragma unroll
       for (int v = 0; v < 4; ++v) { g[i].v[v] = 0.0f; e[i].v[v] = 0.0f; }
       if (ok) {
-        if constexpr (ADD) g[i] = ldgrad<4, LQSGD_NT_G != 0, GB16>(grad_row<GB16>(G, off), (unsigned)cl * 4u);
-        if constexpr (HASM) e[i] = ldrow<4, LQSGD_NT_E != 0>(reinterpret_cast<const char*>(M + off), (unsigned)cl * 4u);
+        if constexpr (ADD) g[i] = ldgrad<4, LQSGD_NT_G != 0, GB16>(grad_row<GB16>(G, off), bo);
+        if constexpr (HASM) e[i] = ldrow<4, LQSGD_NT_E != 0>(reinterpret_cast<const char*>(M + off), bo);
       }
     }
     float bq[NB][32];
@@ -1677,7 +1681,8 @@ __device__ __forceinline__ void mfma_tile(const float* __restrict__ G, float* __
           const int col = c + 32 * h + kk;
           const int rk = 32 * nb + li;
           if constexpr (FULL && EXACT)
-            bq[nb][kk] = Q[(size_t)col * RP + rk];
+            bq[nb][kk] = ldrow<1, false>(reinterpret_cast<const char*>(Q + (size_t)c * RP) + (kk * RP + 32 * nb) * 4,
+                                         (unsigned)(32 * h * RP + li) * 4u).v[0];
           else
             bq[nb][kk] = (col < col1 && rk < r) ? Q[(size_t)col * r + rk] : 0.0f;
         }
@@ -1688,7 +1693,14 @@ __device__ __forceinline__ void mfma_tile(const float* __restrict__ G, float* __
       for (int b = 0; b < 2; ++b) {
         const int col = c + 32 * b + li;
         if constexpr (EXACT) {
-          if (FULL || col < col1) {
+          if constexpr (FULL) {
+            const char* base = reinterpret_cast<const char*>(Q + (size_t)(c + 32 * b) * RP);
+#pragma unroll
+            for (int t = 0; t < KH / 4; ++t) {
+              const Pk<4> x = ldrow<4, false>(base + 16 * t, (unsigned)(li * RP + KH * h) * 4u);
+              qb[b][4 * t] = x.v[0]; qb[b][4 * t + 1] = x.v[1]; qb[b][4 * t + 2] = x.v[2]; qb[b][4 * t + 3] = x.v[3];
+            }
+          } else if (col < col1) {
             const float4* src = reinterpret_cast<const float4*>(Q + (size_t)col * RP + KH * h);
 #pragma unroll
             for (int t = 0; t < KH / 4; ++t) {
@@ -1728,7 +1740,10 @@ __device__ __forceinline__ void mfma_tile(const float* __restrict__ G, float* __
           e[i].v[0] -= t.x; e[i].v[1] -= t.y; e[i].v[2] -= t.z; e[i].v[3] -= t.w;
         }
         if (MODE == kMGhatOnly || (MODE == kMResidualGhat && ghat_out)) {
-          if (FULL || (colok && rr < nrows)) {
+          if constexpr (FULL) {
+            const Pk<4> o{{t.x, t.y, t.z, t.w}};
+            emit_ghat<4>(ghat_out + (size_t)(row0 + 4 * i) * cols + c, lo, o, update, eta);
+          } else if (colok && rr < nrows) {
             const Pk<4> o{{t.x, t.y, t.z, t.w}};
             emit_ghat<4>(ghat_out + (size_t)(row0 + rr) * cols, (unsigned)cl * 4u, o, update, eta);
           }
@@ -1743,7 +1758,9 @@ __device__ __forceinline__ void mfma_tile(const float* __restrict__ G, float* __
         Pk<4> m;
 #pragma unroll
         for (int v = 0; v < 4; ++v) m.v[v] = ADD ? g[i].v[v] + e[i].v[v] : e[i].v[v];
-        if (FULL || (colok && rr < nrows))
+        if constexpr (FULL)
+          strow<4, LQSGD_NT_ST_A != 0>(reinterpret_cast<char*>(M + (size_t)(row0 + 4 * i) * cols + c), lo, m);
+        else if (colok && rr < nrows)
           strow<4, LQSGD_NT_ST_A != 0>(reinterpret_cast<char*>(M + (size_t)(row0 + rr) * cols), (unsigned)cl * 4u, m);
         if constexpr (ADD)
           *reinterpret_cast<float4*>(lds + rr * kLP + c4) = make_float4(m.v[0], m.v[1], m.v[2], m.v[3]);
@@ -1771,8 +1788,9 @@ __device__ __forceinline__ void mfma_tile(const float* __restrict__ G, float* __
       wave_lds_fence();
     }
   };
+  const bool small_offsets = cols < (1 << 26);   // byte offsets within 4 rows fit 32 bits
   for (int c = col0 + 64 * wave; c < col1; c += 256) {
-    if (nrows == 32 && c + 64 <= col1)
+    if (nrows == 32 && c + 64 <= col1 && small_offsets)
       block(std::true_type{}, c);
     else
       block(std::false_type{}, c);
