@@ -53,6 +53,7 @@ struct lqsgd_ctx {
   const float** d_grads = nullptr; float** d_ghat = nullptr;
   std::vector<const float*> h_grads; std::vector<float*> h_ghat;
   bool grads_valid = false, ghat_valid = false;
+  bool ppad_stale = true, qpad_stale = true;   // the padded copies of P-bar / Q-bar lag behind the factors
   bool alias_checked = false;   // the bound gradient and output tables have been checked against each other
   // timing
   bool timing = false;
@@ -185,10 +186,28 @@ int next_dir(lqsgd_ctx* c) {
   return d;
 }
 
+// Matrix-core sweeps 0 / 2 read P-bar and Q-bar from copies with padded rows when some layer has
+// fewer ranks than the register pad; whoever writes a factor marks its copy stale.
+int refresh_padded(lqsgd_ctx* c, bool need_p, bool need_q) {
+  if (!c->plan.padded) return LQSGD_OK;
+  if (need_p && c->ppad_stale) {
+    HIP_TRY(c, launch_pad_factor(c->plan.RP, 0, c->args, c->stream));
+    c->ppad_stale = false;
+  }
+  if (need_q && c->qpad_stale) {
+    HIP_TRY(c, launch_pad_factor(c->plan.RP, 1, c->args, c->stream));
+    c->qpad_stale = false;
+  }
+  return LQSGD_OK;
+}
+int full_rank(const lqsgd_ctx* c) { return (c->plan.max_rank == c->plan.RP || c->plan.padded) ? 1 : 0; }
+
 int run_sweep0(lqsgd_ctx* c) {
+  if (c->plan.mfma_a)
+    if (int rc = refresh_padded(c, c->pending, true)) return rc;
   { Timed t(c, LQSGD_KERNEL_ADD_PROJECT);
     if (c->plan.mfma_a)
-      HIP_TRY(c, launch_mfma_sweep(c->plan.RP, c->pending ? 1 : 0, (c->plan.max_rank == c->plan.RP) ? 1 : 0, c->args, c->d_tilesA, (int)c->plan.tilesA.size(),
+      HIP_TRY(c, launch_mfma_sweep(c->plan.RP, c->pending ? 1 : 0, full_rank(c), c->args, c->d_tilesA, (int)c->plan.tilesA.size(),
                                    next_dir(c), c->stream));
     else
       HIP_TRY(c, launch_add_project(c->plan.RP, c->args, c->d_tilesA, (int)c->plan.tilesA.size(), c->pending ? 1 : 0,
@@ -214,6 +233,7 @@ int run_orth_shared(lqsgd_ctx* c) {
   a.Ppre = c->args.Porth;
   a.Porth = c->args.Pbar;
   HIP_TRY(c, launch_orth(c->plan.RP, c->plan.max_rows, c->plan.max_rank, a, &c->orth_epoch, c->stream));
+  c->ppad_stale = true;
   return LQSGD_OK;
 }
 int run_exchange(lqsgd_ctx* c, int mode, int phase) {
@@ -221,7 +241,8 @@ int run_exchange(lqsgd_ctx* c, int mode, int phase) {
     const auto& tl = phase ? c->plan.tilesXQ : c->plan.tilesXP;
     DevArgs a = c->args;
     if (c->plan.agg_first && phase == 0) a.Porth = c->args.Ppre;   // the raw factors are what gets quantised
-    HIP_TRY(c, launch_exchange(mode, phase, a, phase ? c->d_tilesXQ : c->d_tilesXP, (int)tl.size(), c->stream)); }
+    HIP_TRY(c, launch_exchange(mode, phase, a, phase ? c->d_tilesXQ : c->d_tilesXP, (int)tl.size(), c->stream));
+    if (mode != kQuantOnly) (phase ? c->qpad_stale : c->ppad_stale) = true; }
   if (c->plan.agg_first && phase == 0 && mode != kQuantOnly) return run_orth_shared(c);
   return LQSGD_OK;
 }
@@ -242,17 +263,19 @@ int run_sweep1(lqsgd_ctx* c, bool with_vectors) {
 // in place and let the next iteration's first sweep apply it on the fly; G-hat,
 // when asked for, is then written by a pass of its own over the layers.
 int run_sweep2(lqsgd_ctx* c, bool write_ghat) {
-  Timed t(c, LQSGD_KERNEL_RESIDUAL);
   const Plan& p = c->plan;
+  if (p.mfma_a && (c->eager || write_ghat))
+    if (int rc = refresh_padded(c, true, true)) return rc;
+  Timed t(c, LQSGD_KERNEL_RESIDUAL);
   if (c->eager) {
     if (p.mfma_a)
-      HIP_TRY(c, launch_mfma_sweep(p.RP, write_ghat ? 3 : 2, (c->plan.max_rank == c->plan.RP) ? 1 : 0, c->args, c->d_tilesA, (int)p.tilesA.size(), next_dir(c), c->stream));
+      HIP_TRY(c, launch_mfma_sweep(p.RP, write_ghat ? 3 : 2, full_rank(c), c->args, c->d_tilesA, (int)p.tilesA.size(), next_dir(c), c->stream));
     else
       HIP_TRY(c, launch_residual(p.RP, write_ghat ? 1 : 0, c->args, c->d_tilesB, (int)p.tilesB.size(), next_dir(c), c->stream));
   } else {
     if (write_ghat) {
       if (p.mfma_a)
-        HIP_TRY(c, launch_mfma_sweep(p.RP, 4, (c->plan.max_rank == c->plan.RP) ? 1 : 0, c->args, c->d_tilesAG, (int)p.tilesAG.size(), 0, c->stream));
+        HIP_TRY(c, launch_mfma_sweep(p.RP, 4, full_rank(c), c->args, c->d_tilesAG, (int)p.tilesAG.size(), 0, c->stream));
       else
         HIP_TRY(c, launch_residual(p.RP, 2, c->args, c->d_tilesG, (int)p.tilesG.size(), 0, c->stream));
     }
@@ -263,10 +286,12 @@ int run_sweep2(lqsgd_ctx* c, bool write_ghat) {
 // Applies a deferred residual update, so that the buffer holds E again.
 int materialise(lqsgd_ctx* c) {
   if (!c->pending) return LQSGD_OK;
-  Timed t(c, LQSGD_KERNEL_RESIDUAL);
   const Plan& p = c->plan;
   if (p.mfma_a)
-    HIP_TRY(c, launch_mfma_sweep(p.RP, 2, (c->plan.max_rank == c->plan.RP) ? 1 : 0, c->args, c->d_tilesA, (int)p.tilesA.size(), next_dir(c), c->stream));
+    if (int rc = refresh_padded(c, true, true)) return rc;
+  Timed t(c, LQSGD_KERNEL_RESIDUAL);
+  if (p.mfma_a)
+    HIP_TRY(c, launch_mfma_sweep(p.RP, 2, full_rank(c), c->args, c->d_tilesA, (int)p.tilesA.size(), next_dir(c), c->stream));
   else
     HIP_TRY(c, launch_residual(p.RP, 0, c->args, c->d_tilesB, (int)p.tilesB.size(), next_dir(c), c->stream));
   c->pending = false;
@@ -428,6 +453,11 @@ int lqsgd_create(const lqsgd_config* cfg, const lqsgd_layer* layers, int32_t n_l
   TRY_(dev_alloc(c, &a.Qpart, W * p.qpart_stride + kSlack, true));
   TRY_(dev_alloc(c, &a.Qw, W * p.q_stride + kSlack, true));
   TRY_(dev_alloc(c, &a.Qbar, (size_t)p.q_stride + kSlack, true));
+  a.Ppad = nullptr; a.Qpad = nullptr;
+  if (p.padded) {
+    TRY_(dev_alloc(c, &a.Ppad, (size_t)p.ppad_total + kSlack, true));
+    TRY_(dev_alloc(c, &a.Qpad, (size_t)p.qpad_total + kSlack, true));
+  }
   TRY_(dev_alloc(c, &a.magP, W * p.magp_stride, true));
   TRY_(dev_alloc(c, &a.sgnP, W * p.sgnp_stride, true));
   TRY_(dev_alloc(c, &a.scaleP, W * (size_t)std::max(p.L, 1), true));
@@ -515,8 +545,10 @@ int lqsgd_set_state(lqsgd_ctx* c, int32_t layer, int32_t worker, const float* ho
   if (host_e)
     HIP_TRY(c, hipMemcpy(c->args.E + (size_t)worker * c->args.m_stride + ld->m_off, host_e,
                          (size_t)ld->rows * ld->cols * sizeof(float), hipMemcpyHostToDevice));
-  if (host_q)
+  if (host_q) {
     HIP_TRY(c, hipMemcpy(c->args.Qbar + ld->q_off, host_q, (size_t)ld->nq_el * sizeof(float), hipMemcpyHostToDevice));
+    c->qpad_stale = true;
+  }
   return LQSGD_OK;
 }
 
@@ -725,6 +757,7 @@ int lqsgd_set_factor(lqsgd_ctx* c, int32_t which, int32_t layer, const float* ho
   if ((rc = materialise(c))) return rc;      // a deferred update is defined by the old factors
   if (int rcs = sync_stream(c)) return rcs;
   HIP_TRY(c, hipMemcpy(dst, host, n * sizeof(float), hipMemcpyHostToDevice));
+  (which == LQSGD_FACTOR_P_BAR ? c->ppad_stale : c->qpad_stale) = true;
   return LQSGD_OK;
 }
 

@@ -25,6 +25,7 @@ struct DevArgs {
   float* Qpart;                // sweep-1 partial products, per worker
   float* Qw;                   // Q_w
   float* Qbar;                 // aggregated Q = warm-start Q (shared)
+  float* Ppad; float* Qpad;    // copies of Pbar / Qbar with rows of RP ranks, zero beyond a layer's rank; null if unused
   uint8_t* magP; uint8_t* sgnP; float* scaleP;   // packets of the P exchange
   uint8_t* magQ; uint8_t* sgnQ; float* scaleQ;   // packets of the Q exchange
   const float* thrP; const float* levP;           // quantiser tables for b_p
@@ -71,6 +72,9 @@ hipError_t launch_residual(int RP, int mode, const DevArgs& a, const Tile* tiles
 // sweep 0 (32-row items).  mode: 0 = M = G + E and P partials, 1 = the same with the deferred
 // residual applied on the fly, 2 = residual, 3 = residual + G-hat, 4 = G-hat only (worker 0's items).
 // full_rank: the largest effective rank of the layers equals RP (chooses between two forms of the fused add mode).
+// Refreshes a.Ppad (which = 0) or a.Qpad (which = 1) from the tightly packed factor.
+hipError_t launch_pad_factor(int RP, int which, const DevArgs& a, hipStream_t s);
+
 hipError_t launch_mfma_sweep(int RP, int mode, int full_rank, const DevArgs& a, const Tile* tiles, int ntiles, int reverse,
                              hipStream_t s);
 

@@ -1619,6 +1619,9 @@ __device__ __forceinline__ void mfma_tile(const float* __restrict__ G, float* __
   constexpr bool HASM = (MODE != kMGhatOnly);
   constexpr int KH = RP / 2;                       // ranks per half-wavefront
   constexpr int NB = (RP + 31) / 32;               // blocks of 32 ranks in the P product (2 at rank pad 64)
+  // EXACT: the rows of Q and Pb hold RP ranks (the layer's rank is RP, or the operands are the copies
+  // padded with zeros); r is then only the row length of the P partials this item writes.
+  const int rs = EXACT ? RP : r;
   const int li = lane & 31, h = lane >> 5;
   const int sr = lane >> 4, c4 = (lane & 15) * 4;  // row layout: rows 4 i + sr, columns c4 .. c4 + 3
   float pa[KH];
@@ -1684,7 +1687,7 @@ __device__ __forceinline__ void mfma_tile(const float* __restrict__ G, float* __
             bq[nb][kk] = ldrow<1, false>(reinterpret_cast<const char*>(Q + (size_t)c * RP) + (kk * RP + 32 * nb) * 4,
                                          (unsigned)(32 * h * RP + li) * 4u).v[0];
           else
-            bq[nb][kk] = (col < col1 && rk < r) ? Q[(size_t)col * r + rk] : 0.0f;
+            bq[nb][kk] = (col < col1 && rk < rs) ? Q[(size_t)col * rs + rk] : 0.0f;
         }
     }
     if constexpr (NEEDG) {
@@ -1838,6 +1841,7 @@ __device__ __forceinline__ void mfma_tile32(const float* __restrict__ G, float* 
   float* lds = lds_all[wave];
   constexpr bool NEEDG = (MODE != kMAdd);
   constexpr int KH = RP / 2;
+  const int rs = EXACT ? RP : r;   // row length of the operands Q and Pb (r: that of the P partials written)
   const int li = lane & 31, h = lane >> 5;
   const int sr = lane >> 3, c4 = (lane & 7) * 4;   // row layout: rows 8 i + sr, columns c4 .. c4 + 3
   float pa[KH];
@@ -1939,7 +1943,7 @@ __device__ __forceinline__ void mfma_tile32(const float* __restrict__ G, float* 
       if constexpr (FULL && EXACT)
         bq[kk] = Q[(size_t)col * RP + li];
       else
-        bq[kk] = (col < col1 && li < r) ? Q[(size_t)col * r + li] : 0.0f;
+        bq[kk] = (col < col1 && li < rs) ? Q[(size_t)col * rs + li] : 0.0f;
     }
     wave_lds_fence();
     {
@@ -2207,7 +2211,10 @@ __global__ __launch_bounds__(256, RP <= 16 ? 2 : 1) void mfma_sweep_kernel(DevAr
     if (sub.nrows > 0) mfma_mode_vector_fallback<RP, MODE, GB16>(a, ld, sub, worker, G, M, Pp, ghat_out, col0, col1, lane);
     return;
   }
-  if (ld.r == RP)
+  if (a.Qpad)   // operands with rows of RP ranks, zero beyond the layer's rank
+    mfma_tile<RP, MODE, true, GB16>(G, M, a.Qpad + ld.qpad_off, a.Ppad + ld.ppad_off, Pp, ghat_out, ld.cols, ld.r, tl.row0,
+                              tl.nrows, col0, col1, lane, wave, lds_all, a.update, a.eta);
+  else if (ld.r == RP)
     mfma_tile<RP, MODE, true, GB16>(G, M, a.Qbar + ld.q_off, a.Pbar + ld.p_off, Pp, ghat_out, ld.cols, ld.r, tl.row0,
                               tl.nrows, col0, col1, lane, wave, lds_all, a.update, a.eta);
   else
@@ -2238,12 +2245,30 @@ __global__ __launch_bounds__(512, 2) void mfma_sweep32_kernel(DevArgs a, const T
     if (sub.nrows > 0) mfma_mode_vector_fallback<RP, MODE, GB16>(a, ld, sub, worker, G, M, Pp, nullptr, col0, col1, lane);
     return;
   }
-  if (ld.r == RP)
+  if (a.Qpad)
+    mfma_tile32<RP, MODE, true, GB16>(G, M, a.Qpad + ld.qpad_off, a.Ppad + ld.ppad_off, Pp, ld.cols, ld.r, tl.row0, tl.nrows,
+                                      col0, col1, lane, wave, lds_all);
+  else if (ld.r == RP)
     mfma_tile32<RP, MODE, true, GB16>(G, M, a.Qbar + ld.q_off, a.Pbar + ld.p_off, Pp, ld.cols, ld.r, tl.row0, tl.nrows,
                                       col0, col1, lane, wave, lds_all);
   else
     mfma_tile32<RP, MODE, false, GB16>(G, M, a.Qbar + ld.q_off, a.Pbar + ld.p_off, Pp, ld.cols, ld.r, tl.row0, tl.nrows,
                                        col0, col1, lane, wave, lds_all);
+}
+
+// Copies of the aggregated factors with rows of RP ranks (zero beyond the layer's rank) for the
+// matrix-core sweeps 0 / 2.  blockIdx.y = layer; which: 0 = P-bar, 1 = Q-bar.
+__global__ __launch_bounds__(256) void pad_factor_kernel(DevArgs a, int RP, int which) {
+  const LayerDesc& ld = a.layers[blockIdx.y];
+  const int n = which ? ld.cols : ld.rows, r = ld.r;
+  const float* src = which ? a.Qbar + ld.q_off : a.Pbar + ld.p_off;
+  float* dst = which ? a.Qpad + ld.qpad_off : a.Ppad + ld.ppad_off;
+  const long long total = (long long)n * RP;
+  for (long long e = blockIdx.x * 256 + threadIdx.x; e < total; e += gridDim.x * 256) {
+    const long long row = e / RP;
+    const int k = (int)(e - row * RP);
+    dst[e] = k < r ? src[row * r + k] : 0.0f;
+  }
 }
 
 }  // namespace
@@ -2489,6 +2514,12 @@ hipError_t launch_mfma_sweep(int rp, int mode, int full_rank, const DevArgs& a, 
   if (rp == 32) return launch_mfma_sweep_rp<32>(mode, full_rank, a, tiles, ntiles, reverse, s);
   if (rp == 64) return launch_mfma_sweep_rp<64>(mode, full_rank, a, tiles, ntiles, reverse, s);
   return hipErrorInvalidValue;
+}
+
+hipError_t launch_pad_factor(int RP, int which, const DevArgs& a, hipStream_t s) {
+  if (a.L <= 0 || !a.Ppad || !a.Qpad) return hipSuccess;
+  pad_factor_kernel<<<dim3(64, a.L), dim3(256), 0, s>>>(a, RP, which);
+  return hipGetLastError();
 }
 
 }  // namespace lqsgd

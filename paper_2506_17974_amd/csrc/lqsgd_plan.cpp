@@ -136,6 +136,8 @@ int Plan::build(const lqsgd_config* c, const lqsgd_layer* ls, int32_t n_layers) 
 
   int64_t m_acc = 0, p_acc = 0, q_acc = 0, pp_acc = 0, qp_acc = 0;
   int64_t mp_acc = 0, sp_acc = 0, mq_acc = 0, sq_acc = 0;
+  int64_t ppd_acc = 0, qpd_acc = 0;
+  padded = false;
   wire_bytes = 0;
   for (int li = 0; li < L; ++li) {
     LayerDesc& d = layers[li];
@@ -168,6 +170,9 @@ int Plan::build(const lqsgd_config* c, const lqsgd_layer* ls, int32_t n_layers) 
     d.q_off = q_acc;   q_acc += round_up(d.nq_el, 64);
     d.ppart_off = pp_acc; pp_acc += (int64_t)d.nseg * d.np_pad;
     d.qpart_off = qp_acc; qp_acc += (int64_t)d.nrb * d.nq_pad;
+    d.ppad_off = ppd_acc; ppd_acc += round_up((int64_t)d.rows * RP, 64);
+    d.qpad_off = qpd_acc; qpd_acc += round_up((int64_t)d.cols * RP, 64);
+    if (mfma_a && d.vec == 4 && d.r < RP && env_i64("LQSGD_NO_PAD_OPERANDS", 0) == 0) padded = true;
     const int64_t gp = (d.np_el + kXGroup - 1) / kXGroup, gq = (d.nq_el + kXGroup - 1) / kXGroup;
     d.magp_off = mp_acc; mp_acc += round_up(gp * std::max(1, cfg.bits_p), 16);
     d.sgnp_off = sp_acc; sp_acc += round_up(gp, 16);
@@ -213,6 +218,8 @@ int Plan::build(const lqsgd_config* c, const lqsgd_layer* ls, int32_t n_layers) 
   sgnp_stride = round_up(sp_acc, 64);
   magq_stride = round_up(mq_acc, 64);
   sgnq_stride = round_up(sq_acc, 64);
+  ppad_total = padded ? ppd_acc : 0;
+  qpad_total = padded ? qpd_acc : 0;
 
   int64_t v_acc = 0;
   for (int vi = 0; vi < V; ++vi) {
@@ -226,7 +233,7 @@ int Plan::build(const lqsgd_config* c, const lqsgd_layer* ls, int32_t n_layers) 
                              (int64_t)(tilesXP.size() + tilesXQ.size()) * sizeof(XTile) +
                              (int64_t)(tilesRQ.size() + tilesRP.size()) * sizeof(RTile) + (int64_t)tilesV.size() * sizeof(VTile);
   device_bytes = 4 * ((int64_t)W * (m_stride + 2 * p_stride + q_stride + ppart_stride + qpart_stride) +
-                      p_stride + q_stride + v_total + 2 * (int64_t)W * std::max(L, 1) +
+                      p_stride + q_stride + ppad_total + qpad_total + v_total + 2 * (int64_t)W * std::max(L, 1) +
                       6 * (int64_t)W * std::max(L, 1) * ((max_rows + 255) / 256) * RP) +
                  (int64_t)W * (magp_stride + sgnp_stride + magq_stride + sgnq_stride) + tile_bytes +
                  (int64_t)L * sizeof(LayerDesc) + (int64_t)V * sizeof(VecDesc) +

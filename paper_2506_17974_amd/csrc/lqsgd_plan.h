@@ -34,6 +34,7 @@ struct LayerDesc {
   int64_t qpart_off;            // nrb planes of nq_pad  (worker stride qpart_stride)
   int64_t magp_off, sgnp_off;   // bytes (worker strides magp_stride, sgnp_stride)
   int64_t magq_off, sgnq_off;   // bytes
+  int64_t ppad_off, qpad_off;   // into the copies of P-bar / Q-bar with rows padded to RP ranks (Plan::padded)
 };
 
 struct VecDesc {
@@ -77,6 +78,11 @@ struct Plan {
   std::vector<RTile> tilesRQ;
   std::vector<RTile> tilesRP;      // aggregate-first order: reduce of the P partials (1024 elements each)
   bool agg_first = false;          // LQSGD_FLAG_AGGREGATE_FIRST
+  // Some layer that the matrix-core sweeps 0 / 2 handle has fewer ranks than the register pad: these
+  // sweeps then read P-bar and Q-bar from copies whose rows are padded with zeros to RP ranks
+  // (16-byte aligned rows, no rank tests in the loops); ppad_total / qpad_total floats.
+  bool padded = false;
+  int64_t ppad_total = 0, qpad_total = 0;
   std::vector<VTile> tilesV;
   int64_t m_stride = 0, p_stride = 0, q_stride = 0, ppart_stride = 0, qpart_stride = 0;
   int64_t magp_stride = 0, sgnp_stride = 0, magq_stride = 0, sgnq_stride = 0, v_total = 0;
