@@ -298,6 +298,15 @@ __device__ __forceinline__ float wave_max(float x) {
 
 constexpr int log2c(int n) { return n <= 1 ? 0 : 1 + log2c(n / 2); }
 
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>), in order.
+template <int N, int I = 0, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (I < N) {
+    f(std::integral_constant<int, I>{});
+    static_for<N, I + 1>(f);
+  }
+}
+
 // ---------------------------------------------------------------------------
 // sweep 0: M = G + E (Eq. (9)),  P_w partial = M_w Q  (Algorithm 1, "P <- G'Q")
 // One wavefront per work item: rows [row0, row0+nrows) x columns [col0, col1),
@@ -564,35 +573,73 @@ __global__ __launch_bounds__(BS) void orth_reg_kernel(DevArgs a) {
     }
   }
 
-#pragma unroll
-  for (int j = 0; j < RP; ++j) {
-    if (j < r) {
-      float s[RP];
-#pragma unroll
-      for (int k = 0; k < RP; ++k) s[k] = 0.0f;
-#pragma unroll
-      for (int i = 0; i < RPT; ++i)
-#pragma unroll
-        for (int k = 0; k < RP; ++k) s[k] = fmaf(v[i][j], v[i][k], s[k]);
-      transpose_reduce<RP, RP, 32>(s, lane);
-      const int b = j & 1;
-      if ((lane & (kWave / RP - 1)) == 0) red[b][wave][lane >> (6 - LG)] = s[0];
-      __syncthreads();
-#pragma unroll
-      for (int k = 0; k < RP; ++k) {
-        float t = 0.0f;
-#pragma unroll
-        for (int wv = 0; wv < NW; ++wv) t += red[b][wv][k];
-        s[k] = t;
+  // The column index must reach every use as a constant, so that the rows stay in registers (a
+  // run-time index would move v to scratch memory).  Up to rank pad 16 unrolling does that; at rank
+  // pad 32 the loop is too large to be unrolled on request, and each column is an instantiation.
+  if constexpr (RP >= 32) {
+    static_for<RP>([&](auto jc) __attribute__((always_inline)) {
+      constexpr int j = decltype(jc)::value;
+      if (j < r) {
+        float s[RP];
+  #pragma unroll
+        for (int k = 0; k < RP; ++k) s[k] = 0.0f;
+  #pragma unroll
+        for (int i = 0; i < RPT; ++i)
+  #pragma unroll
+          for (int k = 0; k < RP; ++k) s[k] = fmaf(v[i][j], v[i][k], s[k]);
+        transpose_reduce<RP, RP, 32>(s, lane);
+        const int b = j & 1;
+        if ((lane & (kWave / RP - 1)) == 0) red[b][wave][lane >> (6 - LG)] = s[0];
+        __syncthreads();
+  #pragma unroll
+        for (int k = 0; k < RP; ++k) {
+          float t = 0.0f;
+  #pragma unroll
+          for (int wv = 0; wv < NW; ++wv) t += red[b][wv][k];
+          s[k] = t;
+        }
+        const float nrm2 = s[j];
+        const float inv = (nrm2 > FLT_MIN) ? 1.0f / sqrtf(nrm2) : 0.0f;
+  #pragma unroll
+        for (int i = 0; i < RPT; ++i) {
+          const float qv = v[i][j] * inv;
+          v[i][j] = qv;
+  #pragma unroll
+          for (int k = j + 1; k < RP; ++k) v[i][k] = fmaf(-(s[k] * inv), qv, v[i][k]);
+        }
       }
-      const float nrm2 = s[j];
-      const float inv = (nrm2 > FLT_MIN) ? 1.0f / sqrtf(nrm2) : 0.0f;
+    });
+  } else {
 #pragma unroll
-      for (int i = 0; i < RPT; ++i) {
-        const float qv = v[i][j] * inv;
-        v[i][j] = qv;
-#pragma unroll
-        for (int k = j + 1; k < RP; ++k) v[i][k] = fmaf(-(s[k] * inv), qv, v[i][k]);
+    for (int j = 0; j < RP; ++j) {
+      if (j < r) {
+        float s[RP];
+  #pragma unroll
+        for (int k = 0; k < RP; ++k) s[k] = 0.0f;
+  #pragma unroll
+        for (int i = 0; i < RPT; ++i)
+  #pragma unroll
+          for (int k = 0; k < RP; ++k) s[k] = fmaf(v[i][j], v[i][k], s[k]);
+        transpose_reduce<RP, RP, 32>(s, lane);
+        const int b = j & 1;
+        if ((lane & (kWave / RP - 1)) == 0) red[b][wave][lane >> (6 - LG)] = s[0];
+        __syncthreads();
+  #pragma unroll
+        for (int k = 0; k < RP; ++k) {
+          float t = 0.0f;
+  #pragma unroll
+          for (int wv = 0; wv < NW; ++wv) t += red[b][wv][k];
+          s[k] = t;
+        }
+        const float nrm2 = s[j];
+        const float inv = (nrm2 > FLT_MIN) ? 1.0f / sqrtf(nrm2) : 0.0f;
+  #pragma unroll
+        for (int i = 0; i < RPT; ++i) {
+          const float qv = v[i][j] * inv;
+          v[i][j] = qv;
+  #pragma unroll
+          for (int k = j + 1; k < RP; ++k) v[i][k] = fmaf(-(s[k] * inv), qv, v[i][k]);
+        }
       }
     }
   }
@@ -2314,7 +2361,7 @@ hipError_t launch_add_project(int rp, const DevArgs& a, const Tile* tiles, int n
 // file comfortably; the in-memory kernel otherwise.
 template <int RP, int RPT, int BS>
 void launch_orth_reg(const DevArgs& a, dim3 grid, hipStream_t s) {
-  if constexpr (RP * RPT <= (BS == 256 ? 64 : 48)) {
+  if constexpr (RP * RPT <= (BS == 256 ? (RPT == 2 ? 128 : 64) : 48)) {
     orth_reg_kernel<RP, RPT, BS><<<grid, dim3(BS), 0, s>>>(a);
   } else {
     orth_kernel<RP><<<grid, dim3(256), 0, s>>>(a);
@@ -2390,7 +2437,7 @@ hipError_t launch_orth(int rp, int max_rows, int max_rank, const DevArgs& a, uns
   const int nslice = (max_rows + 255) / 256;
   // Tall factors and too few (layer, worker) pairs to fill 256 CUs with one workgroup
   // each, or no register-resident variant for this rank: one launch per column.
-  const bool reg_fits = (max_rows <= 512 && rp * 2 <= 64) || (max_rows <= 2048 && rp * 8 <= 64) ||
+  const bool reg_fits = (max_rows <= 512 && rp * 2 <= 128) || (max_rows <= 2048 && rp * 8 <= 64) ||
                         (max_rows <= 4096 && rp * 4 <= 48) || (max_rows <= 11264 && rp * 11 <= 48);
   if (a.orth_part && nslice >= 8 && ((int)grid.x < 128 || !reg_fits)) {
     if (launch_orth_coop(rp, nslice, max_rank, a, (int)grid.x * nslice, coop_epoch, s)) return hipSuccess;

@@ -112,6 +112,7 @@ EDGE_CASES = [
     ([(129, 1028)], 2, 2, 2, 2, 255.0),
     ([(129, 1028)], 16, 8, 4, 2, 255.0),                   # b_p != b_q
     ([(96, 520)], 32, 8, 8, 2, 255.0),
+    ([(200, 1100), (10, 512), (64, 27)], 32, 8, 8, 2, 255.0),  # full, clipped (padded operand copies) and unaligned layers together
     ([(100, 1100), (33, 64)], 20, 8, 8, 2, 255.0),         # rank 20 in a rank pad of 32
     ([(70, 200)], 12, 8, 8, 2, 255.0),                     # rank 12 in a rank pad of 16
     ([(40, 36)], 32, 8, 8, 2, 255.0),                      # rank 32 clipped to 36 cols / 40 rows
@@ -333,7 +334,7 @@ def test_resnet18_free_run_matches_oracle_and_is_deterministic():
     ([(64, 576), (128, 64), (64, 27), (10, 512)], 4, 8, 4),
     ([(300, 260), (17, 4100)], 3, 4, 3),
     ([(96, 520)], 16, 8, 2),
-    ([(96, 520), (40, 36), (70, 27), (200, 1100)], 32, 8, 2),     # matrix-core path, clipped ranks, unaligned rows
+    ([(96, 520), (40, 36), (70, 27), (200, 1100), (10, 512)], 32, 8, 2),   # matrix-core path, clipped ranks, unaligned rows
     ([(130, 260)], 20, 4, 3),                                      # rank pad 32 with rank 20
     ([(200, 1100), (70, 27), (96, 520)], 50, 8, 2),                # rank pad 64
 ])
