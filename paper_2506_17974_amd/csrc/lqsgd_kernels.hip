@@ -60,6 +60,9 @@ typedef const float __attribute__((address_space(4)))* const_fp;
 #ifndef LQSGD_BM_U
 #define LQSGD_BM_U 8   // pairs of rows per step of the matrix-core sweep 1 (4: 829 us, 8: 750 us, 16: 833 us at 8192^2 x 16)
 #endif
+#ifndef LQSGD_BQ_LATE      // matrix-core sweep 0, fused mode: fetch the P product's Q slice after the G-hat part
+#define LQSGD_BQ_LATE 1
+#endif
 #ifndef LQSGD_B_U          // rows a wavefront of sweep 1 has in flight
 #define LQSGD_B_U 8
 #endif
@@ -1723,7 +1726,7 @@ __device__ __forceinline__ void mfma_tile(const float* __restrict__ G, float* __
       }
     }
     float bq[NB][32];
-    if constexpr (ADD) {
+    auto load_bq = [&]() __attribute__((always_inline)) {
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
@@ -1736,7 +1739,11 @@ __device__ __forceinline__ void mfma_tile(const float* __restrict__ G, float* __
           else
             bq[nb][kk] = (col < col1 && rk < rs) ? Q[(size_t)col * rs + rk] : 0.0f;
         }
-    }
+    };
+    // In the fused mode the Q slice of the P product is fetched only after the G-hat part, when
+    // the registers of its operands are free again (fetched up front it does not fit the register file).
+    constexpr bool BQ_LATE = ADD && NEEDG && LQSGD_BQ_LATE;
+    if constexpr (ADD && !BQ_LATE) load_bq();
     if constexpr (NEEDG) {
       float qb[2][KH];
 #pragma unroll
@@ -1815,6 +1822,10 @@ __device__ __forceinline__ void mfma_tile(const float* __restrict__ G, float* __
         if constexpr (ADD)
           *reinterpret_cast<float4*>(lds + rr * kLP + c4) = make_float4(m.v[0], m.v[1], m.v[2], m.v[3]);
       }
+    }
+    if constexpr (BQ_LATE) {
+      __builtin_amdgcn_sched_barrier(0);
+      load_bq();
     }
     if constexpr (ADD) {
       wave_lds_fence();
