@@ -1436,7 +1436,7 @@ __device__ __forceinline__ void back_project_mfma_tile_nb(const DevArgs& a, cons
 }
 
 template <int NB>
-__global__ __launch_bounds__(256) void back_project_mfma_kernel(DevArgs a, const Tile* __restrict__ tiles, int ntiles,
+__global__ __launch_bounds__(256, 2) void back_project_mfma_kernel(DevArgs a, const Tile* __restrict__ tiles, int ntiles,
                                                                 const VTile* __restrict__ vtiles, int reverse) {
   if ((int)blockIdx.x >= ntiles) {
     vector_mean_tile(a, vtiles[blockIdx.x - ntiles]);
