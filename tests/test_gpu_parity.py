@@ -328,6 +328,41 @@ def test_resnet18_free_run_matches_oracle_and_is_deterministic():
 
 
 # ---------------------------------------------------------------------------
+# run-to-run determinism of the paths that add partial results across work items
+# (matrix-core sweeps, the one-launch Gram-Schmidt with its slice tables)
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("layers,rank,W", [
+    ([(200, 1100), (10, 512), (64, 27)], 32, 3),      # narrow matrix-core sweep 0, padded operand copies
+    ([(129, 1028), (70, 27)], 16, 2),
+    ([(100, 1100), (70, 200)], 50, 2),                 # rank pad 64
+    ([(20000, 16)], 16, 3),                            # tall factor: Gram-Schmidt in 79 slices, one launch
+])
+def test_three_steps_twice_give_the_same_bits(layers, rank, W):
+    import torch
+    _say("case: determinism", layers, rank, W)
+    rng = np.random.default_rng(11)
+    Q0 = [rng.standard_normal((c, min(rank, r, c))).astype(f32) for r, c in layers]
+    Gs = [pu.to_device(_random_inputs(rng, layers, W)) for _ in range(3)]
+    runs = []
+    for _ in range(2):
+        comp, ml = _make(layers, (), rank, 8, 8, W)
+        for l in ml:
+            comp.set_q(l, Q0[l])
+        ghat = [torch.empty(s, device="cuda") for s in layers]
+        for G in Gs:
+            comp.step(G, ghat)
+        comp.synchronize()
+        runs.append(([g.cpu().numpy() for g in ghat],
+                     [[comp.get_state(l, w) for l in ml] for w in range(W)]))
+        comp.close()
+    (ga, sa), (gb, sb) = runs
+    for l in range(len(layers)):
+        assert np.array_equal(ga[l], gb[l])
+        for w in range(W):
+            assert np.array_equal(sa[w][l][0], sb[w][l][0]) and np.array_equal(sa[w][l][1], sb[w][l][1])
+
+
+# ---------------------------------------------------------------------------
 # deferred residual update (the default) against the eager one: same bits
 # ---------------------------------------------------------------------------
 @pytest.mark.parametrize("layers,rank,bits,W", [
