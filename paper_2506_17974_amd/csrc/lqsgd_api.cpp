@@ -190,13 +190,19 @@ int next_dir(lqsgd_ctx* c) {
 // fewer ranks than the register pad; whoever writes a factor marks its copy stale.
 int refresh_padded(lqsgd_ctx* c, bool need_p, bool need_q) {
   if (!c->plan.padded) return LQSGD_OK;
-  if (need_p && c->ppad_stale) {
+  // While the stream is being captured the flags describe the moment of the capture, not of a later
+  // replay (a host upload may come in between): every copy that is needed is then refreshed, and
+  // the flags are left as they were.
+  hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(c->stream, &cap) != hipSuccess) { (void)hipGetLastError(); cap = hipStreamCaptureStatusNone; }
+  const bool capturing = cap != hipStreamCaptureStatusNone;
+  if (need_p && (c->ppad_stale || capturing)) {
     HIP_TRY(c, launch_pad_factor(c->plan.RP, 0, c->args, c->stream));
-    c->ppad_stale = false;
+    if (!capturing) c->ppad_stale = false;
   }
-  if (need_q && c->qpad_stale) {
+  if (need_q && (c->qpad_stale || capturing)) {
     HIP_TRY(c, launch_pad_factor(c->plan.RP, 1, c->args, c->stream));
-    c->qpad_stale = false;
+    if (!capturing) c->qpad_stale = false;
   }
   return LQSGD_OK;
 }

@@ -305,6 +305,7 @@ def test_bf16_gradients(layers, vectors, rank, bits, W, flags):
 @pytest.mark.parametrize("layers,rank,W", [
     ([(32, 25), (64, 800), (1024, 3136), (10, 1024)], 4, 4),        # the small-CNN set: launch-bound
     ([(2304, 96), (129, 1028)], 16, 2),                             # tall factor: Gram-Schmidt must not take its one-launch form
+    ([(129, 1028), (10, 512)], 16, 2),                              # a clipped rank: the padded operand copies are refreshed in every replay
 ])
 def test_step_recorded_into_a_graph(layers, rank, W):
     """lqsgd_step recorded into a HIP graph on the context's stream: every replay,
