@@ -195,10 +195,12 @@ int lqsgd_step(lqsgd_ctx* ctx, const float* const* grads, float* const* ghat);
  * and lqsgd_step_update enqueue kernels only -- no copies, no memsets, no
  * synchronisation -- and may be recorded into a HIP graph on the context's
  * stream.  Every replay is then one iteration on whatever the recorded buffers
- * hold at that time.  Per-kernel timing must be off while recording.  Calls that
- * change the context's state from the host between replays (lqsgd_set_state,
- * lqsgd_set_factor, lqsgd_set_q) are allowed: a recorded iteration rebuilds
- * whatever it derives from that state. */
+ * hold at that time.  Per-kernel timing must be off while recording.  A
+ * recorded iteration continues from the state the previous one left (with the
+ * residual update still deferred): calls that read or write E or the factors
+ * from the host (lqsgd_get_state with host_e, lqsgd_set_state, lqsgd_set_factor,
+ * lqsgd_set_q) apply that update, so after one of them run an ordinary
+ * iteration and record again before replaying. */
 
 /* The same iteration followed by Algorithm 1's last statement, fused into the
  * pass that would write G-hat: w <- w - eta G-hat (Eq. (2)) for every matrix
