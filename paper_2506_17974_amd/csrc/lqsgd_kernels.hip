@@ -962,13 +962,15 @@ __global__ __launch_bounds__(256) void exchange_kernel(DevArgs a, const XTile* _
   const int bits = phase ? a.bits_q : a.bits_p;
   const int lv = (1 << bits) - 1;
   const int tid = threadIdx.x;
+  // the quantiser tables are requested first and stored to LDS only after the descriptors below
+  // have been requested as well, so that the two chains of dependent loads overlap
+  float thr_v = 0.0f, lev_v = 0.0f;
   if (bits > 0) {
     const float* thr = phase ? a.thrQ : a.thrP;
     const float* lev = phase ? a.levQ : a.levP;
-    if (tid < lv) s_thr[tid] = thr[tid];
-    if (tid <= lv) s_lev[tid] = lev[tid];
+    if (tid < lv) thr_v = thr[tid];
+    if (tid <= lv) lev_v = lev[tid];
   }
-  __syncthreads();
   const XTile tl = tiles[blockIdx.x];
   const LayerDesc& ld = a.layers[tl.layer];
   const int n_el = phase ? ld.nq_el : ld.np_el;
@@ -986,6 +988,22 @@ __global__ __launch_bounds__(256) void exchange_kernel(DevArgs a, const XTile* _
   const size_t sstride = phase ? a.sgnq_stride : a.sgnp_stride;
   const float* scale = phase ? a.scaleQ : a.scaleP;
   const float qscale = phase ? a.qscale_q : a.qscale_p;
+  // this lane's scale and factor values of the first pass over the worker slots, requested before the barrier
+  const bool first_ok = gvalid && slot < a.W;
+  float s_first = 0.0f;
+  float4 lo_first = make_float4(0.0f, 0.0f, 0.0f, 0.0f), hi_first = lo_first;
+  if (first_ok) {
+    if (bits > 0) s_first = scale[(size_t)slot * a.L + tl.layer];
+    if (MODE != kMeanOnly || bits == 0) {
+      lo_first = reinterpret_cast<const float4*>(fac + (size_t)slot * fstride)[0];
+      hi_first = reinterpret_cast<const float4*>(fac + (size_t)slot * fstride)[1];
+    }
+  }
+  if (bits > 0) {
+    if (tid < lv) s_thr[tid] = thr_v;
+    if (tid <= lv) s_lev[tid] = lev_v;
+  }
+  __syncthreads();
 
   float acc = 0.0f;
   for (int wbase = 0; wbase < a.W; wbase += 8) {
@@ -996,8 +1014,8 @@ __global__ __launch_bounds__(256) void exchange_kernel(DevArgs a, const XTile* _
     if (gvalid && w < a.W) {
       float x[kXGroup];
       if (MODE != kMeanOnly || bits == 0) {
-        const float4 lo = reinterpret_cast<const float4*>(fac + (size_t)w * fstride)[0];
-        const float4 hi = reinterpret_cast<const float4*>(fac + (size_t)w * fstride)[1];
+        const float4 lo = wbase ? reinterpret_cast<const float4*>(fac + (size_t)w * fstride)[0] : lo_first;
+        const float4 hi = wbase ? reinterpret_cast<const float4*>(fac + (size_t)w * fstride)[1] : hi_first;
         x[0] = lo.x; x[1] = lo.y; x[2] = lo.z; x[3] = lo.w;
         x[4] = hi.x; x[5] = hi.y; x[6] = hi.z; x[7] = hi.w;
 #pragma unroll
@@ -1008,7 +1026,7 @@ __global__ __launch_bounds__(256) void exchange_kernel(DevArgs a, const XTile* _
 #pragma unroll
         for (int i = 0; i < kXGroup; ++i) val[i] = x[i];
       } else {
-        const float s = scale[(size_t)w * a.L + tl.layer];
+        const float s = wbase ? scale[(size_t)w * a.L + tl.layer] : s_first;
         unsigned long long magbits = 0;
         unsigned sgnbits = 0;
         if (MODE != kMeanOnly) {
