@@ -48,12 +48,6 @@ typedef const float __attribute__((address_space(4)))* const_fp;
 #ifndef LQSGD_NT_M
 #define LQSGD_NT_M 1
 #endif
-#ifndef LQSGD_NT_ST_A      // store of M = G + E in sweep 0
-#define LQSGD_NT_ST_A 0
-#endif
-#ifndef LQSGD_NT_ST_C      // store of E in sweep 2
-#define LQSGD_NT_ST_C 0
-#endif
 #ifndef LQSGD_RT           // rows a wavefront carries through one column pass of sweep 0 (rank <= 8)
 #define LQSGD_RT 8
 #endif
@@ -316,7 +310,7 @@ __device__ __forceinline__ void static_for(F&& f) {
 // RT rows at a time; a lane accumulates RT x r partial dot products over its
 // columns, one butterfly per row group adds them over the lanes.
 // ---------------------------------------------------------------------------
-template <int RP, int VEC, int RT, bool EXACT, bool FULL, bool FUSE, bool GB16>
+template <int RP, int VEC, int RT, bool EXACT, bool FULL, bool FUSE, bool GB16, bool NTS>
 __device__ __forceinline__ void add_project_cols(const char* const (&gr)[RT], char* const (&mr)[RT],
                                                  const float* __restrict__ Q, const float (&pb)[RT * RP], int r, int nr,
                                                  int cbeg, int cend, float (&acc)[RT * RP]) {
@@ -351,7 +345,7 @@ __device__ __forceinline__ void add_project_cols(const char* const (&gr)[RT], ch
         }
         m.v[v] = g[t].v[v] + ev;
       }
-      if (FULL || t < nr) strow<VEC, LQSGD_NT_ST_A != 0>(mr[t], boff, m);
+      if (FULL || t < nr) strow<VEC, NTS>(mr[t], boff, m);
 #pragma unroll
       for (int v = 0; v < VEC; ++v)
 #pragma unroll
@@ -360,7 +354,7 @@ __device__ __forceinline__ void add_project_cols(const char* const (&gr)[RT], ch
   }
 }
 
-template <int RP, int VEC, int RT, bool EXACT, bool FUSE, bool GB16 = false>
+template <int RP, int VEC, int RT, bool EXACT, bool FUSE, bool GB16 = false, bool NTS = false>
 __device__ __forceinline__ void add_project_tile(const float* __restrict__ G, float* __restrict__ M,
                                                  const float* __restrict__ Q, const float* Pb,
                                                  float* __restrict__ Pp, int cols, int r, int row0, int nrows,
@@ -391,9 +385,9 @@ __device__ __forceinline__ void add_project_tile(const float* __restrict__ G, fl
       }
     }
     if (nr == RT)
-      add_project_cols<RP, VEC, RT, EXACT, true, FUSE, GB16>(gr, mr, Q, pb, r, nr, col0 + lane * VEC, col1, acc);
+      add_project_cols<RP, VEC, RT, EXACT, true, FUSE, GB16, NTS>(gr, mr, Q, pb, r, nr, col0 + lane * VEC, col1, acc);
     else
-      add_project_cols<RP, VEC, RT, EXACT, false, FUSE, GB16>(gr, mr, Q, pb, r, nr, col0 + lane * VEC, col1, acc);
+      add_project_cols<RP, VEC, RT, EXACT, false, FUSE, GB16, NTS>(gr, mr, Q, pb, r, nr, col0 + lane * VEC, col1, acc);
     transpose_reduce<N, N, 32>(acc, lane);
     constexpr int NPL = (N >= kWave) ? N / kWave : 1;
 #pragma unroll
@@ -416,7 +410,8 @@ __device__ __forceinline__ void add_project_tile(const float* __restrict__ G, fl
 // FUSE: the residual update of the previous iteration has been deferred; the
 // buffer holds M_{t-1} and this sweep forms E_{t-1} = M_{t-1} - P-bar Q-bar^T on
 // the fly (Q-bar is the warm-start Q this sweep multiplies by anyway).
-template <int RP, bool FUSE, bool GB16>
+// NTS: M is written with non-temporal stores (chosen by the host from the size of the working set).
+template <int RP, bool FUSE, bool GB16, bool NTS>
 __global__ __launch_bounds__(256, LQSGD_A_WAVES) void add_project_kernel(DevArgs a, const Tile* __restrict__ tiles, int ntiles, int reverse) {
   constexpr int RT = (RP <= 8) ? LQSGD_RT : 4;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -437,12 +432,12 @@ __global__ __launch_bounds__(256, LQSGD_A_WAVES) void add_project_kernel(DevArgs
   const int col1 = min(ld.cols, col0 + ld.segw);
   if (ld.vec == 4) {
     if (ld.r == RP)
-      add_project_tile<RP, 4, RT, true, FUSE, GB16>(G, M, Q, Pb, Pp, ld.cols, ld.r, tl.row0, tl.nrows, col0, col1, lane);
+      add_project_tile<RP, 4, RT, true, FUSE, GB16, NTS>(G, M, Q, Pb, Pp, ld.cols, ld.r, tl.row0, tl.nrows, col0, col1, lane);
     else
-      add_project_tile<RP, 4, RT, false, FUSE, GB16>(G, M, Q, Pb, Pp, ld.cols, ld.r, tl.row0, tl.nrows, col0, col1, lane);
+      add_project_tile<RP, 4, RT, false, FUSE, GB16, NTS>(G, M, Q, Pb, Pp, ld.cols, ld.r, tl.row0, tl.nrows, col0, col1, lane);
   } else {
     // rows that are not 16-byte aligned (cols % 4 != 0): tiny layers, one generic path
-    add_project_tile<RP, 1, RT, false, FUSE, GB16>(G, M, Q, Pb, Pp, ld.cols, ld.r, tl.row0, tl.nrows, col0, col1, lane);
+    add_project_tile<RP, 1, RT, false, FUSE, GB16, NTS>(G, M, Q, Pb, Pp, ld.cols, ld.r, tl.row0, tl.nrows, col0, col1, lane);
   }
 }
 
@@ -962,15 +957,13 @@ __global__ __launch_bounds__(256) void exchange_kernel(DevArgs a, const XTile* _
   const int bits = phase ? a.bits_q : a.bits_p;
   const int lv = (1 << bits) - 1;
   const int tid = threadIdx.x;
-  // the quantiser tables are requested first and stored to LDS only after the descriptors below
-  // have been requested as well, so that the two chains of dependent loads overlap
-  float thr_v = 0.0f, lev_v = 0.0f;
   if (bits > 0) {
     const float* thr = phase ? a.thrQ : a.thrP;
     const float* lev = phase ? a.levQ : a.levP;
-    if (tid < lv) thr_v = thr[tid];
-    if (tid <= lv) lev_v = lev[tid];
+    if (tid < lv) s_thr[tid] = thr[tid];
+    if (tid <= lv) s_lev[tid] = lev[tid];
   }
+  __syncthreads();
   const XTile tl = tiles[blockIdx.x];
   const LayerDesc& ld = a.layers[tl.layer];
   const int n_el = phase ? ld.nq_el : ld.np_el;
@@ -988,22 +981,6 @@ __global__ __launch_bounds__(256) void exchange_kernel(DevArgs a, const XTile* _
   const size_t sstride = phase ? a.sgnq_stride : a.sgnp_stride;
   const float* scale = phase ? a.scaleQ : a.scaleP;
   const float qscale = phase ? a.qscale_q : a.qscale_p;
-  // this lane's scale and factor values of the first pass over the worker slots, requested before the barrier
-  const bool first_ok = gvalid && slot < a.W;
-  float s_first = 0.0f;
-  float4 lo_first = make_float4(0.0f, 0.0f, 0.0f, 0.0f), hi_first = lo_first;
-  if (first_ok) {
-    if (bits > 0) s_first = scale[(size_t)slot * a.L + tl.layer];
-    if (MODE != kMeanOnly || bits == 0) {
-      lo_first = reinterpret_cast<const float4*>(fac + (size_t)slot * fstride)[0];
-      hi_first = reinterpret_cast<const float4*>(fac + (size_t)slot * fstride)[1];
-    }
-  }
-  if (bits > 0) {
-    if (tid < lv) s_thr[tid] = thr_v;
-    if (tid <= lv) s_lev[tid] = lev_v;
-  }
-  __syncthreads();
 
   float acc = 0.0f;
   for (int wbase = 0; wbase < a.W; wbase += 8) {
@@ -1014,8 +991,8 @@ __global__ __launch_bounds__(256) void exchange_kernel(DevArgs a, const XTile* _
     if (gvalid && w < a.W) {
       float x[kXGroup];
       if (MODE != kMeanOnly || bits == 0) {
-        const float4 lo = wbase ? reinterpret_cast<const float4*>(fac + (size_t)w * fstride)[0] : lo_first;
-        const float4 hi = wbase ? reinterpret_cast<const float4*>(fac + (size_t)w * fstride)[1] : hi_first;
+        const float4 lo = reinterpret_cast<const float4*>(fac + (size_t)w * fstride)[0];
+        const float4 hi = reinterpret_cast<const float4*>(fac + (size_t)w * fstride)[1];
         x[0] = lo.x; x[1] = lo.y; x[2] = lo.z; x[3] = lo.w;
         x[4] = hi.x; x[5] = hi.y; x[6] = hi.z; x[7] = hi.w;
 #pragma unroll
@@ -1026,7 +1003,7 @@ __global__ __launch_bounds__(256) void exchange_kernel(DevArgs a, const XTile* _
 #pragma unroll
         for (int i = 0; i < kXGroup; ++i) val[i] = x[i];
       } else {
-        const float s = wbase ? scale[(size_t)w * a.L + tl.layer] : s_first;
+        const float s = scale[(size_t)w * a.L + tl.layer];
         unsigned long long magbits = 0;
         unsigned sgnbits = 0;
         if (MODE != kMeanOnly) {
@@ -1585,7 +1562,7 @@ __device__ __forceinline__ void residual_rows(float* __restrict__ M, const float
           if constexpr (MODE != kGhatOnly) e.v[v] = m[u].v[v] - s;
         }
         if constexpr (MODE != kGhatOnly)
-          strow<VEC, LQSGD_NT_ST_C != 0>(reinterpret_cast<char*>(M + (size_t)(i + u) * cols), boff, e);
+          strow<VEC, false>(reinterpret_cast<char*>(M + (size_t)(i + u) * cols), boff, e);
         if constexpr (MODE == kGhatOnly) {
           if (update) {
 #pragma unroll
@@ -1675,7 +1652,7 @@ __device__ __forceinline__ void wave_lds_fence() {
   __builtin_amdgcn_wave_barrier();
 }
 
-template <int RP, int MODE, bool EXACT, bool GB16>
+template <int RP, int MODE, bool EXACT, bool GB16, bool NTS>
 __device__ __forceinline__ void mfma_tile(const float* __restrict__ G, float* __restrict__ M,
                                           const float* Q, const float* Pb, float* __restrict__ Pp,
                                           float* __restrict__ ghat_out, int cols, int r, int row0, int nrows,
@@ -1834,9 +1811,9 @@ __device__ __forceinline__ void mfma_tile(const float* __restrict__ G, float* __
 #pragma unroll
         for (int v = 0; v < 4; ++v) m.v[v] = ADD ? g[i].v[v] + e[i].v[v] : e[i].v[v];
         if constexpr (FULL)
-          strow<4, LQSGD_NT_ST_A != 0>(reinterpret_cast<char*>(M + (size_t)(row0 + 4 * i) * cols + c), lo, m);
+          strow<4, NTS>(reinterpret_cast<char*>(M + (size_t)(row0 + 4 * i) * cols + c), lo, m);
         else if (colok && rr < nrows)
-          strow<4, LQSGD_NT_ST_A != 0>(reinterpret_cast<char*>(M + (size_t)(row0 + rr) * cols), (unsigned)cl * 4u, m);
+          strow<4, NTS>(reinterpret_cast<char*>(M + (size_t)(row0 + rr) * cols), (unsigned)cl * 4u, m);
         if constexpr (ADD)
           *reinterpret_cast<float4*>(lds + rr * kLP + c4) = make_float4(m.v[0], m.v[1], m.v[2], m.v[3]);
       }
@@ -1908,7 +1885,7 @@ __device__ __forceinline__ void mfma_tile(const float* __restrict__ G, float* __
 // ---------------------------------------------------------------------------
 constexpr int kLP32 = 36;   // LDS pitch (floats) of a 32 x 32 tile: 16-byte aligned rows
 
-template <int RP, int MODE, bool EXACT, bool GB16>
+template <int RP, int MODE, bool EXACT, bool GB16, bool NTS>
 __device__ __forceinline__ void mfma_tile32(const float* __restrict__ G, float* __restrict__ M,
                                             const float* Q, const float* Pb, float* __restrict__ Pp,
                                             int cols, int r, int row0, int nrows, int col0, int col1,
@@ -2008,7 +1985,7 @@ __device__ __forceinline__ void mfma_tile32(const float* __restrict__ G, float* 
 #pragma unroll
       for (int v = 0; v < 4; ++v) m.v[v] = g[i].v[v] + e[i].v[v];
       if (FULL || (colok && rr < nrows))
-        strow<4, LQSGD_NT_ST_A != 0>(reinterpret_cast<char*>(M + (size_t)(row0 + rr) * cols), (unsigned)cl * 4u, m);
+        strow<4, NTS>(reinterpret_cast<char*>(M + (size_t)(row0 + rr) * cols), (unsigned)cl * 4u, m);
       *reinterpret_cast<float4*>(lds + rr * kLP32 + c4) = make_float4(m.v[0], m.v[1], m.v[2], m.v[3]);
     }
     // the Q slice of the P product is fetched only now: the registers of the G-hat operands are free again
@@ -2126,7 +2103,7 @@ __device__ __forceinline__ void mfma_tile32(const float* __restrict__ G, float* 
           }
 #pragma unroll
           for (int v = 0; v < 4; ++v) m.v[v] = gv.v[v] + e[i].v[v];
-          strow<4, LQSGD_NT_ST_A != 0>(reinterpret_cast<char*>(M + (size_t)(row0 + 8 * i) * cols + c), goff, m);
+          strow<4, NTS>(reinterpret_cast<char*>(M + (size_t)(row0 + 8 * i) * cols + c), goff, m);
           *reinterpret_cast<float4*>(lds + rr * kLP32 + c4) = make_float4(m.v[0], m.v[1], m.v[2], m.v[3]);
         }
         wave_lds_fence();
@@ -2261,7 +2238,7 @@ __device__ __forceinline__ void mfma_mode_vector_fallback(const DevArgs& a, cons
 
 // Wavefronts per SIMD the register allocation aims for: two at rank pad 16 (2.65 -> 2.47 ms on
 // 8192^2 x 16 workers), one at rank pad 32, where two would spill (3.0 -> 4.6 ms).
-template <int RP, int MODE, bool GB16 = false>
+template <int RP, int MODE, bool GB16 = false, bool NTS = false>
 __global__ __launch_bounds__(256, RP <= 16 ? 2 : 1) void mfma_sweep_kernel(DevArgs a, const Tile* __restrict__ tiles, int ntiles, int reverse) {
   __shared__ __attribute__((aligned(16))) float lds_all[4][32 * kLP];
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -2288,17 +2265,17 @@ __global__ __launch_bounds__(256, RP <= 16 ? 2 : 1) void mfma_sweep_kernel(DevAr
     return;
   }
   if (a.Qpad)   // operands with rows of RP ranks, zero beyond the layer's rank
-    mfma_tile<RP, MODE, true, GB16>(G, M, a.Qpad + ld.qpad_off, a.Ppad + ld.ppad_off, Pp, ghat_out, ld.cols, ld.r, tl.row0,
+    mfma_tile<RP, MODE, true, GB16, NTS>(G, M, a.Qpad + ld.qpad_off, a.Ppad + ld.ppad_off, Pp, ghat_out, ld.cols, ld.r, tl.row0,
                               tl.nrows, col0, col1, lane, wave, lds_all, a.update, a.eta);
   else if (ld.r == RP)
-    mfma_tile<RP, MODE, true, GB16>(G, M, a.Qbar + ld.q_off, a.Pbar + ld.p_off, Pp, ghat_out, ld.cols, ld.r, tl.row0,
+    mfma_tile<RP, MODE, true, GB16, NTS>(G, M, a.Qbar + ld.q_off, a.Pbar + ld.p_off, Pp, ghat_out, ld.cols, ld.r, tl.row0,
                               tl.nrows, col0, col1, lane, wave, lds_all, a.update, a.eta);
   else
-    mfma_tile<RP, MODE, false, GB16>(G, M, a.Qbar + ld.q_off, a.Pbar + ld.p_off, Pp, ghat_out, ld.cols, ld.r, tl.row0,
+    mfma_tile<RP, MODE, false, GB16, NTS>(G, M, a.Qbar + ld.q_off, a.Pbar + ld.p_off, Pp, ghat_out, ld.cols, ld.r, tl.row0,
                                tl.nrows, col0, col1, lane, wave, lds_all, a.update, a.eta);
 }
 
-template <int RP, int MODE, bool GB16>
+template <int RP, int MODE, bool GB16, bool NTS>
 __global__ __launch_bounds__(512, 2) void mfma_sweep32_kernel(DevArgs a, const Tile* __restrict__ tiles, int ntiles, int reverse) {
   __shared__ __attribute__((aligned(16))) float lds_all[8][32 * kLP32];
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -2322,13 +2299,13 @@ __global__ __launch_bounds__(512, 2) void mfma_sweep32_kernel(DevArgs a, const T
     return;
   }
   if (a.Qpad)
-    mfma_tile32<RP, MODE, true, GB16>(G, M, a.Qpad + ld.qpad_off, a.Ppad + ld.ppad_off, Pp, ld.cols, ld.r, tl.row0, tl.nrows,
+    mfma_tile32<RP, MODE, true, GB16, NTS>(G, M, a.Qpad + ld.qpad_off, a.Ppad + ld.ppad_off, Pp, ld.cols, ld.r, tl.row0, tl.nrows,
                                       col0, col1, lane, wave, lds_all);
   else if (ld.r == RP)
-    mfma_tile32<RP, MODE, true, GB16>(G, M, a.Qbar + ld.q_off, a.Pbar + ld.p_off, Pp, ld.cols, ld.r, tl.row0, tl.nrows,
+    mfma_tile32<RP, MODE, true, GB16, NTS>(G, M, a.Qbar + ld.q_off, a.Pbar + ld.p_off, Pp, ld.cols, ld.r, tl.row0, tl.nrows,
                                       col0, col1, lane, wave, lds_all);
   else
-    mfma_tile32<RP, MODE, false, GB16>(G, M, a.Qbar + ld.q_off, a.Pbar + ld.p_off, Pp, ld.cols, ld.r, tl.row0, tl.nrows,
+    mfma_tile32<RP, MODE, false, GB16, NTS>(G, M, a.Qbar + ld.q_off, a.Pbar + ld.p_off, Pp, ld.cols, ld.r, tl.row0, tl.nrows,
                                        col0, col1, lane, wave, lds_all);
 }
 
@@ -2372,17 +2349,17 @@ hipError_t launch_add_project(int rp, const DevArgs& a, const Tile* tiles, int n
                               hipStream_t s) {
   if (ntiles <= 0) return hipSuccess;
   const dim3 grid((ntiles + 3) / 4), block(256);
+#define LQSGD_LAUNCH_A(FUSE, GB) \
+  if (a.nt_store) { LQSGD_RP_SWITCH(rp, (add_project_kernel<RP, FUSE, GB, true><<<grid, block, 0, s>>>(a, tiles, ntiles, reverse))); } \
+  else { LQSGD_RP_SWITCH(rp, (add_project_kernel<RP, FUSE, GB, false><<<grid, block, 0, s>>>(a, tiles, ntiles, reverse))); }
   if (a.g_bf16) {
-    if (fuse_residual) {
-      LQSGD_RP_SWITCH(rp, (add_project_kernel<RP, true, true><<<grid, block, 0, s>>>(a, tiles, ntiles, reverse)));
-    } else {
-      LQSGD_RP_SWITCH(rp, (add_project_kernel<RP, false, true><<<grid, block, 0, s>>>(a, tiles, ntiles, reverse)));
-    }
+    if (fuse_residual) { LQSGD_LAUNCH_A(true, true) } else { LQSGD_LAUNCH_A(false, true) }
   } else if (fuse_residual) {
-    LQSGD_RP_SWITCH(rp, (add_project_kernel<RP, true, false><<<grid, block, 0, s>>>(a, tiles, ntiles, reverse)));
+    LQSGD_LAUNCH_A(true, false)
   } else {
-    LQSGD_RP_SWITCH(rp, (add_project_kernel<RP, false, false><<<grid, block, 0, s>>>(a, tiles, ntiles, reverse)));
+    LQSGD_LAUNCH_A(false, false)
   }
+#undef LQSGD_LAUNCH_A
   return hipGetLastError();
 }
 
@@ -2553,13 +2530,17 @@ hipError_t launch_mfma_sweep_rp(int mode, int full_rank, const DevArgs& a, const
       // not the residual update is deferred
       if constexpr (RP == 32) {
         if (narrow32() && full_rank) {
-          if (a.g_bf16) mfma_sweep32_kernel<32, kMAdd, true><<<grid, dim3(512), 0, s>>>(a, tiles, ntiles, reverse);
-          else mfma_sweep32_kernel<32, kMAdd, false><<<grid, dim3(512), 0, s>>>(a, tiles, ntiles, reverse);
+          if (a.g_bf16) { if (a.nt_store) mfma_sweep32_kernel<32, kMAdd, true, true><<<grid, dim3(512), 0, s>>>(a, tiles, ntiles, reverse);
+                          else mfma_sweep32_kernel<32, kMAdd, true, false><<<grid, dim3(512), 0, s>>>(a, tiles, ntiles, reverse); }
+          else { if (a.nt_store) mfma_sweep32_kernel<32, kMAdd, false, true><<<grid, dim3(512), 0, s>>>(a, tiles, ntiles, reverse);
+                 else mfma_sweep32_kernel<32, kMAdd, false, false><<<grid, dim3(512), 0, s>>>(a, tiles, ntiles, reverse); }
           break;
         }
       }
-      if (a.g_bf16) mfma_sweep_kernel<RP, kMAdd, true><<<grid, block, 0, s>>>(a, tiles, ntiles, reverse);
-      else mfma_sweep_kernel<RP, kMAdd><<<grid, block, 0, s>>>(a, tiles, ntiles, reverse);
+      if (a.g_bf16) { if (a.nt_store) mfma_sweep_kernel<RP, kMAdd, true, true><<<grid, block, 0, s>>>(a, tiles, ntiles, reverse);
+                      else mfma_sweep_kernel<RP, kMAdd, true, false><<<grid, block, 0, s>>>(a, tiles, ntiles, reverse); }
+      else { if (a.nt_store) mfma_sweep_kernel<RP, kMAdd, false, true><<<grid, block, 0, s>>>(a, tiles, ntiles, reverse);
+             else mfma_sweep_kernel<RP, kMAdd, false, false><<<grid, block, 0, s>>>(a, tiles, ntiles, reverse); }
       break;
     case kMAddFused:
       // the narrow form pays where the fused mode would otherwise run one wavefront per SIMD and every
@@ -2567,13 +2548,17 @@ hipError_t launch_mfma_sweep_rp(int mode, int full_rank, const DevArgs& a, const
       // 3.11 -> 3.22 ms, so ranks below the pad stay with the 32 x 64 form)
       if constexpr (RP == 32) {
         if (narrow32() && full_rank) {
-          if (a.g_bf16) mfma_sweep32_kernel<32, kMAddFused, true><<<grid, dim3(512), 0, s>>>(a, tiles, ntiles, reverse);
-          else mfma_sweep32_kernel<32, kMAddFused, false><<<grid, dim3(512), 0, s>>>(a, tiles, ntiles, reverse);
+          if (a.g_bf16) { if (a.nt_store) mfma_sweep32_kernel<32, kMAddFused, true, true><<<grid, dim3(512), 0, s>>>(a, tiles, ntiles, reverse);
+                          else mfma_sweep32_kernel<32, kMAddFused, true, false><<<grid, dim3(512), 0, s>>>(a, tiles, ntiles, reverse); }
+          else { if (a.nt_store) mfma_sweep32_kernel<32, kMAddFused, false, true><<<grid, dim3(512), 0, s>>>(a, tiles, ntiles, reverse);
+                 else mfma_sweep32_kernel<32, kMAddFused, false, false><<<grid, dim3(512), 0, s>>>(a, tiles, ntiles, reverse); }
           break;
         }
       }
-      if (a.g_bf16) mfma_sweep_kernel<RP, kMAddFused, true><<<grid, block, 0, s>>>(a, tiles, ntiles, reverse);
-      else mfma_sweep_kernel<RP, kMAddFused><<<grid, block, 0, s>>>(a, tiles, ntiles, reverse);
+      if (a.g_bf16) { if (a.nt_store) mfma_sweep_kernel<RP, kMAddFused, true, true><<<grid, block, 0, s>>>(a, tiles, ntiles, reverse);
+                      else mfma_sweep_kernel<RP, kMAddFused, true, false><<<grid, block, 0, s>>>(a, tiles, ntiles, reverse); }
+      else { if (a.nt_store) mfma_sweep_kernel<RP, kMAddFused, false, true><<<grid, block, 0, s>>>(a, tiles, ntiles, reverse);
+             else mfma_sweep_kernel<RP, kMAddFused, false, false><<<grid, block, 0, s>>>(a, tiles, ntiles, reverse); }
       break;
     case kMResidual: mfma_sweep_kernel<RP, kMResidual><<<grid, block, 0, s>>>(a, tiles, ntiles, reverse); break;
     case kMResidualGhat: mfma_sweep_kernel<RP, kMResidualGhat><<<grid, block, 0, s>>>(a, tiles, ntiles, reverse); break;
