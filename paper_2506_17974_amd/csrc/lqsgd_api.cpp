@@ -425,11 +425,13 @@ int lqsgd_create(const lqsgd_config* cfg, const lqsgd_layer* layers, int32_t n_l
   a.alpha = p.cfg.alpha;
   a.agg_first = p.agg_first ? 1 : 0; a.orth_shared = 0; a.update = 0; a.eta = 0.0f;
   a.g_bf16 = (cfg->flags & LQSGD_FLAG_BF16_GRADIENTS) ? 1 : 0;
-  // The residual / M slabs are written once and read once per sweep.  While they are about the
-  // size of the memory-side cache (256 MB) plain stores are faster (ResNet-18 set, 357 MB: sweep 0
-  // 178 us against 195 us); far beyond it the dirty lines they leave there are written back
-  // underneath the following reads, and non-temporal stores win (8192^2 x 16, 4.3 GB: sweep 0
-  // 2.27 -> 2.04 ms).  Measured crossover: 0.55 - 0.7 GB.  LQSGD_NT_STORE=1 / 2 forces on / off.
+  // The residual / M slabs are read and written once per sweep.  While they are about the size of
+  // the memory-side cache (256 MB), plain loads and stores in sweep 0 are faster (ResNet-18 set,
+  // 357 MB: a step takes 276 us; 284 us with non-temporal loads of E, 295 us with non-temporal
+  // stores as well).  Far beyond it, the dirty lines that plain stores leave in that cache are
+  // written back underneath the following reads, and streaming both ways wins (8192^2 x 16,
+  // 4.3 GB: sweep 0 2.27 -> 2.04 - 2.14 ms).  Measured crossover: 0.55 - 0.7 GB.
+  // LQSGD_NT_STORE=1 / 2 forces streaming on / off.
   {
     const int64_t slab_bytes = 4 * (int64_t)p.W * p.m_stride;
     a.nt_store = slab_bytes >= ((int64_t)640 << 20) ? 1 : 0;

@@ -40,7 +40,7 @@ struct DevArgs {
   int32_t orth_shared;         // the Gram-Schmidt kernels run once per layer, in place on the plane at Ppart + p_off
   int32_t g_bf16;              // the gradient tensors hold bfloat16 values (G-hat / parameters stay fp32)
   int32_t update;              // G-hat outputs are parameters to update: w <- w - eta G-hat
-  int32_t nt_store;            // sweep 0 writes M with non-temporal stores (the launchers pick the kernels built that way)
+  int32_t nt_store;            // sweep 0 streams the residual slabs: non-temporal loads of E and stores of M (the launchers pick the kernels built that way)
   float eta;
 };
 

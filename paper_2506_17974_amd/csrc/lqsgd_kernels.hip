@@ -42,7 +42,7 @@ typedef const float __attribute__((address_space(4)))* const_fp;
 #ifndef LQSGD_NT_G
 #define LQSGD_NT_G 1
 #endif
-#ifndef LQSGD_NT_E
+#ifndef LQSGD_NT_E          // residual sweeps (eager schedule); sweep 0 follows its store policy, see add_project_kernel
 #define LQSGD_NT_E 1
 #endif
 #ifndef LQSGD_NT_M
@@ -323,7 +323,7 @@ __device__ __forceinline__ void add_project_cols(const char* const (&gr)[RT], ch
     for (int t = 0; t < RT; ++t) {
       if (FULL || t < nr) {
         g[t] = ldgrad<VEC, LQSGD_NT_G != 0, GB16>(gr[t], boff);
-        e[t] = ldrow<VEC, LQSGD_NT_E != 0>(mr[t], boff);
+        e[t] = ldrow<VEC, NTS>(mr[t], boff);
       } else {
 #pragma unroll
         for (int v = 0; v < VEC; ++v) { g[t].v[v] = 0.0f; e[t].v[v] = 0.0f; }
@@ -410,7 +410,8 @@ __device__ __forceinline__ void add_project_tile(const float* __restrict__ G, fl
 // FUSE: the residual update of the previous iteration has been deferred; the
 // buffer holds M_{t-1} and this sweep forms E_{t-1} = M_{t-1} - P-bar Q-bar^T on
 // the fly (Q-bar is the warm-start Q this sweep multiplies by anyway).
-// NTS: M is written with non-temporal stores (chosen by the host from the size of the working set).
+// NTS: the residual slabs are streamed -- E (or last iteration's M) is read with the non-temporal
+// hint and M is written with non-temporal stores; chosen by the host from the size of the working set.
 template <int RP, bool FUSE, bool GB16, bool NTS>
 __global__ __launch_bounds__(256, LQSGD_A_WAVES) void add_project_kernel(DevArgs a, const Tile* __restrict__ tiles, int ntiles, int reverse) {
   constexpr int RT = (RP <= 8) ? LQSGD_RT : 4;
@@ -1717,7 +1718,7 @@ __device__ __forceinline__ void mfma_tile(const float* __restrict__ G, float* __
       for (int v = 0; v < 4; ++v) { g[i].v[v] = 0.0f; e[i].v[v] = 0.0f; }
       if (ok) {
         if constexpr (ADD) g[i] = ldgrad<4, LQSGD_NT_G != 0, GB16>(grad_row<GB16>(G, off), bo);
-        if constexpr (HASM) e[i] = ldrow<4, LQSGD_NT_E != 0>(reinterpret_cast<const char*>(M + off), bo);
+        if constexpr (HASM) e[i] = ldrow<4, (ADD ? NTS : LQSGD_NT_E != 0)>(reinterpret_cast<const char*>(M + off), bo);
       }
     }
     float bq[NB][32];
@@ -1935,7 +1936,7 @@ __device__ __forceinline__ void mfma_tile32(const float* __restrict__ G, float* 
       for (int v = 0; v < 4; ++v) { g[i].v[v] = 0.0f; e[i].v[v] = 0.0f; }
       if (ok) {
         g[i] = ldgrad<4, LQSGD_NT_G != 0, GB16>(grad_row<GB16>(G, off), (unsigned)cl * 4u);
-        e[i] = ldrow<4, LQSGD_NT_E != 0>(reinterpret_cast<const char*>(M + off), (unsigned)cl * 4u);
+        e[i] = ldrow<4, NTS>(reinterpret_cast<const char*>(M + off), (unsigned)cl * 4u);
       }
     }
   };
@@ -2049,7 +2050,7 @@ __device__ __forceinline__ void mfma_tile32(const float* __restrict__ G, float* 
           } else {
             gg[i] = ldgrad<4, LQSGD_NT_G != 0, GB16>(grad_row<GB16>(G, off), goff);
           }
-          ee[i] = ldrow<4, LQSGD_NT_E != 0>(reinterpret_cast<const char*>(M + off), goff);
+          ee[i] = ldrow<4, NTS>(reinterpret_cast<const char*>(M + off), goff);
         }
       };
       auto fetch_qb = [&](const int cb) {
