@@ -127,7 +127,7 @@ int Plan::build(const lqsgd_config* c, const lqsgd_layer* ls, int32_t n_layers) 
   // work lists stay small.
   const int64_t total = matrix_elements * W;
   const int64_t tgtA = env_i64("LQSGD_TILE_A", std::min<int64_t>(131072, std::max<int64_t>(2048, total / 49152)));
-  const int64_t tgtB = env_i64("LQSGD_TILE_B", std::min<int64_t>(131072, std::max<int64_t>(8192, total / 2730)));
+  const int64_t tgtB = env_i64("LQSGD_TILE_B", std::min<int64_t>(524288, std::max<int64_t>(8192, total / 2730)));
   // the G-hat-only pass covers one worker's worth of elements: smaller items keep its grid wide
   const int64_t tgtG = env_i64("LQSGD_TILE_G", std::min<int64_t>(tgtB, std::max<int64_t>(4096, matrix_elements / 2730)));
   // column segments: at most 1024 columns (2048 at rank pad 32, where fewer, longer segments save
@@ -153,8 +153,11 @@ int Plan::build(const lqsgd_config* c, const lqsgd_layer* ls, int32_t n_layers) 
 
     // sweeps 1 / 2 on the vector units: row blocks of rbb_v rows
     int64_t rbb = std::max<int64_t>(4, round_up(std::max<int64_t>(1, tgtB / cw), 4));
-    const int32_t rbb_v = (int32_t)std::min<int64_t>(rbb, round_up(d.rows, 4));
-    const int32_t nrb_v = (d.rows + rbb_v - 1) / rbb_v;
+    int32_t rbb_v = (int32_t)std::min<int64_t>(rbb, round_up(d.rows, 4));
+    int32_t nrb_v = (d.rows + rbb_v - 1) / rbb_v;
+    // equal blocks: 8192 rows in blocks of 1536 would end in a block of 512
+    rbb_v = (int32_t)std::min<int64_t>(rbb_v, round_up((d.rows + nrb_v - 1) / nrb_v, 4));
+    nrb_v = (d.rows + rbb_v - 1) / rbb_v;
     // the partial planes of Q belong to whichever kernel runs sweep 1
     if (mfma) {
       const int64_t rbm = env_i64("LQSGD_TILE_BM", std::min<int64_t>(2048, std::max<int64_t>(256, total / (49152 * 16))));
