@@ -297,6 +297,7 @@ __device__ __forceinline__ float wave_max(float x) {
 }
 
 constexpr int log2c(int n) { return n <= 1 ? 0 : 1 + log2c(n / 2); }
+constexpr int pow2ceil(int n) { return n <= 1 ? 1 : 2 * pow2ceil((n + 1) / 2); }
 
 // f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>), in order.
 template <int N, int I = 0, typename F>
@@ -581,33 +582,36 @@ __global__ __launch_bounds__(BS) void orth_reg_kernel(DevArgs a) {
   if constexpr (RP >= 32) {
     static_for<RP>([&](auto jc) __attribute__((always_inline)) {
       constexpr int j = decltype(jc)::value;
+      // only the products with columns j .. RP - 1 are needed: they lie in the last N columns,
+      // N the next power of two (the width the butterfly below needs)
+      constexpr int N = pow2ceil(RP - j), K0 = RP - N, LGN = log2c(N);
       if (j < r) {
-        float s[RP];
-  #pragma unroll
-        for (int k = 0; k < RP; ++k) s[k] = 0.0f;
-  #pragma unroll
+        float s[N];
+#pragma unroll
+        for (int k = 0; k < N; ++k) s[k] = 0.0f;
+#pragma unroll
         for (int i = 0; i < RPT; ++i)
-  #pragma unroll
-          for (int k = 0; k < RP; ++k) s[k] = fmaf(v[i][j], v[i][k], s[k]);
-        transpose_reduce<RP, RP, 32>(s, lane);
+#pragma unroll
+          for (int k = 0; k < N; ++k) s[k] = fmaf(v[i][j], v[i][K0 + k], s[k]);
+        transpose_reduce<N, N, 32>(s, lane);
         const int b = j & 1;
-        if ((lane & (kWave / RP - 1)) == 0) red[b][wave][lane >> (6 - LG)] = s[0];
+        if ((lane & (kWave / N - 1)) == 0) red[b][wave][K0 + (lane >> (6 - LGN))] = s[0];
         __syncthreads();
-  #pragma unroll
-        for (int k = 0; k < RP; ++k) {
+#pragma unroll
+        for (int k = 0; k < N; ++k) {
           float t = 0.0f;
-  #pragma unroll
-          for (int wv = 0; wv < NW; ++wv) t += red[b][wv][k];
+#pragma unroll
+          for (int wv = 0; wv < NW; ++wv) t += red[b][wv][K0 + k];
           s[k] = t;
         }
-        const float nrm2 = s[j];
+        const float nrm2 = s[j - K0];
         const float inv = (nrm2 > FLT_MIN) ? 1.0f / sqrtf(nrm2) : 0.0f;
-  #pragma unroll
+#pragma unroll
         for (int i = 0; i < RPT; ++i) {
           const float qv = v[i][j] * inv;
           v[i][j] = qv;
-  #pragma unroll
-          for (int k = j + 1; k < RP; ++k) v[i][k] = fmaf(-(s[k] * inv), qv, v[i][k]);
+#pragma unroll
+          for (int k = j + 1; k < RP; ++k) v[i][k] = fmaf(-(s[k - K0] * inv), qv, v[i][k]);
         }
       }
     });
