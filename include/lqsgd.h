@@ -233,6 +233,19 @@ int lqsgd_set_packet(lqsgd_ctx* ctx, int32_t phase, int32_t layer, int32_t worke
 int lqsgd_get_packet_raw(lqsgd_ctx* ctx, int32_t phase, int32_t layer, int32_t worker,
                          uint8_t* mag_plane, int64_t* mag_len, uint8_t* sign_plane,
                          int64_t* sign_len);
+/* Where that packet lies: device pointers to its magnitude plane, its sign
+ * plane and its scale (one float), with the planes' byte counts, so that a
+ * caller can hand a worker's packet to a collective, or have one written into a
+ * worker's slot, without a trip through host memory -- the exchange of
+ * Algorithm 1's "All-Reduce" statements (Section 3.1), which this one-GPU
+ * build replaces by the on-device mean.  The memory belongs to the context and
+ * stays valid until lqsgd_destroy; it is written by lqsgd_compress / lqsgd_step
+ * and read by lqsgd_decompress, in stream order on the context's stream.  Any
+ * output pointer may be NULL.  Does not synchronise.  bits == 0: EUNSUPPORTED
+ * (the packet is then the fp32 factor, see lqsgd_get_factor). */
+int lqsgd_packet_device(lqsgd_ctx* ctx, int32_t phase, int32_t layer, int32_t worker,
+                        uint8_t** mag_plane, int64_t* mag_len, uint8_t** sign_plane,
+                        int64_t* sign_len, float** scale);
 
 /* Copies one of the LQSGD_FACTOR_* tensors to host memory.  `worker` is
  * ignored for shared tensors.  Synchronises. */

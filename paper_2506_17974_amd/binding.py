@@ -27,7 +27,7 @@ MAX_RANK, MAX_WORKERS = 64, 64
 SYMBOLS = [
     "lqsgd_create", "lqsgd_destroy", "lqsgd_synchronize", "lqsgd_last_error", "lqsgd_set_q",
     "lqsgd_get_state", "lqsgd_set_state", "lqsgd_compress", "lqsgd_decompress", "lqsgd_step", "lqsgd_step_update",
-    "lqsgd_get_packet", "lqsgd_set_packet", "lqsgd_get_packet_raw", "lqsgd_get_factor",
+    "lqsgd_get_packet", "lqsgd_set_packet", "lqsgd_get_packet_raw", "lqsgd_packet_device", "lqsgd_get_factor",
     "lqsgd_set_factor", "lqsgd_wire_bytes", "lqsgd_plan_query", "lqsgd_plan_tiles",
     "lqsgd_timing_enable", "lqsgd_timing_read", "lqsgd_kernel_name",
 ]
@@ -85,6 +85,8 @@ def lib():
     L.lqsgd_get_packet.argtypes = [vp, i32, i32, i32, u8p, u8p, fp]
     L.lqsgd_set_packet.argtypes = [vp, i32, i32, i32, u8p, u8p, C.c_float]
     L.lqsgd_get_packet_raw.argtypes = [vp, i32, i32, i32, u8p, C.POINTER(i64), u8p, C.POINTER(i64)]
+    L.lqsgd_packet_device.argtypes = [vp, i32, i32, i32, C.POINTER(C.c_void_p), C.POINTER(i64), C.POINTER(C.c_void_p),
+                                      C.POINTER(i64), C.POINTER(C.c_void_p)]
     L.lqsgd_get_factor.argtypes = [vp, i32, i32, i32, fp]
     L.lqsgd_set_factor.argtypes = [vp, i32, i32, fp]
     L.lqsgd_wire_bytes.argtypes = [vp]
@@ -282,6 +284,14 @@ class Compressor:
         s = np.ascontiguousarray(s, np.uint8).ravel()
         assert k.size == self._factor_len(phase, layer) == s.size
         self._check(lib().lqsgd_set_packet(self._h, phase, layer, worker, _u8p(k), _u8p(s), float(scale)))
+
+    def packet_device(self, phase, layer, worker):
+        """(mag_ptr, mag_len, sign_ptr, sign_len, scale_ptr): device addresses of one packet."""
+        mp, sp, cp = C.c_void_p(), C.c_void_p(), C.c_void_p()
+        ml, sl = C.c_int64(), C.c_int64()
+        self._check(lib().lqsgd_packet_device(self._h, phase, layer, worker, C.byref(mp), C.byref(ml), C.byref(sp),
+                                              C.byref(sl), C.byref(cp)))
+        return mp.value, ml.value, sp.value, sl.value, cp.value
 
     def get_packet_raw(self, phase, layer, worker):
         ml, sl = C.c_int64(), C.c_int64()

@@ -675,6 +675,20 @@ int lqsgd_get_packet_raw(lqsgd_ctx* c, int32_t phase, int32_t layer, int32_t wor
   return LQSGD_OK;
 }
 
+int lqsgd_packet_device(lqsgd_ctx* c, int32_t phase, int32_t layer, int32_t worker, uint8_t** mag_plane,
+                        int64_t* mag_len, uint8_t** sign_plane, int64_t* sign_len, float** scale) {
+  if (!c) return fail(nullptr, LQSGD_EINVAL, "NULL context");
+  PacketLoc loc{};
+  int rc = locate_packet(c, phase, layer, worker, &loc);
+  if (rc) return rc;
+  if (mag_plane) *mag_plane = loc.mag;
+  if (mag_len) *mag_len = loc.mag_len;
+  if (sign_plane) *sign_plane = loc.sgn;
+  if (sign_len) *sign_len = loc.sign_len;
+  if (scale) *scale = loc.scale;
+  return LQSGD_OK;
+}
+
 int lqsgd_get_packet(lqsgd_ctx* c, int32_t phase, int32_t layer, int32_t worker, uint8_t* mag_codes,
                      uint8_t* sign_bits, float* scale) {
   if (!c) return fail(nullptr, LQSGD_EINVAL, "NULL context");

@@ -372,3 +372,46 @@ def test_step_recorded_into_a_graph(layers, rank, W):
             eb, qb = ref.get_state(l, w)
             assert np.array_equal(qa, qb) and np.array_equal(ea, eb)
     rec.close(); ref.close()
+
+
+def test_packets_move_between_contexts_on_the_device():
+    """lqsgd_packet_device: the packets one context compressed are copied, device to device, into
+    the slots of a second context, whose decompress then gives the first one's aggregate bit for bit
+    (what a collective between GPUs would do with the same pointers)."""
+    import ctypes as C
+    import torch
+    _say("case: packets handed over through device pointers")
+    hip = C.CDLL("libamdhip64.so")
+    hip.hipMemcpy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int]
+    layers, rank, bp, bq, W = [(300, 260), (64, 27)], 4, 8, 5, 3
+    rng = np.random.default_rng(31)
+    q0 = [rng.standard_normal((c, min(rank, r, c))).astype(f32) for r, c in layers]
+    G = [[torch.from_numpy((rng.standard_normal(s) * 1e-3).astype(f32)).cuda() for s in layers] for _ in range(W)]
+    Z = [[torch.zeros(s, device="cuda") for s in layers] for _ in range(W)]
+    ll = B.layer_list(layers, ())
+    src = B.Compressor(ll, rank, bp, bq, W, 255.0, 0)
+    dst = B.Compressor(ll, rank, bp, bq, W, 255.0, 0)
+    for l in range(len(layers)):
+        src.set_q(l, q0[l]); dst.set_q(l, q0[l])
+    src.compress(B.PHASE_P, G)
+    dst.compress(B.PHASE_P, Z)          # brings dst to the same phase; its own packets are all zero
+    src.synchronize(); dst.synchronize()
+    for l in range(len(layers)):
+        for w in range(W):
+            mp, ml, sp, sl, cp = src.packet_device(B.PHASE_P, l, w)
+            mp2, ml2, sp2, sl2, cp2 = dst.packet_device(B.PHASE_P, l, w)
+            assert (ml, sl) == (ml2, sl2) and ml == bp * sl
+            raw_m, raw_s = src.get_packet_raw(B.PHASE_P, l, w)
+            t = torch.empty(ml, dtype=torch.uint8, device="cuda")
+            assert hip.hipMemcpy(t.data_ptr(), mp, ml, 3) == 0        # 3 = device to device
+            assert np.array_equal(t.cpu().numpy(), raw_m)
+            for a, b, n in ((mp2, mp, ml), (sp2, sp, sl), (cp2, cp, 4)):
+                assert hip.hipMemcpy(a, b, n, 3) == 0
+    torch.cuda.synchronize()
+    src.decompress(B.PHASE_P); dst.decompress(B.PHASE_P)
+    for l in range(len(layers)):
+        assert np.array_equal(src.get_factor(B.FACTOR_P_BAR, l), dst.get_factor(B.FACTOR_P_BAR, l))
+    off = B.Compressor(ll, rank, 0, 0, W, 255.0, 0)
+    with pytest.raises(B.LqsgdError):
+        off.packet_device(B.PHASE_P, 0, 0)      # quantisation off: there is no packet
+    src.close(); dst.close(); off.close()
