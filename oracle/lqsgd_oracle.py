@@ -26,9 +26,10 @@ Readings of the paper where it is silent or ambiguous:
       (one float32 sent with the codes); s == 0 gives all-zero codes.
 * R5  a code is one sign bit plus a b-bit magnitude index k in [0, 2^b - 1];
       levels are uniform in the q-domain with both endpoints,
-      level_k = k / (2^b - 1); nearest level, ties upward; the paper fixes no
-      precision for that decision: it is taken on the float32 u against
-      float32 thresholds (the midpoints between levels mapped back by Eq. (6)).
+      level_k = k / (2^b - 1); nearest level of |q(u)| (Eq. (5)), ties upward,
+      decided in float64 on the float32 u = |x| / s.  (A second function gives
+      the float32 threshold-table form of the same decision; the two differ
+      only within a float32 rounding of a bucket boundary.)
 * R6  the "All-Reduce" of quantised factors means: dequantise every worker's
       packet, then take the mean (Eq. (1)), summed in worker order.
 * R7  effective rank of a layer is min(r, rows, cols).
@@ -73,14 +74,6 @@ def expand(q, alpha):
 # ----------------------------------------------------------------------------
 # Section 4.1, last paragraph: b-bit discretisation of |q| (readings R4, R5)
 # ----------------------------------------------------------------------------
-def level_thresholds(bits, alpha):
-    """Decision thresholds of the b-bit discretisation in the normalised magnitude u:
-    T_j = Eq. (6) at the midpoint (j + 1/2) / (2^b - 1) between levels j and j + 1,
-    j = 0 .. 2^b - 2, evaluated in float64 and stored as float32."""
-    lv = (1 << bits) - 1
-    return expand((np.arange(lv) + 0.5) / lv, alpha).astype(f32)
-
-
 def log_quantize(x, bits, alpha):
     """LogQuantize of Algorithm 1 (statements "P_quant <- ..." / "Q_quant <- ...").
 
@@ -91,11 +84,9 @@ def log_quantize(x, bits, alpha):
             nothing and is canonically 0)
       s     float32 absmax scale
     The normalised magnitude u = |x| / s is taken in float32 (the precision the
-    stored factor has).  Nearest level with ties upward, k = floor(lv q(u) + 1/2)
-    with q of Eq. (5), is the number of decision thresholds T_j <= u (Eq. (5) is
-    increasing); the comparison is taken in float32, u against the float32
-    thresholds, which is the precision an implementation that stores u in
-    float32 decides in.
+    stored factor has).  The map of Eq. (5) and the choice of the nearest of the
+    2^bits levels k / (2^bits - 1) of |q| (Section 4.1, last paragraph; ties go
+    up) run in float64: k = floor((2^bits - 1) q(u) + 1/2).
     """
     if not (1 <= bits <= 8):
         raise ValueError("bits must be in 1..8")
@@ -105,10 +96,38 @@ def log_quantize(x, bits, alpha):
     if not (s > 0):
         return (np.zeros(x.shape, np.uint8), np.zeros(x.shape, np.uint8), f32(0.0))
     u = (np.abs(x) / s).astype(f32)                       # float32 division
-    k = np.searchsorted(level_thresholds(bits, alpha), u, side="right")
+    t = lv * np.log1p(f64(alpha) * u.astype(f64)) / np.log1p(f64(alpha))
+    k = np.floor(t + 0.5)
     k = np.clip(k, 0, lv).astype(np.uint8)
     sign = ((x < 0) & (k > 0)).astype(np.uint8)
     return k, sign, s
+
+
+def level_thresholds(bits, alpha):
+    """Decision thresholds of the same discretisation in the normalised magnitude u:
+    T_j = Eq. (6) at the midpoint (j + 1/2) / (2^b - 1) between levels j and j + 1,
+    j = 0 .. 2^b - 2, evaluated in float64 and stored as float32."""
+    nlev = (1 << bits) - 1
+    return expand((np.arange(nlev) + 0.5) / nlev, alpha).astype(f32)
+
+
+def log_quantize_threshold_form(x, bits, alpha):
+    """The same discretisation decided in float32: the code of u is the number of float32
+    thresholds T_j <= u (Eq. (5) is increasing, so in exact arithmetic this is the nearest
+    level with ties upward).  It can differ from ``log_quantize`` by one level, and only where
+    u lies within a float32 rounding of a threshold; it is what an implementation that keeps
+    u and a threshold table in float32 computes, and the tests use it to tell such boundary
+    cases from real mistakes.  Returns (k, sign, s) like ``log_quantize``."""
+    if not (1 <= bits <= 8):
+        raise ValueError("bits must be in 1..8")
+    x = np.asarray(x, dtype=f32)
+    s = f32(np.max(np.abs(x))) if x.size else f32(0.0)
+    if not (s > 0):
+        return (np.zeros(x.shape, np.uint8), np.zeros(x.shape, np.uint8), f32(0.0))
+    u = (np.abs(x) / s).astype(f32)
+    kt = np.searchsorted(level_thresholds(bits, alpha), u, side="right").astype(np.uint8)
+    sign_t = ((x < 0) & (kt > 0)).astype(np.uint8)
+    return kt, sign_t, s
 
 
 def log_dequantize(k, sign, s, bits, alpha):

@@ -110,25 +110,70 @@ def check_two_bit_enumeration(o):
 
 
 def check_threshold_ties(o):
-    """The bin decision at the boundaries themselves: a value that equals a decision
-    threshold (the midpoint between two levels, mapped back by Eq. (6)) goes to the upper
-    level, the float32 value just below it to the lower one; thresholds written out here from
-    Eq. (6), not taken from the oracle."""
+    """The bin decision at and around the boundaries.
+    (a) Exact ties: for b = 1 the boundary is |q| = 1/2, i.e. 1 + alpha u = sqrt(1 + alpha); with
+        (alpha, u) = (8, 1/4), (48, 1/8), (224, 1/16) both sides are exact in binary (3^2 = 9,
+        7^2 = 49, 15^2 = 225), the tie goes to the upper level and the float32 below it down.
+    (b) Around every boundary (the midpoint between two levels mapped back by Eq. (6), written
+        out here, not taken from the oracle): a few float32 steps above it the upper level,
+        a few below it the lower one."""
+    for alpha, u in ((8.0, 0.25), (48.0, 0.125), (224.0, 0.0625)):
+        x = np.array([u, np.nextafter(f32(u), f32(0.0)), -u, 1.0], f32)
+        k, sg, s = o.log_quantize(x, 1, alpha)
+        assert s == 1.0 and k.tolist() == [1, 0, 1, 1] and sg.tolist() == [0, 0, 1, 0], (alpha, k, sg)
     for alpha in (1.0, 255.0):
         for bits in (1, 2, 4, 8):
             lv = (1 << bits) - 1
             mid = (np.arange(lv) + 0.5) / lv
-            thr = (((1.0 + alpha) ** mid - 1.0) / alpha).astype(f32)          # Eq. (6), float64 -> float32
-            below = np.nextafter(thr, f32(0.0)).astype(f32)
-            x = np.concatenate([thr, below, [f32(1.0)]]).astype(f32)          # the 1 makes the scale exactly 1
+            thr = ((1.0 + alpha) ** mid - 1.0) / alpha                        # Eq. (6), float64
+            above = thr.astype(f32)
+            below = thr.astype(f32)
+            for _ in range(3):
+                above = np.nextafter(above, f32(2.0)).astype(f32)
+                below = np.nextafter(below, f32(0.0)).astype(f32)
+            x = np.concatenate([above, below, [f32(1.0)]]).astype(f32)        # the 1 makes the scale exactly 1
+            for fn in (o.log_quantize, o.log_quantize_threshold_form):
+                k, sg, s = fn(x, bits, alpha)
+                assert s == 1.0
+                assert np.array_equal(k[:lv], np.arange(1, lv + 1)), (alpha, bits)
+                assert np.array_equal(k[lv:2 * lv], np.arange(0, lv)), (alpha, bits)
+                assert k[-1] == lv
+                kn, sgn, _ = fn(-x, bits, alpha)
+                assert np.array_equal(kn, k) and np.array_equal(sgn, (k > 0).astype(np.uint8))
+
+
+def check_threshold_form(o):
+    """The float32 threshold-table form against the float64 rule: equal everywhere except
+    within one float32 step of a boundary, and there at most one level apart; a value equal
+    to a float32 threshold counts as reached (goes up)."""
+    rng = _rng(17)
+    for alpha in (1.0, 255.0, 1000.0):
+        for bits in (1, 2, 4, 8):
+            lv = (1 << bits) - 1
+            mid = (np.arange(lv) + 0.5) / lv
+            thr32 = (((1.0 + alpha) ** mid - 1.0) / alpha).astype(f32)
+            x = np.concatenate([thr32, [f32(1.0)]]).astype(f32)
+            kt, _, s = o.log_quantize_threshold_form(x, bits, alpha)
+            assert s == 1.0 and np.array_equal(kt[:lv], np.arange(1, lv + 1))
+            # random values crowded around the boundaries, and plain ones
+            near = thr32[rng.integers(0, lv, 20000)]
+            steps = rng.integers(-3, 4, near.size)
+            for _ in range(3):
+                near = np.where(steps > 0, np.nextafter(near, f32(2.0)), np.where(steps < 0, np.nextafter(near, f32(0.0)), near)).astype(f32)
+                steps = steps - np.sign(steps)
+            x = np.concatenate([near, rng.random(20000).astype(f32), [f32(1.0)]]).astype(f32)
             k, sg, s = o.log_quantize(x, bits, alpha)
-            assert s == 1.0
-            assert np.array_equal(k[:lv], np.arange(1, lv + 1)), (alpha, bits)  # ties upward
-            assert np.array_equal(k[lv:2 * lv], np.arange(0, lv)), (alpha, bits)
-            assert k[-1] == lv
-            # and the same through negative values
-            kn, sgn, _ = o.log_quantize(-x, bits, alpha)
-            assert np.array_equal(kn, k) and np.array_equal(sgn, (k > 0).astype(np.uint8))
+            kt, sgt, st = o.log_quantize_threshold_form(x, bits, alpha)
+            assert s == st == 1.0
+            d = k.astype(np.int64) - kt.astype(np.int64)
+            assert np.abs(d).max() <= 1
+            bad = np.nonzero(d)[0]
+            u = x[bad]
+            j = np.minimum(k[bad], kt[bad]).astype(np.int64)      # the boundary between the two codes
+            t = thr32[j]
+            assert np.all((u == t) | (np.nextafter(u, f32(2.0)) == t) | (np.nextafter(u, f32(0.0)) == t))
+            assert bad.size < 0.5 * near.size                      # the crowd is +-3 steps wide
+            assert np.array_equal(sgt, ((x < 0) & (kt > 0)).astype(np.uint8))
 
 
 def check_quantiser_properties(o):
@@ -604,6 +649,7 @@ def all_checks(resnet_layers, resnet_vector_elems):
         ("bin_rounding_bruteforce", check_bin_rounding_bruteforce),
         ("two_bit_enumeration", check_two_bit_enumeration),
         ("threshold_ties", check_threshold_ties),
+        ("threshold_form", check_threshold_form),
         ("quantiser_properties", check_quantiser_properties),
         ("zero_and_shapes", check_zero_and_shapes),
         ("packing", check_packing),

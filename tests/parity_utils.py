@@ -19,10 +19,21 @@ from paper_2506_17974_amd import binding as B
 f32, f64 = np.float32, np.float64
 FP_TOL = 1e-4          # relative Frobenius error allowed on fp32 factors and residuals
 MEAN_TOL = 2e-6        # dequantise-and-mean: a handful of fp32 roundings
-# Codes: both sides take the bin decision in float32 (u against float32 thresholds), so the codes
-# of the HIP path must equal the oracle's on the same factor, all of them.  (The bar the task
-# states is looser: differences within 1 ulp of a bucket boundary on at most 1e-5 of the elements.)
-CODE_FLIP_BUDGET = 0.0
+# Codes are compared with the oracle's quantiser, which takes Eq. (5) and the nearest of the 2^b
+# levels in float64 (Section 4.1).  The HIP path decides in float32 against a float32 threshold
+# table, so it may land one level off where u lies within one float32 step of a bucket boundary;
+# every such element is verified to be exactly that, counted and reported, and the count is held to
+# CODE_BAND_BUDGET of the elements checked (on sets below SMALL_SET elements, where that would be a
+# fraction of one element, to at most SMALL_SET_BAND verified boundary cases).  Outside that band
+# the codes must be equal.  The HIP path's codes must also equal, all of them, the oracle's
+# float32 threshold-table form of the same decision.
+CODE_BAND_BUDGET = 1e-5
+SMALL_SET = 200000
+SMALL_SET_BAND = 2
+
+
+def code_band_budget(n_elems):
+    return SMALL_SET_BAND if n_elems < SMALL_SET else int(CODE_BAND_BUDGET * n_elems)
 
 
 def rel_fro(a, b):
@@ -39,17 +50,17 @@ def to_device(arrs):
 
 
 def check_codes(x_gpu, k_gpu, s_gpu, scale_gpu, bits, alpha):
-    """Oracle quantiser applied to the HIP path's own pre-quantisation tensor.
-    Returns the number of elements whose code differs (the caller requires zero); should one
-    ever differ, it is first classified here: anything but a one-level difference within one
-    fp32 ulp of a bucket boundary fails at once with that message."""
+    """Oracle quantiser (float64 nearest-level rule) applied to the HIP path's own
+    pre-quantisation tensor.  Returns the number of elements whose code differs; each of them
+    has been verified here to be a one-level difference at a bucket boundary (moving u by one
+    float32 step reaches the HIP path's code under the float64 rule) -- anything else fails at
+    once.  The caller adds the counts up and holds them to the budget."""
     k, sg, s = orc.log_quantize(x_gpu, bits, alpha)
     assert f32(scale_gpu) == s, "absmax scale differs: %r vs %r" % (scale_gpu, s)
     diff = k.astype(np.int32) != k_gpu.astype(np.int32)
-    nbad = int(diff.sum())
-    if nbad:
+    nband = int(diff.sum())
+    if nband:
         assert np.all(np.abs(k.astype(np.int32) - k_gpu.astype(np.int32))[diff] == 1), "a code is off by more than one level"
-        # boundary test: moving u by one ulp either way reaches the other code
         lv = (1 << bits) - 1
         u = (np.abs(x_gpu[diff]) / s).astype(f32)
         up = np.nextafter(u, f32(2.0)).astype(f64)
@@ -58,11 +69,15 @@ def check_codes(x_gpu, k_gpu, s_gpu, scale_gpu, bits, alpha):
         t_dn = np.floor(lv * np.log1p(alpha * dn) / np.log1p(alpha) + 0.5)
         kg = k_gpu[diff].astype(f64)
         assert np.all((t_up == kg) | (t_dn == kg)), "a differing code is not within 1 ulp of a bucket boundary"
-    # signs: compared where the code is non-zero on both sides
+    # the float32 threshold-table form of the same decision: no difference at all
+    kt, sgt, _ = orc.log_quantize_threshold_form(x_gpu, bits, alpha)
+    assert np.array_equal(kt, k_gpu), "%d codes differ from the float32 threshold form" % int((kt != k_gpu).sum())
+    assert np.array_equal(sgt, s_gpu), "sign bits differ"
+    # signs against the float64 rule: compared where the code is non-zero on both sides
     both = (k > 0) & (k_gpu > 0)
     assert np.array_equal(sg[both], s_gpu[both]), "sign bits differ"
     assert not np.any(s_gpu[k_gpu == 0]), "sign bit set on a zero code"
-    return nbad
+    return nband
 
 
 class StageReport:
@@ -76,7 +91,8 @@ class StageReport:
 
     def __str__(self):
         parts = ["%s=%.2e" % kv for kv in sorted(self.worst.items())]
-        return "codes %d/%d flipped; " % (self.code_flips, self.code_elems) + " ".join(parts)
+        return "codes: %d of %d at a bucket boundary (one level off the float64 rule, verified; budget %d), 0 elsewhere; " % (
+            self.code_flips, self.code_elems, code_band_budget(self.code_elems)) + " ".join(parts)
 
 
 def staged_iteration(comp: B.Compressor, G_host, G_dev, E_host, Q_host, matrix_layers, rep: StageReport,
@@ -192,7 +208,7 @@ def staged_iteration(comp: B.Compressor, G_host, G_dev, E_host, Q_host, matrix_l
             # behind G-hat rounds r times, each relative to the size of its terms
             scale = np.abs(M[(li, w)]) + absterms
             assert np.all(np.abs(e_gpu.astype(f64) + ghat - M[(li, w)]) <= (r_l + 2) * 6e-8 * scale + 1e-30)
-    assert rep.code_flips <= CODE_FLIP_BUDGET * rep.code_elems, str(rep)
+    assert rep.code_flips <= code_band_budget(rep.code_elems), str(rep)
     return E_new, Q_bar
 
 

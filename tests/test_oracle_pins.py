@@ -26,11 +26,17 @@ MUTANTS = [
     ("compand_unnormalised", "np.log1p(alpha * np.abs(x)) / np.log1p(alpha)", "np.log1p(alpha * np.abs(x))"),
     ("compand_drops_sign", "return np.sign(x) * np.log1p(alpha * np.abs(x))", "return np.log1p(alpha * np.abs(x))"),
     ("expand_misses_minus_one", "np.expm1(np.abs(q) * np.log1p(alpha)) / alpha", "np.exp(np.abs(q) * np.log1p(alpha)) / alpha"),
-    ("levels_off_by_one", "lv = (1 << bits) - 1\n    return expand((np.arange(lv)", "lv = (1 << bits)\n    return expand((np.arange(lv)"),
-    ("truncate_instead_of_round", "expand((np.arange(lv) + 0.5) / lv, alpha).astype(f32)", "expand((np.arange(lv) + 1.0) / lv, alpha).astype(f32)"),
-    ("round_down_ties_shifted", "expand((np.arange(lv) + 0.5) / lv, alpha).astype(f32)", "expand((np.arange(lv) + 0.25) / lv, alpha).astype(f32)"),
-    ("ties_downward", 'np.searchsorted(level_thresholds(bits, alpha), u, side="right")', 'np.searchsorted(level_thresholds(bits, alpha), u, side="left")'),
-    ("thresholds_in_q_domain", "expand((np.arange(lv) + 0.5) / lv, alpha).astype(f32)", "((np.arange(lv) + 0.5) / lv).astype(f32)"),
+    ("levels_off_by_one", "lv = (1 << bits) - 1\n    s = ", "lv = (1 << bits)\n    s = "),
+    ("truncate_instead_of_round", "k = np.floor(t + 0.5)", "k = np.floor(t)"),
+    ("round_down_ties_shifted", "k = np.floor(t + 0.5)", "k = np.floor(t + 0.75)"),
+    ("ties_downward", "k = np.floor(t + 0.5)", "k = np.ceil(t - 0.5)"),
+    ("nearest_in_x_domain", "t = lv * np.log1p(f64(alpha) * u.astype(f64)) / np.log1p(f64(alpha))", "t = lv * u.astype(f64)"),
+    ("log_map_unnormalised", "t = lv * np.log1p(f64(alpha) * u.astype(f64)) / np.log1p(f64(alpha))", "t = lv * np.log1p(f64(alpha) * u.astype(f64))"),
+    ("threshold_form_levels_off_by_one", "nlev = (1 << bits) - 1", "nlev = (1 << bits)"),
+    ("threshold_form_truncates", "expand((np.arange(nlev) + 0.5) / nlev, alpha).astype(f32)", "expand((np.arange(nlev) + 1.0) / nlev, alpha).astype(f32)"),
+    ("threshold_form_ties_downward", 'np.searchsorted(level_thresholds(bits, alpha), u, side="right")', 'np.searchsorted(level_thresholds(bits, alpha), u, side="left")'),
+    ("threshold_form_in_q_domain", "expand((np.arange(nlev) + 0.5) / nlev, alpha).astype(f32)", "((np.arange(nlev) + 0.5) / nlev).astype(f32)"),
+    ("threshold_form_sign_inverted", "sign_t = ((x < 0) & (kt > 0))", "sign_t = ((x > 0) & (kt > 0))"),
     ("scale_not_absmax", "s = f32(np.max(np.abs(x))) if x.size", "s = f32(np.max(x)) if x.size"),
     ("sign_inverted", "sign = ((x < 0) & (k > 0))", "sign = ((x > 0) & (k > 0))"),
     ("dequant_ignores_sign", "sgn = np.where(np.asarray(sign) != 0, -1.0, 1.0)", "sgn = 1.0"),
