@@ -155,7 +155,17 @@ int lqsgd_set_q(lqsgd_ctx* ctx, int32_t layer, const float* host_q);
 
 /* Copies out / in the residual E of (layer, worker) (rows x cols floats) and
  * the warm-start Q of `layer` (cols x r floats).  Either host pointer may be
- * NULL to skip that tensor.  Synchronises.  For a VECTOR layer: ESHAPE. */
+ * NULL to skip that tensor.  Synchronises.  For a VECTOR layer: ESHAPE.
+ * Between iterations this pair is all the state the method carries (Section 4.2;
+ * Algorithm 1, "Warm-start from previous Q"): saving it for every layer and
+ * worker and loading it into a fresh context of the same configuration resumes
+ * the run bit for bit.
+ * In the middle of a staged iteration -- after lqsgd_compress(PHASE_P) and before
+ * lqsgd_decompress(PHASE_Q) has run -- the residual buffer holds G' = G + E
+ * (Eq. (9)) of the iteration in progress, and that is what host_e receives;
+ * host_q still receives the Q this iteration started from.  lqsgd_set_state is
+ * meant for the time between iterations: in the middle of one it overwrites G'
+ * (or Q) under the iteration in progress. */
 int lqsgd_get_state(lqsgd_ctx* ctx, int32_t layer, int32_t worker, float* host_e, float* host_q);
 int lqsgd_set_state(lqsgd_ctx* ctx, int32_t layer, int32_t worker, const float* host_e,
                     const float* host_q);

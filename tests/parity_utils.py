@@ -11,6 +11,8 @@ that are insensitive to single code flips (E and G-hat).
 """
 from __future__ import annotations
 
+import os
+
 import numpy as np
 
 import oracle.lqsgd_oracle as orc
@@ -30,6 +32,11 @@ MEAN_TOL = 2e-6        # dequantise-and-mean: a handful of fp32 roundings
 CODE_BAND_BUDGET = 1e-5
 SMALL_SET = 200000
 SMALL_SET_BAND = 2
+
+
+# Per test (pytest's current test id): [codes at a bucket boundary, codes checked]; printed by
+# tests/conftest.py in the terminal summary, so that the counts reach the log of a quiet run too.
+BAND_COUNTS = {}
 
 
 def code_band_budget(n_elems):
@@ -77,6 +84,9 @@ def check_codes(x_gpu, k_gpu, s_gpu, scale_gpu, bits, alpha):
     both = (k > 0) & (k_gpu > 0)
     assert np.array_equal(sg[both], s_gpu[both]), "sign bits differ"
     assert not np.any(s_gpu[k_gpu == 0]), "sign bit set on a zero code"
+    tally = BAND_COUNTS.setdefault(os.environ.get("PYTEST_CURRENT_TEST", "?").split(" ")[0], [0, 0])
+    tally[0] += nband
+    tally[1] += int(k_gpu.size)
     return nband
 
 

@@ -55,13 +55,25 @@ def test_sweep_8192_full_size():
     _sampled_run(w, [0], [0, 7, 15], steps=2)
 
 
-@pytest.mark.parametrize("rank,bits", [(1, 2), (2, 4), (8, 8), (16, 4), (32, 8), (50, 8)])
-def test_sweep_8192_other_ranks(rank, bits):
-    """The other points of the rank / bit-width sweep at the full matrix size,
-    with four workers (the per-worker kernels do not depend on W)."""
-    w = wl.sweep_8192(rank, bits, workers=4)
-    _say("case: sweep_8192 r=%d b=%d W=4" % (rank, bits))
-    _sampled_run(w, [0], [3], steps=2 if rank <= 8 else 1)
+SWEEP_POINTS = [(r, b) for r in (1, 2, 4, 8, 16, 32) for b in (2, 4, 8)]
+
+
+@pytest.mark.parametrize("rank,bits", SWEEP_POINTS, ids=["r%d-b%d" % p for p in SWEEP_POINTS])
+def test_sweep_8192_every_point(rank, bits):
+    """Every point of the rank / bit-width sweep at the full matrix size and the configured
+    sixteen workers: all workers run, one is checked stage by stage (the per-worker kernels do
+    not depend on which worker it is; the exchange is checked over all sixteen packets).  Two
+    iterations at b = 8 (the second carries the residual and the warm start), one at b = 2, 4."""
+    w = wl.sweep_8192(rank, bits)
+    _say("case: sweep_8192 r=%d b=%d W=%d full size" % (rank, bits, w.workers))
+    _sampled_run(w, [0], [(5 * rank + bits) % w.workers], steps=2 if bits == 8 else 1)
+
+
+def test_sweep_8192_rank_50():
+    """A rank of the paper's own convergence figures (rank pad 64), four workers."""
+    w = wl.sweep_8192(50, 8, workers=4)
+    _say("case: sweep_8192 r=50 b=8 W=4")
+    _sampled_run(w, [0], [3], steps=1)
 
 
 def test_llm_stack_full_size():
@@ -80,7 +92,7 @@ def test_llm_stack_full_size():
     _sampled_run(w, sample, [0, 3], steps=2)
 
 
-@pytest.mark.parametrize("rank", [4, 32])
+@pytest.mark.parametrize("rank", [4, 16, 32])
 def test_sweep_8192_fused_step_equals_staged_at_full_size(rank):
     """The call the benchmark times (lqsgd_step with G-hat, residual deferred) at the full
     8192 x 8192, W = 16 size: two iterations leave bit for bit the state that the staged

@@ -121,6 +121,8 @@ EDGE_CASES = [
     ([(129, 131), (300, 64)], 40, 8, 4, 2, 255.0),         # pad 64 with unaligned rows (plain fallback) and a clipped rank
     ([(257, 513)], 4, 1, 1, 2, 255.0),
     ([(257, 513)], 4, 3, 5, 2, 255.0),
+    ([(257, 513)], 4, 6, 7, 2, 255.0),                     # bit widths that are not whole bytes or nibbles
+    ([(257, 513), (64, 27)], 8, 7, 6, 3, 255.0),
     ([(257, 513)], 4, 0, 0, 4, 255.0),                     # quantisation off
     ([(257, 513)], 4, 0, 8, 2, 255.0),
     ([(64, 576), (128, 64)], 4, 8, 8, 8, 1.0),

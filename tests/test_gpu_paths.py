@@ -1,0 +1,187 @@
+"""GPU parity for the code paths and API calls that the other files do not reach:
+the in-memory Gram-Schmidt kernel (factors of 513..2048 rows at rank pads >= 16),
+factor injection through lqsgd_set_factor, the checkpoint round trip through
+lqsgd_get_state / lqsgd_set_state, and what lqsgd_get_state returns in the middle of
+a staged iteration.  Everything here needs a real MI355X."""
+import numpy as np
+import pytest
+
+import oracle.lqsgd_oracle as orc
+from paper_2506_17974_amd import binding as B
+from paper_2506_17974_amd import workloads as wl
+from tests import parity_utils as pu
+from tests.test_gpu_parity import _make, _random_inputs, _run_staged, _say, _vector_mean_ok
+
+pytestmark = pytest.mark.gpu
+f32, f64 = np.float32, np.float64
+
+
+# ---------------------------------------------------------------------------
+# Gram-Schmidt in memory: one workgroup per (layer, worker), rows beyond what the
+# register-resident form holds at that rank
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("layers,rank,W", [
+    ([(1024, 260)], 16, 2),                       # 1024 rows at rank pad 16
+    ([(1024, 3136), (10, 1024)], 16, 4),          # the small CNN's fc1 / fc2 at rank 16
+    ([(1024, 260), (600, 128)], 32, 2),           # rank pad 32
+    ([(1500, 68)], 50, 2),                        # rank pad 64
+    ([(1024, 132)], 20, 3),                       # rank below its pad
+])
+def test_in_memory_gram_schmidt(layers, rank, W):
+    _say("case: in-memory Gram-Schmidt", layers, rank, W)
+    rep = _run_staged(layers, rank, 8, 8, W, steps=2, seed=rank + W, e0_scale=3e-4)
+    _say("  ", rep)
+
+
+# ---------------------------------------------------------------------------
+# lqsgd_set_factor: another implementation's aggregated factors take the place of
+# the device's own (Algorithm 1, "Q <- G'^T P" with the injected P; the warm start
+# with the injected Q)
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("layers,rank,W", [([(64, 576), (33, 70)], 4, 4), ([(200, 1100)], 32, 2)])
+def test_set_factor_injects_the_oracles_factors(layers, rank, W):
+    _say("case: set_factor", layers, rank, W)
+    rng = np.random.default_rng(rank)
+    comp, ml = _make(layers, (), rank, 8, 8, W)
+    Q0 = [rng.standard_normal((c, min(rank, r, c))).astype(f32) for r, c in layers]
+    for l in ml:
+        comp.set_q(l, Q0[l])
+    G = _random_inputs(rng, layers, W)
+    Gd = pu.to_device(G)
+    zeros = [[np.zeros(s, f32) for s in layers] for _ in range(W)]
+    # the oracle's own iteration on the same inputs
+    outs = [orc.layer_step([G[k][l] for k in range(W)], [zeros[k][l] for k in range(W)], Q0[l], rank, 8, 8, 255.0)
+            for l in ml]
+    comp.compress(B.PHASE_P, Gd)
+    comp.decompress(B.PHASE_P)
+    for l in ml:
+        assert pu.rel_fro(comp.get_factor(B.FACTOR_P_BAR, l), outs[l]["P_bar"]) < 0.1    # same thing, up to code flips
+        comp.set_factor(B.FACTOR_P_BAR, l, outs[l]["P_bar"])
+        assert np.array_equal(comp.get_factor(B.FACTOR_P_BAR, l), outs[l]["P_bar"])
+    comp.compress(B.PHASE_Q)
+    for l in ml:
+        for k in range(W):
+            # M is one IEEE addition on both sides, so the oracle's Q_w is M^T P-bar of the same operands
+            err = pu.rel_fro(comp.get_factor(B.FACTOR_Q_W, l, k), outs[l]["Q_w"][k])
+            assert err <= pu.FP_TOL, (l, k, err)
+    comp.decompress(B.PHASE_Q)
+    for l in ml:
+        pb = outs[l]["P_bar"]
+        qb_dev = comp.get_factor(B.FACTOR_Q_BAR, l)
+        # injecting Q-bar after the iteration: the residual keeps the value the device's own Q-bar gave it
+        # (a deferred update is applied before the factor is overwritten), the warm start changes
+        comp.set_factor(B.FACTOR_Q_BAR, l, outs[l]["Q_bar"])
+        for k in range(W):
+            e, q = comp.get_state(l, k)
+            assert np.array_equal(q, outs[l]["Q_bar"])
+            m = (G[k][l].astype(f64) + zeros[k][l]).astype(f32)
+            want = (m.astype(f64) - (pb.astype(f64) @ qb_dev.astype(f64).T).astype(f32)).astype(f32)
+            assert pu.rel_fro(e, want) <= pu.FP_TOL
+    # the next iteration starts from the injected Q-bar
+    G2 = _random_inputs(rng, layers, W)
+    comp.compress(B.PHASE_P, pu.to_device(G2))
+    for l in ml:
+        for k in range(W):
+            m, _ = comp.get_state(l, k, want_q=False)
+            want = m.astype(f64) @ outs[l]["Q_bar"].astype(f64)
+            assert pu.rel_fro(comp.get_factor(B.FACTOR_P_PRE, l, k), want) <= pu.FP_TOL
+    with pytest.raises(B.LqsgdError) as ei:
+        comp.set_factor(B.FACTOR_Q_W, 0, outs[0]["Q_w"][0])
+    assert ei.value.code == B.EINVAL
+    comp.close()
+
+
+# ---------------------------------------------------------------------------
+# what lqsgd_get_state returns between the calls of a staged iteration
+# ---------------------------------------------------------------------------
+def test_get_state_in_the_middle_of_an_iteration():
+    _say("case: get_state mid-iteration")
+    layers, rank, W = [(64, 576), (17, 100)], 4, 2
+    rng = np.random.default_rng(3)
+    comp, ml = _make(layers, (), rank, 8, 8, W)
+    Q0 = [rng.standard_normal((c, min(rank, r, c))).astype(f32) for r, c in layers]
+    E0 = [[(rng.standard_normal(s) * 1e-4).astype(f32) for s in layers] for _ in range(W)]
+    for l in ml:
+        comp.set_q(l, Q0[l])
+        for k in range(W):
+            comp.set_state(l, k, e=E0[k][l])
+    G = _random_inputs(rng, layers, W)
+    comp.compress(B.PHASE_P, pu.to_device(G))
+    for stage in ("after compress(P)", "after decompress(P)", "after compress(Q)"):
+        for l in ml:
+            for k in range(W):
+                m, q = comp.get_state(l, k)
+                assert np.array_equal(m, (G[k][l].astype(f64) + E0[k][l]).astype(f32)), stage   # G' = G + E (Eq. (9))
+                assert np.array_equal(q, Q0[l]), stage                                          # still this iteration's Q
+        if stage == "after compress(P)":
+            comp.decompress(B.PHASE_P)
+        elif stage == "after decompress(P)":
+            comp.compress(B.PHASE_Q)
+    comp.decompress(B.PHASE_Q)
+    for l in ml:
+        qb = comp.get_factor(B.FACTOR_Q_BAR, l)
+        gh = (comp.get_factor(B.FACTOR_P_BAR, l).astype(f64) @ qb.astype(f64).T).astype(f32)
+        for k in range(W):
+            e, q = comp.get_state(l, k)
+            assert np.array_equal(q, qb)
+            m = (G[k][l].astype(f64) + E0[k][l]).astype(f32)
+            assert pu.rel_fro(e, (m.astype(f64) - gh).astype(f32)) <= pu.FP_TOL                 # Eq. (8)
+    comp.close()
+
+
+# ---------------------------------------------------------------------------
+# checkpoint / resume: the state the method carries between iterations is E of every
+# worker (Section 4.2) and the warm-start Q of every layer (Algorithm 1)
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("name,rank,flags", [("small_cnn", 4, 0), ("small_cnn", 16, 0), ("mixed", 32, 0),
+                                             ("small_cnn", 4, B.FLAG_AGGREGATE_FIRST)])
+def test_resume_from_saved_state_is_bit_identical(name, rank, flags):
+    import torch
+    _say("case: resume", name, rank, flags)
+    if name == "small_cnn":
+        w = wl.small_cnn()
+        layers, vectors, W = list(w.layers), list(w.vectors), w.workers
+    else:
+        layers, vectors, W = [(200, 1100), (10, 512), (64, 27), (1024, 260)], [33], 2
+    L, V = len(layers), len(vectors)
+    rng = np.random.default_rng(41)
+    Q0 = [rng.standard_normal((c, min(rank, r, c))).astype(f32) for r, c in layers]
+    steps = [pu.to_device([g + [(rng.standard_normal(n) * 1e-3).astype(f32) for n in vectors]
+                           for g in _random_inputs(rng, layers, W)]) for _ in range(10)]
+
+    def outputs():
+        return [torch.empty(s, device="cuda") for s in layers] + [torch.empty(n, device="cuda") for n in vectors]
+
+    def run(comp, ghat, ts):
+        for t in ts:
+            comp.step(steps[t], ghat)
+        comp.synchronize()
+
+    ref, ml = _make(layers, vectors, rank, 8, 8, W, flags=flags)
+    for l in ml:
+        ref.set_q(l, Q0[l])
+    g_ref = outputs()
+    run(ref, g_ref, range(10))
+
+    first, _ = _make(layers, vectors, rank, 8, 8, W, flags=flags)
+    for l in ml:
+        first.set_q(l, Q0[l])
+    g_a = outputs()
+    run(first, g_a, range(5))
+    saved = [[first.get_state(l, k) for l in ml] for k in range(W)]      # (E, Q) per worker and layer
+    first.close()
+
+    second, _ = _make(layers, vectors, rank, 8, 8, W, flags=flags)
+    for l in ml:
+        for k in range(W):
+            second.set_state(l, k, e=saved[k][l][0], q=saved[k][l][1] if k == 0 else None)
+    g_b = outputs()
+    run(second, g_b, range(5, 10))
+    for i in range(L + V):
+        assert torch.equal(g_ref[i], g_b[i]), "output %d differs after the resume" % i
+    for l in ml:
+        for k in range(W):
+            e1, q1 = ref.get_state(l, k)
+            e2, q2 = second.get_state(l, k)
+            assert np.array_equal(e1, e2) and np.array_equal(q1, q2), (l, k)
+    ref.close(); second.close()
