@@ -8,6 +8,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -40,10 +41,14 @@ struct lqsgd_ctx {
   bool flip = true;
   bool eager = false;       // LQSGD_FLAG_EAGER_RESIDUAL
   bool pending = false;     // E buffer holds M; E = M - P-bar Q-bar^T not applied yet
-  unsigned long long orth_epoch = 0;   // cooperative Gram-Schmidt launches so far
+  CoopState coop;           // one-launch Gram-Schmidt: launch count, device capacity, wait bound
   int* status = nullptr;    // pinned, device-visible: non-zero once a bounded device-side wait has expired
   std::string err;
   std::vector<void*> allocs;
+  // When set, device memory is carved out of this caller-provided block instead of being allocated
+  // (the context then owns no device memory at all).
+  unsigned char* arena = nullptr;
+  size_t arena_cap = 0, arena_used = 0;
   DevArgs args{};
   // device copies of the work lists
   Tile* d_tilesA = nullptr; Tile* d_tilesB = nullptr; Tile* d_tilesG = nullptr; Tile* d_tilesBM = nullptr; Tile* d_tilesAG = nullptr;
@@ -84,6 +89,18 @@ template <typename T>
 int dev_alloc(lqsgd_ctx* c, T** out, size_t count, bool zero) {
   *out = nullptr;
   if (count == 0) count = 1;
+  if (c->arena) {     // bump allocation, 256-byte granules; the block is cleared as a whole by whoever set it up
+    const size_t bytes = (count * sizeof(T) + 255) & ~(size_t)255;
+    if (bytes > c->arena_cap - c->arena_used) {
+      char buf[200];
+      std::snprintf(buf, sizeof buf, "this configuration needs more scratch memory than the static buffer holds (%zu bytes)",
+                    c->arena_cap);
+      return fail(c, LQSGD_EUNSUPPORTED, buf);
+    }
+    *out = reinterpret_cast<T*>(c->arena + c->arena_used);
+    c->arena_used += bytes;
+    return LQSGD_OK;
+  }
   void* p = nullptr;
   hipError_t e = hipMalloc(&p, count * sizeof(T));
   if (e != hipSuccess) {
@@ -224,7 +241,7 @@ int run_sweep0(lqsgd_ctx* c) {
     HIP_TRY(c, launch_reduce_q(0, c->args, c->d_tilesRP, (int)c->plan.tilesRP.size(), c->stream));
   } else {
     Timed t(c, LQSGD_KERNEL_ORTH);
-    HIP_TRY(c, launch_orth(c->plan.RP, c->plan.max_rows, c->plan.max_rank, c->args, &c->orth_epoch, c->stream));
+    HIP_TRY(c, launch_orth(c->plan.RP, c->plan.max_rows, c->plan.max_rank, c->args, &c->coop, c->stream));
   }
   return LQSGD_OK;
 }
@@ -238,7 +255,7 @@ int run_orth_shared(lqsgd_ctx* c) {
   a.Ppart = c->args.Pbar; a.ppart_stride = 0;
   a.Ppre = c->args.Porth;
   a.Porth = c->args.Pbar;
-  HIP_TRY(c, launch_orth(c->plan.RP, c->plan.max_rows, c->plan.max_rank, a, &c->orth_epoch, c->stream));
+  HIP_TRY(c, launch_orth(c->plan.RP, c->plan.max_rows, c->plan.max_rank, a, &c->coop, c->stream));
   c->ppad_stale = true;
   return LQSGD_OK;
 }
@@ -392,53 +409,39 @@ int64_t lqsgd_plan_tiles(const lqsgd_config* cfg, const lqsgd_layer* layers, int
   return (int64_t)tl.size();
 }
 
-int lqsgd_create(const lqsgd_config* cfg, const lqsgd_layer* layers, int32_t n_layers, void* hip_stream,
-                 lqsgd_ctx** out) {
-  if (!out) return fail(nullptr, LQSGD_EINVAL, "NULL output pointer");
-  *out = nullptr;
-  lqsgd_ctx* c = new (std::nothrow) lqsgd_ctx();
-  if (!c) return fail(nullptr, LQSGD_ENOMEM, "out of host memory");
-  int rc = c->plan.build(cfg, layers, n_layers);
-  if (rc) {
-    g_create_error = c->plan.err;
-    delete c;
-    return rc;
-  }
-  c->stream = static_cast<hipStream_t>(hip_stream);
-  if (const char* f = std::getenv("LQSGD_FLIP")) c->flip = (f[0] != '0');
-  c->eager = (cfg->flags & LQSGD_FLAG_EAGER_RESIDUAL) != 0;
-  if (const char* f = std::getenv("LQSGD_EAGER")) c->eager = (f[0] != '0');
-  auto bail = [&](int code) {
-    g_create_error = c->err;
-    for (void* p : c->allocs) (void)hipFree(p);
-    if (c->status) (void)hipHostFree(c->status);
-    delete c;
-    return code;
-  };
-  {
-    hipError_t e = hipGetDevice(&c->device);
-    if (e != hipSuccess) { fail_hip(c, e, "hipGetDevice"); return bail(LQSGD_EHIP); }
-  }
+namespace {
+// Fills c->args and uploads the tables of c->plan.  Device memory comes from hipMalloc or, when
+// c->arena is set, from that block: then the residual slabs and the warm-start Q are not allocated
+// (the caller's buffers are bound per call), and the one-launch Gram-Schmidt of tall factors, which
+// needs a pinned status word and a table that starts from zero, is off (its per-column form runs).
+// On failure the caller releases c->allocs / c->status.
+int setup_device(lqsgd_ctx* c, uint32_t flags) {
+  int rc;
+  const bool ext = c->arena != nullptr;
+  c->eager = ext || (flags & LQSGD_FLAG_EAGER_RESIDUAL) != 0;
+  HIP_TRY(c, hipGetDevice(&c->device));
   const Plan& p = c->plan;
   DevArgs& a = c->args;
   a.W = p.W; a.L = p.L; a.n_all = p.n_all; a.bits_p = p.cfg.bits_p; a.bits_q = p.cfg.bits_q;
   a.alpha = p.cfg.alpha;
   a.agg_first = p.agg_first ? 1 : 0; a.orth_shared = 0; a.update = 0; a.eta = 0.0f;
-  a.g_bf16 = (cfg->flags & LQSGD_FLAG_BF16_GRADIENTS) ? 1 : 0;
+  a.g_bf16 = (flags & LQSGD_FLAG_BF16_GRADIENTS) ? 1 : 0;
   // The residual / M slabs are read and written once per sweep.  While they are about the size of
   // the memory-side cache (256 MB), plain loads and stores in sweep 0 are faster (ResNet-18 set,
   // 357 MB: a step takes 276 us; 284 us with non-temporal loads of E, 295 us with non-temporal
   // stores as well).  Far beyond it, the dirty lines that plain stores leave in that cache are
   // written back underneath the following reads, and streaming both ways wins (8192^2 x 16,
   // 4.3 GB: sweep 0 2.27 -> 2.04 - 2.14 ms).  Measured crossover: 0.55 - 0.7 GB.
-  // LQSGD_NT_STORE=1 / 2 forces streaming on / off.
   {
     const int64_t slab_bytes = 4 * (int64_t)p.W * p.m_stride;
     a.nt_store = slab_bytes >= ((int64_t)640 << 20) ? 1 : 0;
+#ifdef LQSGD_TUNING     // a tuning build can force the choice and switch the alternating sweep direction off
     if (const char* f = std::getenv("LQSGD_NT_STORE")) {
       if (f[0] == '1') a.nt_store = 1;
       if (f[0] == '2') a.nt_store = 0;
     }
+    if (const char* f = std::getenv("LQSGD_FLIP")) c->flip = (f[0] != '0');
+#endif
   }
   a.qscale_p = (float)(((1 << p.cfg.bits_p) - 1) / std::log2(1.0 + (double)p.cfg.alpha));
   a.qscale_q = (float)(((1 << p.cfg.bits_q) - 1) / std::log2(1.0 + (double)p.cfg.alpha));
@@ -452,20 +455,22 @@ int lqsgd_create(const lqsgd_config* cfg, const lqsgd_layer* layers, int32_t n_l
   std::vector<float> tP, lP, tQ, lQ;
   quantiser_tables(p.cfg.bits_p, (double)p.cfg.alpha, tP, lP);
   quantiser_tables(p.cfg.bits_q, (double)p.cfg.alpha, tQ, lQ);
-#define TRY_(x) do { if ((rc = (x))) return bail(rc); } while (0)
+#define TRY_(x) do { if ((rc = (x))) return rc; } while (0)
   // Loaders for ranks below their register pad fetch whole padded rows and may run up to 31 floats
   // past the last row of a factor: every factor buffer ends with this much readable slack.
-  constexpr size_t kSlack = 64;
-  TRY_(dev_alloc(c, &a.E, W * p.m_stride, true));
+  constexpr size_t kSlack = kFactorSlack;
+  const size_t orth_cells = 2 * W * (size_t)std::max(p.L, 1) * ((p.max_rows + 255) / 256) * p.RP;
+  a.E = nullptr; a.Qbar = nullptr; a.orth_table = nullptr; a.status = nullptr;
+  if (!ext) TRY_(dev_alloc(c, &a.E, W * p.m_stride, true));
   TRY_(dev_alloc(c, &a.Ppart, W * p.ppart_stride + kSlack, true));
   TRY_(dev_alloc(c, &a.Ppre, W * p.p_stride + kSlack, true));
   TRY_(dev_alloc(c, &a.Porth, W * p.p_stride + kSlack, true));
-  TRY_(dev_alloc(c, &a.orth_part, 2 * W * (size_t)std::max(p.L, 1) * ((p.max_rows + 255) / 256) * p.RP, true));
-  TRY_(dev_alloc(c, &a.orth_table, 2 * W * (size_t)std::max(p.L, 1) * ((p.max_rows + 255) / 256) * p.RP, true));
-  {
+  TRY_(dev_alloc(c, &a.orth_part, orth_cells, true));
+  if (!ext) {
+    TRY_(dev_alloc(c, &a.orth_table, orth_cells, true));
     void* hp = nullptr;
     hipError_t e = hipHostMalloc(&hp, sizeof(int), hipHostMallocDefault);
-    if (e != hipSuccess) { fail_hip(c, e, "hipHostMalloc"); return bail(LQSGD_ENOMEM); }
+    if (e != hipSuccess) { fail_hip(c, e, "hipHostMalloc"); return LQSGD_ENOMEM; }
     c->status = static_cast<int*>(hp);
     *c->status = 0;
     a.status = c->status;
@@ -473,7 +478,7 @@ int lqsgd_create(const lqsgd_config* cfg, const lqsgd_layer* layers, int32_t n_l
   TRY_(dev_alloc(c, &a.Pbar, (size_t)p.p_stride + kSlack, true));
   TRY_(dev_alloc(c, &a.Qpart, W * p.qpart_stride + kSlack, true));
   TRY_(dev_alloc(c, &a.Qw, W * p.q_stride + kSlack, true));
-  TRY_(dev_alloc(c, &a.Qbar, (size_t)p.q_stride + kSlack, true));
+  if (!ext) TRY_(dev_alloc(c, &a.Qbar, (size_t)p.q_stride + kSlack, true));
   a.Ppad = nullptr; a.Qpad = nullptr;
   if (p.padded) {
     TRY_(dev_alloc(c, &a.Ppad, (size_t)p.ppad_total + kSlack, true));
@@ -486,6 +491,12 @@ int lqsgd_create(const lqsgd_config* cfg, const lqsgd_layer* layers, int32_t n_l
   TRY_(dev_alloc(c, &a.sgnQ, W * p.sgnq_stride, true));
   TRY_(dev_alloc(c, &a.scaleQ, W * (size_t)std::max(p.L, 1), true));
   TRY_(dev_alloc(c, &a.vmean, (size_t)p.v_total, true));
+  TRY_(dev_alloc(c, &c->d_grads, W * p.n_all, true));
+  TRY_(dev_alloc(c, &c->d_ghat, (size_t)p.n_all, true));
+  // In a caller-provided block everything above is cleared here, by a kernel, before the tables
+  // below are copied in (the block keeps whatever its last user left).
+  if (ext) HIP_TRY(c, launch_fill_zero(c->arena, c->arena_used, c->stream));
+  if (ext) HIP_TRY(c, hipStreamSynchronize(c->stream));
   TRY_(dev_upload(c, &d_layers, p.layers));
   TRY_(dev_upload(c, &d_vecs, p.vecs));
   TRY_(dev_upload(c, &thrP, tP)); TRY_(dev_upload(c, &levP, lP));
@@ -500,15 +511,40 @@ int lqsgd_create(const lqsgd_config* cfg, const lqsgd_layer* layers, int32_t n_l
   TRY_(dev_upload(c, &c->d_tilesRQ, p.tilesRQ));
   TRY_(dev_upload(c, &c->d_tilesRP, p.tilesRP));
   TRY_(dev_upload(c, &c->d_tilesV, p.tilesV));
-  TRY_(dev_alloc(c, &c->d_grads, W * p.n_all, true));
-  TRY_(dev_alloc(c, &c->d_ghat, (size_t)p.n_all, true));
 #undef TRY_
   a.layers = d_layers; a.vecs = d_vecs;
   a.thrP = thrP; a.levP = levP; a.thrQ = thrQ; a.levQ = levQ;
   a.grads = c->d_grads; a.ghat = nullptr;
-  {
-    hipError_t e = hipStreamSynchronize(c->stream);
-    if (e != hipSuccess) { fail_hip(c, e, "hipStreamSynchronize"); return bail(LQSGD_EHIP); }
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  return LQSGD_OK;
+}
+}  // namespace
+
+int lqsgd_create(const lqsgd_config* cfg, const lqsgd_layer* layers, int32_t n_layers, void* hip_stream,
+                 lqsgd_ctx** out) {
+  if (!out) return fail(nullptr, LQSGD_EINVAL, "NULL output pointer");
+  *out = nullptr;
+  lqsgd_ctx* c = new (std::nothrow) lqsgd_ctx();
+  if (!c) return fail(nullptr, LQSGD_ENOMEM, "out of host memory");
+  int rc = c->plan.build(cfg, layers, n_layers);
+  if (rc) {
+    g_create_error = c->plan.err;
+    delete c;
+    return rc;
+  }
+  c->stream = static_cast<hipStream_t>(hip_stream);
+  // The bound of the device-side waits of the one-launch Gram-Schmidt can be shortened for a test
+  // of the expiry path (read once, here; nothing else in the library reads the environment).
+  if (const char* e = std::getenv("LQSGD_TABLE_POLLS")) {
+    const long v = std::strtol(e, nullptr, 10);
+    if (v >= 1) c->coop.max_polls = (unsigned)v;
+  }
+  if ((rc = setup_device(c, cfg->flags))) {
+    g_create_error = c->err;
+    for (void* p : c->allocs) (void)hipFree(p);
+    if (c->status) (void)hipHostFree(c->status);
+    delete c;
+    return rc;
   }
   *out = c;
   return LQSGD_OK;

@@ -53,9 +53,14 @@ enum ExchangeMode { kQuantOnly = 0, kMeanOnly = 1, kFused = 2 };
 // E = M - P-bar Q-bar^T is applied on the fly (see add_project_kernel).
 hipError_t launch_add_project(int RP, const DevArgs& a, const Tile* tiles, int ntiles, int fuse_residual, int reverse,
                               hipStream_t s);
-// coop_epoch: number of cooperative Gram-Schmidt launches this context has made so far (it makes the
-// tags in `a.orth_table` unique); incremented when that path is taken.  NULL disables it.
-hipError_t launch_orth(int RP, int max_rows, int max_rank, const DevArgs& a, unsigned long long* coop_epoch, hipStream_t s);
+// What a context keeps for the one-launch (cooperative) Gram-Schmidt of tall factors.
+struct CoopState {
+  unsigned long long epoch = 0;   // launches made so far: makes the tags in `a.orth_table` unique
+  int capacity = -1;              // workgroups of that kernel that fit the context's device at once (-1: not asked yet)
+  unsigned max_polls = 0;         // bound of a device-side wait; 0 = the default (about a second)
+};
+// coop: NULL disables the one-launch form.
+hipError_t launch_orth(int RP, int max_rows, int max_rank, const DevArgs& a, CoopState* coop, hipStream_t s);
 hipError_t launch_exchange(int mode, int phase, const DevArgs& a, const XTile* tiles, int ntiles, hipStream_t s);
 // Sweep 1 also runs the plain mean of the 1-D tensors (nvtiles extra workgroups).
 hipError_t launch_back_project(int RP, const DevArgs& a, const Tile* tiles, int ntiles, const VTile* vtiles, int nvtiles,
@@ -75,6 +80,9 @@ hipError_t launch_residual(int RP, int mode, const DevArgs& a, const Tile* tiles
 // full_rank: the largest effective rank of the layers equals RP (chooses between two forms of the fused add mode).
 // Refreshes a.Ppad (which = 0) or a.Qpad (which = 1) from the tightly packed factor.
 hipError_t launch_pad_factor(int RP, int which, const DevArgs& a, hipStream_t s);
+
+// Clears `bytes` (a multiple of 16) at the 16-byte aligned device address p with a kernel.
+hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);
 
 hipError_t launch_mfma_sweep(int RP, int mode, int full_rank, const DevArgs& a, const Tile* tiles, int ntiles, int reverse,
                              hipStream_t s);

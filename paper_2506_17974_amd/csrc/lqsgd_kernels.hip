@@ -20,6 +20,7 @@
 
 #include <hip/hip_cooperative_groups.h>
 
+#include <algorithm>
 #include <cfloat>
 #include <cstdlib>
 #include <type_traits>
@@ -2396,31 +2397,25 @@ void launch_orth_reg(const DevArgs& a, dim3 grid, hipStream_t s) {
 // One cooperative launch if every workgroup of the grid can be resident at once; returns false
 // (nothing launched) otherwise, and the caller takes the one-launch-per-column path.
 template <int RP>
-bool try_orth_coop(int nslice, int max_rank, const DevArgs& a, int nblocks, unsigned long long* epoch, hipStream_t s) {
-  static int capacity = -1;                      // resident workgroups of this kernel on the whole device
-  if (capacity < 0) {
+bool try_orth_coop(int nslice, int max_rank, const DevArgs& a, int nblocks, CoopState* cs, hipStream_t s) {
+  if (cs->capacity < 0) {                        // resident workgroups of this kernel on the context's device
     int dev = 0, coop = 0, cus = 0, per_cu = 0;
     if (hipGetDevice(&dev) != hipSuccess ||
         hipDeviceGetAttribute(&coop, hipDeviceAttributeCooperativeLaunch, dev) != hipSuccess ||
         hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
         hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, orth_coop_kernel<RP>, 256, 0) != hipSuccess) {
       (void)hipGetLastError();
-      capacity = 0;
+      cs->capacity = 0;
     } else {
-      capacity = coop ? cus * per_cu : 0;
+      cs->capacity = coop ? cus * per_cu : 0;
     }
   }
-  if (nblocks > capacity) return false;
+  if (nblocks > cs->capacity) return false;
   DevArgs args = a;
   unsigned long long* table = a.orth_table;
-  unsigned long long n = *epoch;
+  unsigned long long n = cs->epoch;
   int* status = a.status;
-  // LQSGD_TABLE_POLLS shortens the bound (a test of the expiry path sets it to 1)
-  unsigned max_polls = kTablePolls;
-  if (const char* e = std::getenv("LQSGD_TABLE_POLLS")) {
-    const long v = std::strtol(e, nullptr, 10);
-    if (v >= 1) max_polls = (unsigned)v;
-  }
+  unsigned max_polls = cs->max_polls ? cs->max_polls : kTablePolls;
   void* params[] = {&args, &nslice, &max_rank, &table, &n, &status, &max_polls};
   const hipError_t e = hipLaunchCooperativeKernel(reinterpret_cast<void*>(orth_coop_kernel<RP>), dim3(nblocks), dim3(256),
                                                   params, 0, s);
@@ -2428,14 +2423,16 @@ bool try_orth_coop(int nslice, int max_rank, const DevArgs& a, int nblocks, unsi
     (void)hipGetLastError();
     return false;
   }
-  *epoch += 1;                                   // the tags of a launch are epoch * max_rank + 1 ... + max_rank
+  cs->epoch += 1;                                // the tags of a launch are epoch * max_rank + 1 ... + max_rank
   return true;
 }
 
-bool launch_orth_coop(int rp, int nslice, int max_rank, const DevArgs& a, int nblocks, unsigned long long* epoch,
-                      hipStream_t s) {
+bool launch_orth_coop(int rp, int nslice, int max_rank, const DevArgs& a, int nblocks, CoopState* cs, hipStream_t s) {
+#ifdef LQSGD_TUNING
   static const bool enabled = [] { const char* e = std::getenv("LQSGD_ORTH_COOP"); return !(e && e[0] == '0'); }();
-  if (!enabled || !epoch || !a.orth_table || !a.status || nslice > kCoopMaxSlices) return false;
+  if (!enabled) return false;
+#endif
+  if (!cs || !a.orth_table || !a.status || nslice > kCoopMaxSlices) return false;
   // Under stream capture the launch would be replayed with this launch's epoch baked in, and the
   // tags of one replay would be indistinguishable from the next one's: take the per-column path.
   hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
@@ -2445,18 +2442,18 @@ bool launch_orth_coop(int rp, int nslice, int max_rank, const DevArgs& a, int nb
   }
   if (cap != hipStreamCaptureStatusNone) return false;
   switch (rp) {
-    case 1: return try_orth_coop<1>(nslice, max_rank, a, nblocks, epoch, s);
-    case 2: return try_orth_coop<2>(nslice, max_rank, a, nblocks, epoch, s);
-    case 4: return try_orth_coop<4>(nslice, max_rank, a, nblocks, epoch, s);
-    case 8: return try_orth_coop<8>(nslice, max_rank, a, nblocks, epoch, s);
-    case 16: return try_orth_coop<16>(nslice, max_rank, a, nblocks, epoch, s);
-    case 32: return try_orth_coop<32>(nslice, max_rank, a, nblocks, epoch, s);
-    case 64: return try_orth_coop<64>(nslice, max_rank, a, nblocks, epoch, s);
+    case 1: return try_orth_coop<1>(nslice, max_rank, a, nblocks, cs, s);
+    case 2: return try_orth_coop<2>(nslice, max_rank, a, nblocks, cs, s);
+    case 4: return try_orth_coop<4>(nslice, max_rank, a, nblocks, cs, s);
+    case 8: return try_orth_coop<8>(nslice, max_rank, a, nblocks, cs, s);
+    case 16: return try_orth_coop<16>(nslice, max_rank, a, nblocks, cs, s);
+    case 32: return try_orth_coop<32>(nslice, max_rank, a, nblocks, cs, s);
+    case 64: return try_orth_coop<64>(nslice, max_rank, a, nblocks, cs, s);
     default: return false;
   }
 }
 
-hipError_t launch_orth(int rp, int max_rows, int max_rank, const DevArgs& a, unsigned long long* coop_epoch, hipStream_t s) {
+hipError_t launch_orth(int rp, int max_rows, int max_rank, const DevArgs& a, CoopState* coop, hipStream_t s) {
   if (a.L <= 0) return hipSuccess;
   const dim3 grid(a.L * a.W);
   const int nslice = (max_rows + 255) / 256;
@@ -2465,7 +2462,7 @@ hipError_t launch_orth(int rp, int max_rows, int max_rank, const DevArgs& a, uns
   const bool reg_fits = (max_rows <= 512 && rp * 2 <= 128) || (max_rows <= 2048 && rp * 8 <= 64) ||
                         (max_rows <= 4096 && rp * 4 <= 48) || (max_rows <= 11264 && rp * 11 <= 48);
   if (a.orth_part && nslice >= 8 && ((int)grid.x < 128 || !reg_fits)) {
-    if (launch_orth_coop(rp, nslice, max_rank, a, (int)grid.x * nslice, coop_epoch, s)) return hipSuccess;
+    if (launch_orth_coop(rp, nslice, max_rank, a, (int)grid.x * nslice, coop, s)) return hipSuccess;
     for (int j = 0; j <= max_rank; ++j) {
       LQSGD_RP_SWITCH_ORTH(rp, (orth_wide_kernel<RP><<<dim3(grid.x * nslice), dim3(256), 0, s>>>(a, j, nslice)));
     }
@@ -2533,10 +2530,14 @@ hipError_t launch_residual(int rp, int mode, const DevArgs& a, const Tile* tiles
   return hipGetLastError();
 }
 
-// LQSGD_MFMA_NARROW32=0 keeps the 32 x 64 form at rank pad 32 (for comparisons).
+// A tuning build (-DLQSGD_TUNING) can keep the 32 x 64 form at rank pad 32 for comparisons (LQSGD_MFMA_NARROW32=0).
 static bool narrow32() {
+#ifdef LQSGD_TUNING
   static const bool on = [] { const char* e = std::getenv("LQSGD_MFMA_NARROW32"); return !(e && e[0] == '0'); }();
   return on;
+#else
+  return true;
+#endif
 }
 
 template <int RP>
@@ -2594,6 +2595,22 @@ hipError_t launch_mfma_sweep(int rp, int mode, int full_rank, const DevArgs& a, 
   if (rp == 32) return launch_mfma_sweep_rp<32>(mode, full_rank, a, tiles, ntiles, reverse, s);
   if (rp == 64) return launch_mfma_sweep_rp<64>(mode, full_rank, a, tiles, ntiles, reverse, s);
   return hipErrorInvalidValue;
+}
+
+namespace {
+__global__ __launch_bounds__(256) void fill_zero_kernel(uint4* p, size_t n16) {
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256)
+    p[i] = make_uint4(0u, 0u, 0u, 0u);
+}
+}  // namespace
+
+hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s) {
+  if (bytes == 0) return hipSuccess;
+  if ((reinterpret_cast<uintptr_t>(p) | bytes) & 15u) return hipErrorInvalidValue;
+  const size_t n16 = bytes / 16;
+  const unsigned grid = (unsigned)std::min<size_t>(2048, (n16 + 255) / 256);
+  fill_zero_kernel<<<dim3(grid), dim3(256), 0, s>>>(static_cast<uint4*>(p), n16);
+  return hipGetLastError();
 }
 
 hipError_t launch_pad_factor(int RP, int which, const DevArgs& a, hipStream_t s) {

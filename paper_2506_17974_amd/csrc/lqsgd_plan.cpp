@@ -10,12 +10,19 @@ namespace lqsgd {
 
 namespace {
 
+// Work-list sizes below have measured defaults.  Only a build with -DLQSGD_TUNING (for sweeps of
+// these sizes) lets an environment variable override them; the normal build reads no environment.
 int64_t env_i64(const char* name, int64_t dflt) {
+#ifdef LQSGD_TUNING
   const char* s = std::getenv(name);
   if (!s || !*s) return dflt;
   char* end = nullptr;
   long long v = std::strtoll(s, &end, 10);
   return (end && *end == 0 && v > 0) ? (int64_t)v : dflt;
+#else
+  (void)name;
+  return dflt;
+#endif
 }
 
 int pad_rank(int r) {

@@ -16,6 +16,7 @@ constexpr int kRowsPerGroup = 8;   // rows a wavefront carries through one colum
 constexpr int kMfmaCols = 512;     // columns one workgroup of the matrix-core sweep 1 covers (4 waves x 4 strips x 32)
 constexpr int kXGroup = 8;         // elements one lane quantises / packs (b bytes + 1 sign byte)
 constexpr int kXBlockGroups = 32;  // groups of 8 elements one exchange workgroup covers
+constexpr int kFactorSlack = 64;   // readable floats after the last row of every factor buffer (loaders of ranks below their pad overrun)
 
 // One matrix layer as the kernels see it.  Offsets are in elements (floats)
 // from the start of a per-worker slab unless they say bytes.
