@@ -222,6 +222,49 @@ int lqsgd_step(lqsgd_ctx* ctx, const float* const* grads, float* const* ghat);
  *   eta    : learning rate, finite. */
 int lqsgd_step_update(lqsgd_ctx* ctx, const float* const* grads, float* const* params, float eta);
 
+/* One whole iteration, as lqsgd_step, for callers that cannot allocate device
+ * memory or keep a context: code that runs under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  It takes the configuration
+ * and the state with every call, keeps nothing between calls that the caller
+ * must free, and calls no hipMalloc, hipFree or any other allocating routine:
+ * everything lqsgd_create would allocate besides the state -- partial products,
+ * factors, packets, quantiser tables, work lists -- lies in one static block of
+ * device memory inside the library (LQSGD_STATIC_SCRATCH_BYTES, 32 MiB, per GPU,
+ * held until the process ends).  A configuration that needs more returns
+ * EUNSUPPORTED and launches nothing (fc 256 x 128 needs under 0.1 MiB, the small
+ * CNN 7 MiB, the ResNet-18 set at rank 4 and 8 workers 19 MiB).
+ *   cfg, layers, n_layers : as for lqsgd_create (host pointers).
+ *   hip_stream : all work is enqueued here.
+ *   grads, ghat: as for lqsgd_step.
+ *   residual   : device pointer, workers x residual_stride floats (see
+ *                lqsgd_plan_query), 16-byte aligned.  Worker w's E of the i-th
+ *                matrix layer starts at w * residual_stride + off_i, where off_i
+ *                adds up rows x cols of the matrix layers before it in list order,
+ *                each rounded up to a multiple of 64 floats.  Holds E_{t-1} on
+ *                entry (Algorithm 1 starts from zeros) and E_t once the enqueued
+ *                work has run.
+ *   warm_q     : device pointer, warm_q_floats floats, 16-byte aligned.  The Q of
+ *                the i-th matrix layer (cols x r, row-major) starts where the
+ *                cols x r of the layers before it add up to, each rounded up to 64
+ *                floats; the floats after the last layer are slack that the
+ *                kernels may read.  Holds the warm-start Q on entry and the
+ *                aggregated Q of this iteration afterwards.
+ *                Either may be NULL when there is no matrix layer.
+ * The residual update runs at the end of the call's work (never deferred).
+ * Results are bit-identical to lqsgd_step on a context holding the same state.
+ * The first call with a configuration (or stream) other than the previous
+ * call's on that GPU waits for the previous call's stream, lays the block out
+ * anew and copies its tables in with synchronous copies; calls that repeat the
+ * previous configuration only enqueue kernels (plus one small copy when the
+ * pointer lists change).  All calls on a GPU share that GPU's block: two calls
+ * whose work overlaps in time -- different streams, or different threads --
+ * race; a caller that uses more than one stream orders them itself.  The
+ * Gram-Schmidt of tall factors takes its one-launch-per-column form here.
+ * Errors: as lqsgd_create and lqsgd_step; text from lqsgd_last_error(NULL). */
+int lqsgd_step_static(const lqsgd_config* cfg, const lqsgd_layer* layers, int32_t n_layers,
+                      void* hip_stream, const float* const* grads, float* residual, float* warm_q,
+                      float* const* ghat);
+
 /* ---- taps for parity checks and for a transport layer ------------------- */
 
 /* Packet of (phase, layer, worker) as unpacked codes: mag_codes[i] in
@@ -277,6 +320,9 @@ typedef struct {
   int32_t n_matrix, n_vector;
   int32_t rank_pad;          /* register rank the kernels are instantiated for           */
   int32_t tiles[3];          /* work items of the three streaming sweeps                 */
+  int32_t reserved;
+  int64_t residual_stride;   /* floats between two workers' residual slabs (lqsgd_step_static) */
+  int64_t warm_q_floats;     /* floats of the warm-start buffer of lqsgd_step_static      */
 } lqsgd_plan_info;
 
 /* Pure host computation: validates cfg / layers exactly as lqsgd_create does

@@ -29,7 +29,7 @@ SYMBOLS = [
     "lqsgd_get_state", "lqsgd_set_state", "lqsgd_compress", "lqsgd_decompress", "lqsgd_step", "lqsgd_step_update",
     "lqsgd_get_packet", "lqsgd_set_packet", "lqsgd_get_packet_raw", "lqsgd_packet_device", "lqsgd_get_factor",
     "lqsgd_set_factor", "lqsgd_wire_bytes", "lqsgd_plan_query", "lqsgd_plan_tiles",
-    "lqsgd_timing_enable", "lqsgd_timing_read", "lqsgd_kernel_name",
+    "lqsgd_timing_enable", "lqsgd_timing_read", "lqsgd_kernel_name", "lqsgd_step_static",
 ]
 
 
@@ -51,7 +51,8 @@ class Config(C.Structure):
 class PlanInfo(C.Structure):
     _fields_ = [("device_bytes", C.c_int64), ("wire_bytes", C.c_int64), ("matrix_elements", C.c_int64),
                 ("n_matrix", C.c_int32), ("n_vector", C.c_int32), ("rank_pad", C.c_int32),
-                ("tiles", C.c_int32 * 3)]
+                ("tiles", C.c_int32 * 3), ("reserved", C.c_int32),
+                ("residual_stride", C.c_int64), ("warm_q_floats", C.c_int64)]
 
 
 _lib = None
@@ -82,6 +83,7 @@ def lib():
     L.lqsgd_decompress.argtypes = [vp, i32]
     L.lqsgd_step.argtypes = [vp, C.POINTER(vp), C.POINTER(vp)]
     L.lqsgd_step_update.argtypes = [vp, C.POINTER(vp), C.POINTER(vp), C.c_float]
+    L.lqsgd_step_static.argtypes = [C.POINTER(Config), C.POINTER(Layer), i32, vp, C.POINTER(vp), vp, vp, C.POINTER(vp)]
     L.lqsgd_get_packet.argtypes = [vp, i32, i32, i32, u8p, u8p, fp]
     L.lqsgd_set_packet.argtypes = [vp, i32, i32, i32, u8p, u8p, C.c_float]
     L.lqsgd_get_packet_raw.argtypes = [vp, i32, i32, i32, u8p, C.POINTER(i64), u8p, C.POINTER(i64)]
@@ -329,6 +331,31 @@ class Compressor:
         n = (C.c_int64 * KERNEL_COUNT)()
         self._check(lib().lqsgd_timing_read(self._h, ms, n))
         return [float(x) for x in ms], [int(x) for x in n]
+
+
+def step_static(layers, rank, bits_p, bits_q, workers, alpha, flags, grads, residual, warm_q, ghat=None, stream=None):
+    """lqsgd_step_static: one iteration on caller-held state, no device allocation.
+    grads[w][l]: device tensors; residual, warm_q: device tensors laid out as the header says
+    (None when there is no matrix layer); ghat: list over layers of device tensors / None."""
+    import torch
+    cfg = Config(rank, bits_p, bits_q, workers, alpha, flags)
+    n = len(layers)
+    tab = (C.c_void_p * (workers * n))()
+    for w in range(workers):
+        for l in range(n):
+            tab[w * n + l] = grads[w][l].data_ptr()
+    gt = None
+    if ghat is not None:
+        gt = (C.c_void_p * n)()
+        for l, t in enumerate(ghat):
+            gt[l] = t.data_ptr() if t is not None else None
+    if stream is None:
+        stream = torch.cuda.current_stream().cuda_stream
+    rc = lib().lqsgd_step_static(C.byref(cfg), _layers_array(layers), n, C.c_void_p(int(stream)), tab,
+                                 C.c_void_p(residual.data_ptr() if residual is not None else None),
+                                 C.c_void_p(warm_q.data_ptr() if warm_q is not None else None), gt)
+    if rc:
+        raise LqsgdError(rc, lib().lqsgd_last_error(None).decode())
 
 
 def kernel_name(k: int) -> str:

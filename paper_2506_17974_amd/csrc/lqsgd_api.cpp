@@ -372,6 +372,8 @@ int lqsgd_plan_query(const lqsgd_config* cfg, const lqsgd_layer* layers, int32_t
   out->tiles[0] = (int32_t)p.tilesA.size();
   out->tiles[1] = (int32_t)(p.mfma ? p.tilesBM.size() : p.tilesB.size());
   out->tiles[2] = (int32_t)(p.mfma_a ? p.tilesA.size() : p.tilesB.size());
+  out->residual_stride = p.m_stride;
+  out->warm_q_floats = p.q_stride + kFactorSlack;
   return LQSGD_OK;
 }
 
@@ -868,6 +870,95 @@ const char* lqsgd_kernel_name(int32_t kernel) {
     case LQSGD_KERNEL_REDUCE_P: return "reduce_p_kernel";
     default: return "";
   }
+}
+
+// ---- the entry point that allocates nothing ----------------------------------------------------
+namespace {
+// One slot per device: the host-side plan of the last configuration run there, whose device tables
+// still lie in that device's static scratch block.
+struct StaticSlot {
+  lqsgd_ctx* ctx = nullptr;
+  lqsgd_config cfg{};
+  std::vector<lqsgd_layer> layers;
+};
+constexpr int kMaxDevices = 64;
+StaticSlot g_static[kMaxDevices];
+std::mutex g_static_mu;
+
+bool same_config(const StaticSlot& s, const lqsgd_config* cfg, const lqsgd_layer* layers, int32_t n, hipStream_t stream) {
+  if (!s.ctx || s.ctx->stream != stream || (int32_t)s.layers.size() != n) return false;
+  if (s.cfg.rank != cfg->rank || s.cfg.bits_p != cfg->bits_p || s.cfg.bits_q != cfg->bits_q ||
+      s.cfg.workers != cfg->workers || s.cfg.alpha != cfg->alpha || s.cfg.flags != cfg->flags)
+    return false;
+  for (int32_t i = 0; i < n; ++i)
+    if (s.layers[i].rows != layers[i].rows || s.layers[i].cols != layers[i].cols || s.layers[i].flags != layers[i].flags)
+      return false;
+  return true;
+}
+}  // namespace
+
+int lqsgd_step_static(const lqsgd_config* cfg, const lqsgd_layer* layers, int32_t n_layers, void* hip_stream,
+                      const float* const* grads, float* residual, float* warm_q, float* const* ghat) {
+  if (!cfg || !layers) return fail(nullptr, LQSGD_EINVAL, "NULL config or layer list");
+  if (!grads) return fail(nullptr, LQSGD_EINVAL, "NULL gradient list");
+  std::lock_guard<std::mutex> lock(g_static_mu);
+  int dev = 0;
+  {
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail_hip(nullptr, e, "hipGetDevice");
+  }
+  if (dev < 0 || dev >= kMaxDevices) return fail(nullptr, LQSGD_EUNSUPPORTED, "device index beyond the table of static scratch blocks");
+  void* block = nullptr;
+  size_t block_bytes = 0;
+  {
+    hipError_t e = static_scratch(dev, &block, &block_bytes);
+    if (e != hipSuccess) return fail_hip(nullptr, e, "hipGetSymbolAddress(scratch)");
+  }
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  StaticSlot& slot = g_static[dev];
+  if (!same_config(slot, cfg, layers, n_layers, stream)) {
+    // A new configuration lays the block out anew: whatever the last one enqueued must have finished.
+    if (slot.ctx) {
+      (void)hipStreamSynchronize(slot.ctx->stream);
+      (void)hipGetLastError();
+      delete slot.ctx;
+      slot.ctx = nullptr;
+    }
+    lqsgd_ctx* c = new (std::nothrow) lqsgd_ctx();
+    if (!c) return fail(nullptr, LQSGD_ENOMEM, "out of host memory");
+    int rc = c->plan.build(cfg, layers, n_layers);
+    if (rc) {
+      g_create_error = c->plan.err;
+      delete c;
+      return rc;
+    }
+    c->stream = stream;
+    c->arena = static_cast<unsigned char*>(block);
+    c->arena_cap = block_bytes;
+    if ((rc = setup_device(c, cfg->flags))) {
+      g_create_error = c->err;
+      delete c;
+      return rc;
+    }
+    slot.ctx = c;
+    slot.cfg = *cfg;
+    slot.layers.assign(layers, layers + n_layers);
+  }
+  lqsgd_ctx* c = slot.ctx;
+  const bool has_matrix = c->plan.L > 0;
+  if (has_matrix && (!residual || !warm_q)) { g_create_error = "NULL residual or warm-start buffer"; return LQSGD_EINVAL; }
+  if ((reinterpret_cast<uintptr_t>(residual) | reinterpret_cast<uintptr_t>(warm_q)) & 15u) {
+    g_create_error = "residual / warm-start buffer not 16-byte aligned";
+    return LQSGD_EINVAL;
+  }
+  c->args.E = residual;
+  c->args.Qbar = warm_q;
+  c->pending = false;                        // the caller's buffer holds E, and holds E again on return
+  c->ppad_stale = c->qpad_stale = true;      // the warm-start Q is the caller's: any padded copy is out of date
+  c->state = kIdle;
+  const int rc = step_impl(c, grads, ghat);
+  if (rc) g_create_error = c->err;
+  return rc;
 }
 
 }  // extern "C"

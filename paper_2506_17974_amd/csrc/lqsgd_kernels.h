@@ -81,6 +81,12 @@ hipError_t launch_residual(int RP, int mode, const DevArgs& a, const Tile* tiles
 // Refreshes a.Ppad (which = 0) or a.Qpad (which = 1) from the tightly packed factor.
 hipError_t launch_pad_factor(int RP, int which, const DevArgs& a, hipStream_t s);
 
+// The per-GPU scratch block of the entry point that allocates nothing: device address and size of
+// the block of `device`, which must be the current device on the first call for it.
+#ifndef LQSGD_STATIC_SCRATCH_BYTES
+#define LQSGD_STATIC_SCRATCH_BYTES (32u << 20)
+#endif
+hipError_t static_scratch(int device, void** ptr, size_t* bytes);
 // Clears `bytes` (a multiple of 16) at the 16-byte aligned device address p with a kernel.
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);
 

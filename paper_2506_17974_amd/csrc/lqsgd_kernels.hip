@@ -25,6 +25,11 @@
 #include <cstdlib>
 #include <type_traits>
 
+// Scratch block of lqsgd_step_static (see static_scratch() below): device memory that is part of
+// the code object, one copy per GPU.  In host code this name is a handle for hipGetSymbolAddress,
+// never an address.
+static __device__ __align__(256) unsigned char scratch[LQSGD_STATIC_SCRATCH_BYTES];
+
 namespace lqsgd {
 namespace {
 
@@ -2595,6 +2600,35 @@ hipError_t launch_mfma_sweep(int rp, int mode, int full_rank, const DevArgs& a, 
   if (rp == 32) return launch_mfma_sweep_rp<32>(mode, full_rank, a, tiles, ntiles, reverse, s);
   if (rp == 64) return launch_mfma_sweep_rp<64>(mode, full_rank, a, tiles, ntiles, reverse, s);
   return hipErrorInvalidValue;
+}
+
+// ---------------------------------------------------------------------------
+// Scratch memory for the entry point that allocates nothing: one block per GPU,
+// part of the loaded code object, held until the process ends.  The name below
+// is a host-side handle only; the block's device address is asked for once per
+// device and that address is what kernels and copies use.  (The array itself
+// is defined at file scope, at the top of this file.)
+// ---------------------------------------------------------------------------
+constexpr size_t kStaticScratchBytes = (size_t)LQSGD_STATIC_SCRATCH_BYTES;
+
+hipError_t static_scratch(int device, void** ptr, size_t* bytes) {
+  constexpr int kMaxDev = 64;
+  static void* addr[kMaxDev] = {};              // per device; the caller serialises calls
+  if (device < 0 || device >= kMaxDev) return hipErrorInvalidDevice;
+  if (!addr[device]) {
+    int cur = -1;
+    hipError_t e = hipGetDevice(&cur);
+    if (e != hipSuccess) return e;
+    if (cur != device) return hipErrorInvalidDevice;     // the address belongs to the device that is current
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    addr[device] = p;
+  }
+  *ptr = addr[device];
+  *bytes = kStaticScratchBytes;
+  return hipSuccess;
 }
 
 namespace {
