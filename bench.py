@@ -30,11 +30,11 @@ def sweep_bytes(kernel, w, ghat, eager, bf16=False):
     written, 1 = stored, 2 = applied to the parameters (read w, write w)."""
     e1 = w.elements_per_worker
     e = w.workers * e1
-    if kernel == "add_project_kernel":
+    if kernel == "sweep0_add_project":
         return (10.0 if bf16 else 12.0) * e
-    if kernel == "back_project_kernel":
+    if kernel == "sweep1_back_project":
         return 4.0 * e
-    if kernel == "residual_kernel":
+    if kernel == "sweep2_residual_ghat":
         return (8.0 * e if eager else 0.0) + 4.0 * e1 * ghat
     return None
 
@@ -64,6 +64,9 @@ def main():
                     help="hand the gradients over in bfloat16 (the first sweep then reads 10 instead of 12 bytes per element)")
     ap.add_argument("--update", type=float, default=None, metavar="ETA",
                     help="apply w <- w - ETA G-hat to synthetic parameters inside the step instead of storing G-hat")
+    ap.add_argument("--no-cooperative-launch", action="store_true",
+                    help="the Gram-Schmidt of tall factors takes its one-launch-per-column form instead of one "
+                         "cooperative launch (for runs under rocprofv3, whose exit handler crashes after a cooperative launch)")
     ap.add_argument("--graph", action="store_true",
                     help="record one step into a HIP graph and time replays of it (for the small, launch-bound sets)")
     ap.add_argument("--rank-sweep", action="store_true",
@@ -124,7 +127,8 @@ def main():
     comp = B.Compressor(B.layer_list(w.layers, w.vectors), w.rank, w.bits, w.bits, W, w.alpha,
                         (B.FLAG_EAGER_RESIDUAL if args.eager else 0) |
                         (B.FLAG_AGGREGATE_FIRST if args.aggregate_first else 0) |
-                        (B.FLAG_BF16_GRADIENTS if args.bf16_grads else 0),
+                        (B.FLAG_BF16_GRADIENTS if args.bf16_grads else 0) |
+                        (B.FLAG_NO_COOPERATIVE_LAUNCH if args.no_cooperative_launch else 0),
                         stream=side.cuda_stream if side is not None else None)
     q0 = [wl.initial_q(w, l) for l in range(L)]
     for l in range(L):
@@ -179,15 +183,20 @@ def main():
         elems = W * w.elements_per_worker
         for k in range(B.KERNEL_COUNT):
             if cnt[k]:
-                name = B.kernel_name(k) + ("_q" if k == B.KERNEL_EXCHANGE_Q else "_p" if k == B.KERNEL_EXCHANGE_P else "")
-                kernels[name] = {"avg_us": 1e3 * ms[k] / cnt[k], "launches": cnt[k]}
+                # keyed by the stage of the iteration; "function" is the device function that served it
+                # (template arguments included, as rocprofv3's kernel list names it)
+                kernels[B.kernel_name(k)] = {"function": comp.launched_kernel(k), "avg_us": 1e3 * ms[k] / cnt[k],
+                                             "launches": cnt[k]}
         dom = max((k for k in kernels), key=lambda n: kernels[n]["avg_us"])
         alg = sweep_bytes(dom, w, ghat_mode, args.eager, args.bf16_grads)
         if alg:
             achieved = alg / (kernels[dom]["avg_us"] * 1e-6) / 1e9
-            roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-                        "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                        "traffic": _measured_traffic(dom, "%s_r%d_b%d_W%d" % (w.name, w.rank, w.bits, W)),
+            traffic = _measured_traffic(dom, "%s_r%d_b%d_W%d" % (w.name, w.rank, w.bits, W))
+            roofline = {"bound": "hbm", "kernel": kernels[dom]["function"], "stage": dom, "achieved": round(achieved, 1),
+                        "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                        "traffic": traffic,
+                        "traffic_source": ("rocprofv3 FETCH_SIZE + WRITE_SIZE counter runs committed under profiles/ "
+                                           "(hbm_traffic.txt), not measured by this run") if traffic else None,
                         "algorithmic_bytes_per_launch": alg,
                         "avg_launch_us": round(kernels[dom]["avg_us"], 2)}
         for n, d in kernels.items():
@@ -202,7 +211,7 @@ def main():
         cpu = _cpu_baseline(w, grads, q0)
 
     step_bytes = sum(sweep_bytes(k, w, ghat_mode, args.eager, args.bf16_grads)
-                     for k in ("add_project_kernel", "back_project_kernel", "residual_kernel"))
+                     for k in ("sweep0_add_project", "sweep1_back_project", "sweep2_residual_ghat"))
     out = {
         "metric": "compressed gradient GB/s per LQ-SGD step (ResNet-18 set, r=4) and % HBM peak",
         "value": round(value, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -216,6 +225,7 @@ def main():
                    "gradient_dtype": "bf16" if args.bf16_grads else "f32",
                    "launch": "replays of a HIP graph holding one step" if args.graph else "eager launches",
                    "order": "aggregate, then orthonormalise" if args.aggregate_first else "orthonormalise, then aggregate (Algorithm 1)",
+                   "cooperative_launch": not args.no_cooperative_launch,
                    "rank": w.rank, "bits": w.bits, "workers": W, "gradient_bytes_per_step": grad_bytes},
         "step_algorithmic_bytes": step_bytes,
         "step_hbm_frac": round(step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),

@@ -87,6 +87,14 @@ typedef struct {
  * everything after that, the state and the outputs are fp32 as always.  The
  * first sweep then reads 2 bytes per element less. */
 #define LQSGD_FLAG_BF16_GRADIENTS 4u
+/* Never launch a kernel cooperatively.  The Gram-Schmidt of tall factors with few
+ * (layer, worker) pairs normally runs as one cooperative launch whose workgroups
+ * exchange partial sums while it runs; with this flag it takes its
+ * one-launch-per-column form (same bits, slower: 1.3 ms instead of 0.3 ms at
+ * 8192 rows, rank 32, 16 workers).  For processes in which cooperative launches
+ * are unwelcome -- e.g. under rocprofv3, whose exit handler has been seen to
+ * crash after the process has made one. */
+#define LQSGD_FLAG_NO_COOPERATIVE_LAUNCH 8u
 
 /* The "Require" line of Algorithm 1, plus the number of simulated workers. */
 typedef struct {
@@ -232,7 +240,7 @@ int lqsgd_step_update(lqsgd_ctx* ctx, const float* const* grads, float* const* p
  * device memory inside the library (LQSGD_STATIC_SCRATCH_BYTES, 32 MiB, per GPU,
  * held until the process ends).  A configuration that needs more returns
  * EUNSUPPORTED and launches nothing (fc 256 x 128 needs under 0.1 MiB, the small
- * CNN 7 MiB, the ResNet-18 set at rank 4 and 8 workers 19 MiB).
+ * CNN 1 MiB, the ResNet-18 set with 8 workers 9 MiB at rank 4 and 17 MiB at rank 8).
  *   cfg, layers, n_layers : as for lqsgd_create (host pointers).
  *   hip_stream : all work is enqueued here.
  *   grads, ghat: as for lqsgd_step.
@@ -358,8 +366,14 @@ int lqsgd_timing_enable(lqsgd_ctx* ctx, int32_t on);
  * lqsgd_timing_enable: total_ms[k] and launches[k] for k < LQSGD_KERNEL_COUNT
  * (host pointers to arrays of that length). */
 int lqsgd_timing_read(lqsgd_ctx* ctx, double* total_ms, int64_t* launches);
-/* Name of the device function behind a LQSGD_KERNEL_* id (as a profiler shows it). */
+/* Name of a LQSGD_KERNEL_* timing slot: the stage of the iteration, not a device
+ * function (which function serves a stage depends on rank, shapes and flags). */
 const char* lqsgd_kernel_name(int32_t kernel);
+/* The device function this context launched last for that slot, with its template
+ * arguments, as a profiler's kernel list names it (namespaces and the parameter
+ * list left out), e.g. "add_project_kernel<4, true, false, false>"; "" before
+ * the first launch.  Valid until the next launch for that slot. */
+const char* lqsgd_launched_kernel(const lqsgd_ctx* ctx, int32_t kernel);
 
 #ifdef __cplusplus
 }

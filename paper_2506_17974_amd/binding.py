@@ -15,7 +15,7 @@ LIB_PATH = os.environ.get("LQSGD_LIB") or os.path.join(_HERE, "liblqsgd.so")
 
 OK, EINVAL, ESHAPE, EUNSUPPORTED, ENOMEM, EHIP, ESTATE = 0, -1, -2, -3, -4, -5, -6
 LAYER_MATRIX, LAYER_VECTOR = 0, 1
-FLAG_NONE, FLAG_EAGER_RESIDUAL, FLAG_AGGREGATE_FIRST, FLAG_BF16_GRADIENTS = 0, 1, 2, 4
+FLAG_NONE, FLAG_EAGER_RESIDUAL, FLAG_AGGREGATE_FIRST, FLAG_BF16_GRADIENTS, FLAG_NO_COOPERATIVE_LAUNCH = 0, 1, 2, 4, 8
 PHASE_P, PHASE_Q = 0, 1
 FACTOR_P_PRE, FACTOR_P_ORTH, FACTOR_P_BAR, FACTOR_Q_W, FACTOR_Q_BAR, FACTOR_VMEAN, FACTOR_P_MEAN = range(7)
 (KERNEL_ADD_PROJECT, KERNEL_ORTH, KERNEL_EXCHANGE_P, KERNEL_BACK_PROJECT, KERNEL_REDUCE_Q,
@@ -29,7 +29,7 @@ SYMBOLS = [
     "lqsgd_get_state", "lqsgd_set_state", "lqsgd_compress", "lqsgd_decompress", "lqsgd_step", "lqsgd_step_update",
     "lqsgd_get_packet", "lqsgd_set_packet", "lqsgd_get_packet_raw", "lqsgd_packet_device", "lqsgd_get_factor",
     "lqsgd_set_factor", "lqsgd_wire_bytes", "lqsgd_plan_query", "lqsgd_plan_tiles",
-    "lqsgd_timing_enable", "lqsgd_timing_read", "lqsgd_kernel_name", "lqsgd_step_static",
+    "lqsgd_timing_enable", "lqsgd_timing_read", "lqsgd_kernel_name", "lqsgd_launched_kernel", "lqsgd_step_static",
 ]
 
 
@@ -100,6 +100,8 @@ def lib():
     L.lqsgd_timing_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64)]
     L.lqsgd_kernel_name.argtypes = [i32]
     L.lqsgd_kernel_name.restype = C.c_char_p
+    L.lqsgd_launched_kernel.argtypes = [vp, i32]
+    L.lqsgd_launched_kernel.restype = C.c_char_p
     _lib = L
     return L
 
@@ -325,6 +327,10 @@ class Compressor:
     # -- timing ----------------------------------------------------------
     def timing_enable(self, on=True):
         self._check(lib().lqsgd_timing_enable(self._h, 1 if on else 0))
+
+    def launched_kernel(self, k: int) -> str:
+        """Device function last launched for timing slot k (template arguments included)."""
+        return lib().lqsgd_launched_kernel(self._h, k).decode()
 
     def timing_read(self):
         ms = (C.c_double * KERNEL_COUNT)()

@@ -55,5 +55,30 @@ def build(verbose: bool = True, extra=(), out: str = LIB) -> str:
     return out
 
 
+def build_host_sanitize(verbose: bool = True) -> str:
+    """The planner and the argument-checking half of the ABI as a host-only program with
+    AddressSanitizer and UndefinedBehaviorSanitizer: lqsgd_plan.cpp and lqsgd_api.cpp compiled for
+    the CPU, the kernel launchers replaced by stand-ins, csrc/host_check.cpp as its main.  No device
+    code is built or sanitized.  Returns the path of the executable; it needs no GPU."""
+    bdir = os.path.join(HERE, "_build")
+    os.makedirs(bdir, exist_ok=True)
+    out = os.path.join(bdir, "lqsgd_host_check")
+    srcs = [os.path.join(CSRC, f) for f in ("lqsgd_plan.cpp", "lqsgd_api.cpp", "host_check_stubs.cpp", "host_check.cpp")]
+    cmd = [hipcc(), "-O1", "-g", "-std=c++17", "-fno-omit-frame-pointer", "-fsanitize=address,undefined",
+           "-fno-sanitize-recover=undefined", "-fno-gpu-sanitize", "-Wall", "-Wno-unused-command-line-argument",
+           "-I", os.path.join(ROOT, "include"), "-I", CSRC] + srcs + ["-o", out]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    p = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if p.returncode != 0:
+        raise RuntimeError("host sanitizer build failed:\n" + p.stdout)
+    return out
+
+
 if __name__ == "__main__":
+    if "--sanitize" in sys.argv[1:]:
+        exe = build_host_sanitize()
+        # the HIP runtime's own start-up allocations are not this library's: no leak report at exit
+        env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1")
+        sys.exit(subprocess.call([exe], env=env))
     build(extra=sys.argv[1:])

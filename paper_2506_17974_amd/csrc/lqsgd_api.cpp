@@ -61,6 +61,7 @@ struct lqsgd_ctx {
   bool ppad_stale = true, qpad_stale = true;   // the padded copies of P-bar / Q-bar lag behind the factors
   bool alias_checked = false;   // the bound gradient and output tables have been checked against each other
   // timing
+  std::string launched[LQSGD_KERNEL_COUNT];   // device function last launched for each timing slot
   bool timing = false;
   std::vector<EventPair> events;
   size_t events_used = 0;
@@ -125,8 +126,9 @@ int dev_upload(lqsgd_ctx* c, T** out, const std::vector<T>& v) {
 
 struct Timed {
   lqsgd_ctx* c;
+  int kernel;
   EventPair* ep = nullptr;
-  Timed(lqsgd_ctx* ctx, int kernel) : c(ctx) {
+  Timed(lqsgd_ctx* ctx, int k) : c(ctx), kernel(k) {
     if (!c->timing) return;
     if (c->events_used == c->events.size()) {
       EventPair p{};
@@ -139,6 +141,7 @@ struct Timed {
   }
   ~Timed() {
     if (ep) (void)hipEventRecord(ep->b, c->stream);
+    c->launched[kernel] = last_launched_kernel();
   }
 };
 
@@ -225,6 +228,11 @@ int refresh_padded(lqsgd_ctx* c, bool need_p, bool need_q) {
 }
 int full_rank(const lqsgd_ctx* c) { return (c->plan.max_rank == c->plan.RP || c->plan.padded) ? 1 : 0; }
 
+// The one-launch Gram-Schmidt's state, or null where the context must not launch cooperatively.
+CoopState* coop_state(lqsgd_ctx* c) {
+  return (c->plan.cfg.flags & LQSGD_FLAG_NO_COOPERATIVE_LAUNCH) ? nullptr : &c->coop;
+}
+
 int run_sweep0(lqsgd_ctx* c) {
   if (c->plan.mfma_a)
     if (int rc = refresh_padded(c, c->pending, true)) return rc;
@@ -241,7 +249,7 @@ int run_sweep0(lqsgd_ctx* c) {
     HIP_TRY(c, launch_reduce_q(0, c->args, c->d_tilesRP, (int)c->plan.tilesRP.size(), c->stream));
   } else {
     Timed t(c, LQSGD_KERNEL_ORTH);
-    HIP_TRY(c, launch_orth(c->plan.RP, c->plan.max_rows, c->plan.max_rank, c->args, &c->coop, c->stream));
+    HIP_TRY(c, launch_orth(c->plan.RP, c->plan.max_rows, c->plan.max_rank, c->args, coop_state(c), c->stream));
   }
   return LQSGD_OK;
 }
@@ -255,7 +263,7 @@ int run_orth_shared(lqsgd_ctx* c) {
   a.Ppart = c->args.Pbar; a.ppart_stride = 0;
   a.Ppre = c->args.Porth;
   a.Porth = c->args.Pbar;
-  HIP_TRY(c, launch_orth(c->plan.RP, c->plan.max_rows, c->plan.max_rank, a, &c->coop, c->stream));
+  HIP_TRY(c, launch_orth(c->plan.RP, c->plan.max_rows, c->plan.max_rank, a, coop_state(c), c->stream));
   c->ppad_stale = true;
   return LQSGD_OK;
 }
@@ -278,7 +286,8 @@ int run_sweep1(lqsgd_ctx* c, bool with_vectors) {
     else
       HIP_TRY(c, launch_back_project(c->plan.RP, c->args, c->d_tilesB, (int)c->plan.tilesB.size(), c->d_tilesV, nv,
                                      next_dir(c), c->stream)); }
-  { Timed t(c, LQSGD_KERNEL_REDUCE_Q);
+  if (!c->plan.tilesRQ.empty()) {      // layers whose sweep-1 items each cover all rows have stored Q_w themselves
+    Timed t(c, LQSGD_KERNEL_REDUCE_Q);
     HIP_TRY(c, launch_reduce_q(1, c->args, c->d_tilesRQ, (int)c->plan.tilesRQ.size(), c->stream)); }
   return LQSGD_OK;
 }
@@ -858,16 +867,21 @@ int lqsgd_timing_read(lqsgd_ctx* c, double* total_ms, int64_t* launches) {
   return LQSGD_OK;
 }
 
+const char* lqsgd_launched_kernel(const lqsgd_ctx* c, int32_t kernel) {
+  if (!c || kernel < 0 || kernel >= LQSGD_KERNEL_COUNT) return "";
+  return c->launched[kernel].c_str();
+}
+
 const char* lqsgd_kernel_name(int32_t kernel) {
   switch (kernel) {
-    case LQSGD_KERNEL_ADD_PROJECT: return "add_project_kernel";
-    case LQSGD_KERNEL_ORTH: return "orth_kernel";
-    case LQSGD_KERNEL_EXCHANGE_P: return "exchange_kernel";
-    case LQSGD_KERNEL_BACK_PROJECT: return "back_project_kernel";
-    case LQSGD_KERNEL_REDUCE_Q: return "reduce_q_kernel";
-    case LQSGD_KERNEL_EXCHANGE_Q: return "exchange_kernel";
-    case LQSGD_KERNEL_RESIDUAL: return "residual_kernel";
-    case LQSGD_KERNEL_REDUCE_P: return "reduce_p_kernel";
+    case LQSGD_KERNEL_ADD_PROJECT: return "sweep0_add_project";
+    case LQSGD_KERNEL_ORTH: return "gram_schmidt";
+    case LQSGD_KERNEL_EXCHANGE_P: return "exchange_p";
+    case LQSGD_KERNEL_BACK_PROJECT: return "sweep1_back_project";
+    case LQSGD_KERNEL_REDUCE_Q: return "reduce_q";
+    case LQSGD_KERNEL_EXCHANGE_Q: return "exchange_q";
+    case LQSGD_KERNEL_RESIDUAL: return "sweep2_residual_ghat";
+    case LQSGD_KERNEL_REDUCE_P: return "reduce_p";
     default: return "";
   }
 }

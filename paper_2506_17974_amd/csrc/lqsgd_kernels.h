@@ -46,6 +46,10 @@ struct DevArgs {
 
 enum ExchangeMode { kQuantOnly = 0, kMeanOnly = 1, kFused = 2 };
 
+// The device function the calling thread's most recent launcher call has launched, with its
+// template arguments, as a profiler's kernel list names it (namespaces and parameters left out).
+const char* last_launched_kernel();
+
 // Each launcher enqueues one kernel on `s` and returns hipGetLastError().
 // `reverse` walks the work list backwards: consecutive sweeps alternate direction so that
 // each one starts on the data the previous one touched last (still in the memory-side cache).
@@ -62,7 +66,8 @@ struct CoopState {
 // coop: NULL disables the one-launch form.
 hipError_t launch_orth(int RP, int max_rows, int max_rank, const DevArgs& a, CoopState* coop, hipStream_t s);
 hipError_t launch_exchange(int mode, int phase, const DevArgs& a, const XTile* tiles, int ntiles, hipStream_t s);
-// Sweep 1 also runs the plain mean of the 1-D tensors (nvtiles extra workgroups).
+// Sweep 1 also runs the plain mean of the 1-D tensors (nvtiles extra workgroups).  Layers whose
+// items cover all their rows (LayerDesc::direct_q) get Q_w and its absmax from this sweep itself.
 hipError_t launch_back_project(int RP, const DevArgs& a, const Tile* tiles, int ntiles, const VTile* vtiles, int nvtiles,
                                int reverse, hipStream_t s);
 // The same sweep on the matrix cores (rank pad 32 or 64; tiles are row block x 512-column group).

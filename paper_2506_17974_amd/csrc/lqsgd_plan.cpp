@@ -64,7 +64,7 @@ int Plan::build(const lqsgd_config* c, const lqsgd_layer* ls, int32_t n_layers) 
     return LQSGD_EINVAL;
   }
   if (!(c->alpha > 0.0f) || !std::isfinite(c->alpha)) { err = "alpha must be finite and > 0"; return LQSGD_EINVAL; }
-  if (c->flags & ~(LQSGD_FLAG_EAGER_RESIDUAL | LQSGD_FLAG_AGGREGATE_FIRST | LQSGD_FLAG_BF16_GRADIENTS)) { err = "unknown config flags"; return LQSGD_EINVAL; }
+  if (c->flags & ~(LQSGD_FLAG_EAGER_RESIDUAL | LQSGD_FLAG_AGGREGATE_FIRST | LQSGD_FLAG_BF16_GRADIENTS | LQSGD_FLAG_NO_COOPERATIVE_LAUNCH)) { err = "unknown config flags"; return LQSGD_EINVAL; }
   agg_first = (c->flags & LQSGD_FLAG_AGGREGATE_FIRST) != 0;
   cfg = *c;
   W = c->workers;
@@ -165,6 +165,15 @@ int Plan::build(const lqsgd_config* c, const lqsgd_layer* ls, int32_t n_layers) 
     // equal blocks: 8192 rows in blocks of 1536 would end in a block of 512
     rbb_v = (int32_t)std::min<int64_t>(rbb_v, round_up((d.rows + nrb_v - 1) / nrb_v, 4));
     nrb_v = (d.rows + rbb_v - 1) / rbb_v;
+    // Layers of moderate height take one row block per column chunk: sweep 1 then writes Q_w itself
+    // (no partial planes, no reduce pass for this layer), and measured on the ResNet-18-shaped set
+    // it streams as fast with 512-row items as with 128-row ones (63 us either way).
+    // Not where that would leave the launch with too few items: at most four times the size the
+    // work list aims for (a 1024-row layer of a small set keeps its row blocks).
+    if (!mfma && (int64_t)d.rows * cw <= env_i64("LQSGD_DIRECT_Q_MAX", 262144) && d.rows <= 4 * rbb) {
+      rbb_v = (int32_t)round_up(d.rows, 4);
+      nrb_v = 1;
+    }
     // the partial planes of Q belong to whichever kernel runs sweep 1
     if (mfma) {
       const int64_t rbm = env_i64("LQSGD_TILE_BM", std::min<int64_t>(2048, std::max<int64_t>(256, total / (49152 * 16))));
@@ -173,13 +182,14 @@ int Plan::build(const lqsgd_config* c, const lqsgd_layer* ls, int32_t n_layers) 
       d.rbb = rbb_v;
     }
     d.nrb = (d.rows + d.rbb - 1) / d.rbb;
+    d.direct_q = (!mfma && d.nrb == 1) ? 1 : 0;
     const int nchunk = (d.cols + cw - 1) / cw;
 
     d.m_off = m_acc;   m_acc += round_up((int64_t)d.rows * d.cols, 64);
     d.p_off = p_acc;   p_acc += round_up(d.np_el, 64);
     d.q_off = q_acc;   q_acc += round_up(d.nq_el, 64);
     d.ppart_off = pp_acc; pp_acc += (int64_t)d.nseg * d.np_pad;
-    d.qpart_off = qp_acc; qp_acc += (int64_t)d.nrb * d.nq_pad;
+    d.qpart_off = qp_acc; qp_acc += d.direct_q ? 0 : (int64_t)d.nrb * d.nq_pad;   // no partial planes where sweep 1 stores Q_w itself
     d.ppad_off = ppd_acc; ppd_acc += round_up((int64_t)d.rows * RP, 64);
     d.qpad_off = qpd_acc; qpd_acc += round_up((int64_t)d.cols * RP, 64);
     if (mfma_a && d.vec == 4 && d.r < RP && env_i64("LQSGD_NO_PAD_OPERANDS", 0) == 0) padded = true;
@@ -212,7 +222,8 @@ int Plan::build(const lqsgd_config* c, const lqsgd_layer* ls, int32_t n_layers) 
         for (int32_t rb = 0; rb < d.nrb; ++rb)
           for (int32_t cg = 0; cg < (d.cols + kMfmaCols - 1) / kMfmaCols; ++cg)
             tilesBM.push_back(Tile{lw, rb * d.rbb, std::min(d.rbb, d.rows - rb * d.rbb), cg});
-      for (int32_t e = 0; e < d.nq_el; e += 1024) tilesRQ.push_back(RTile{lw, e});
+      if (!d.direct_q)
+        for (int32_t e = 0; e < d.nq_el; e += 1024) tilesRQ.push_back(RTile{lw, e});
       if (agg_first)
         for (int32_t e = 0; e < d.np_el; e += 1024) tilesRP.push_back(RTile{lw, e});
     }

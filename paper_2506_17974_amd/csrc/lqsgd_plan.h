@@ -27,7 +27,7 @@ struct LayerDesc {
   int32_t gidx;                 // position in the caller's tensor list
   int32_t np_el, nq_el;         // rows*r, cols*r
   int32_t np_pad, nq_pad;       // the same rounded up to 16 elements (stride of the partial planes)
-  int32_t pad0;
+  int32_t direct_q;             // sweep 1 covers all rows in one block and writes Q_w (and its absmax) itself: no partial planes, no reduce
   int64_t m_off;                // into E / M          (worker stride m_stride)
   int64_t p_off;                // into rows x r slabs (worker stride p_stride)
   int64_t q_off;                // into cols x r slabs (worker stride q_stride)

@@ -346,8 +346,10 @@ def test_three_steps_twice_give_the_same_bits(layers, rank, W):
     Q0 = [rng.standard_normal((c, min(rank, r, c))).astype(f32) for r, c in layers]
     Gs = [pu.to_device(_random_inputs(rng, layers, W)) for _ in range(3)]
     runs = []
-    for _ in range(2):
-        comp, ml = _make(layers, (), rank, 8, 8, W)
+    for rep in range(2):
+        # the second run must not launch cooperatively: the tall factor's Gram-Schmidt then takes its
+        # one-launch-per-column form, which has to give the same bits as the one-launch form
+        comp, ml = _make(layers, (), rank, 8, 8, W, flags=B.FLAG_NO_COOPERATIVE_LAUNCH if rep else 0)
         for l in ml:
             comp.set_q(l, Q0[l])
         ghat = [torch.empty(s, device="cuda") for s in layers]

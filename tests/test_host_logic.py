@@ -34,7 +34,7 @@ def test_kernel_names():
     (dict(alpha=0.0), B.EINVAL), (dict(alpha=float("nan")), B.EINVAL),
     (dict(layers=[(0, 4, 0)]), B.ESHAPE), (dict(layers=[(4, -1, 0)]), B.ESHAPE),
     (dict(layers=[(65536, 65536, 0)]), B.ESHAPE), (dict(layers=[(8, 2, B.LAYER_VECTOR)]), B.ESHAPE),
-    (dict(layers=[(8, 2, 4)]), B.EINVAL), (dict(flags=8), B.EINVAL),
+    (dict(layers=[(8, 2, 4)]), B.EINVAL), (dict(flags=16), B.EINVAL),
 ])
 def test_plan_rejects_bad_arguments(kw, code):
     args = dict(layers=[(16, 8, 0)], rank=2, bits_p=8, bits_q=8, workers=2, alpha=255.0)
@@ -119,7 +119,8 @@ def test_compressor_refuses_to_run_without_gpu():
 
 
 @pytest.mark.parametrize("flags", [0, B.FLAG_EAGER_RESIDUAL, B.FLAG_AGGREGATE_FIRST, B.FLAG_BF16_GRADIENTS,
-                                   B.FLAG_EAGER_RESIDUAL | B.FLAG_AGGREGATE_FIRST | B.FLAG_BF16_GRADIENTS])
+                                   B.FLAG_NO_COOPERATIVE_LAUNCH,
+                                   B.FLAG_EAGER_RESIDUAL | B.FLAG_AGGREGATE_FIRST | B.FLAG_BF16_GRADIENTS | B.FLAG_NO_COOPERATIVE_LAUNCH])
 def test_plan_accepts_every_flag_combination(flags):
     w = wl.small_cnn()
     info = B.plan_query(B.layer_list(w.layers, w.vectors), 4, 8, 8, 4, flags=flags)
