@@ -183,7 +183,10 @@ int lqsgd_set_state(lqsgd_ctx* ctx, int32_t layer, int32_t worker, const float* 
 /* grads: host array of workers * n_layers device pointers,
  * grads[w * n_layers + l] -> fp32 tensor of layer l on worker w, 16-byte
  * aligned, read-only.  The pointer values are copied; the array itself need
- * not outlive the call.
+ * not outlive the call.  The context keeps a device copy of the list: a call
+ * whose list (or G-hat / parameter list) differs from the previous call's waits
+ * for the context's stream, then copies the new list to the device
+ * (synchronously); a call that repeats the previous lists only enqueues kernels.
  *
  * lqsgd_compress(PHASE_P, grads): for every matrix layer and worker
  *     M_w = G_w + E_w (kept in the context, Eq. (9)); P_w = M_w Q;

@@ -185,3 +185,39 @@ def test_resume_from_saved_state_is_bit_identical(name, rank, flags):
             e2, q2 = second.get_state(l, k)
             assert np.array_equal(e1, e2) and np.array_equal(q1, q2), (l, k)
     ref.close(); second.close()
+
+
+# ---------------------------------------------------------------------------
+# Gram-Schmidt on nearly dependent columns (here: a warm-start Q with two almost equal columns, so
+# that two columns of P = M Q are almost parallel): the result must still be the oracle's within
+# the fp32 tolerance on every column that is well defined, and orthonormal there
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("layers,rank,eps", [
+    ([(300, 260)], 16, 4e-3), ([(512, 1100), (64, 576)], 32, 4e-3), ([(200, 520)], 50, 4e-3),
+    ([(512, 1100)], 32, 3e-2),
+])
+def test_gram_schmidt_with_nearly_dependent_columns(layers, rank, eps):
+    _say("case: nearly dependent columns", layers, rank, eps)
+    rng = np.random.default_rng(int(rank + 1000 * eps))
+    W = 2
+    comp, ml = _make(layers, (), rank, 8, 8, W)
+    Q = []
+    for rows, cols in layers:
+        q = rng.standard_normal((cols, min(rank, rows, cols))).astype(f32)
+        q[:, 3] = q[:, 1] + eps * rng.standard_normal(cols).astype(f32)
+        Q.append(q)
+    E = [[np.zeros(s, f32) for s in layers] for _ in range(W)]
+    for l in ml:
+        comp.set_q(l, Q[l])
+    rep = pu.StageReport()
+    G = _random_inputs(rng, layers, W)
+    E, Q = pu.staged_iteration(comp, G, pu.to_device(G), E, Q, ml, rep)
+    for l in ml:
+        for k in range(W):
+            p = comp.get_factor(B.FACTOR_P_ORTH, l, k).astype(f64)
+            ok = pu._well_defined_columns(comp.get_factor(B.FACTOR_P_PRE, l, k))
+            gram = p[:, ok].T @ p[:, ok]
+            assert np.abs(gram - np.eye(int(ok.sum()))).max() <= 2e-4, "columns not orthonormal"
+            assert np.all(np.isfinite(p))
+    _say("  ", rep)
+    comp.close()
