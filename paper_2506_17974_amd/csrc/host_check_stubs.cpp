@@ -8,6 +8,7 @@ namespace lqsgd {
 const char* last_launched_kernel() { return ""; }
 hipError_t launch_add_project(int, const DevArgs&, const Tile*, int, int, int, hipStream_t) { return hipErrorNotSupported; }
 hipError_t launch_orth(int, int, int, const DevArgs&, CoopState*, hipStream_t) { return hipErrorNotSupported; }
+int chol_entries(int) { return 0; }
 hipError_t launch_exchange(int, int, const DevArgs&, const XTile*, int, hipStream_t) { return hipErrorNotSupported; }
 hipError_t launch_back_project(int, const DevArgs&, const Tile*, int, const VTile*, int, int, hipStream_t) { return hipErrorNotSupported; }
 hipError_t launch_back_project_mfma(int, const DevArgs&, const Tile*, int, const VTile*, int, int, hipStream_t) { return hipErrorNotSupported; }

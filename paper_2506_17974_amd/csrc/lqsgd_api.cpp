@@ -472,11 +472,24 @@ int setup_device(lqsgd_ctx* c, uint32_t flags) {
   constexpr size_t kSlack = kFactorSlack;
   const size_t orth_cells = 2 * W * (size_t)std::max(p.L, 1) * ((p.max_rows + 255) / 256) * p.RP;
   a.E = nullptr; a.Qbar = nullptr; a.orth_table = nullptr; a.status = nullptr;
+  a.chol_table = nullptr; a.chol_part = nullptr; a.chol_redo = nullptr;
   if (!ext) TRY_(dev_alloc(c, &a.E, W * p.m_stride, true));
   TRY_(dev_alloc(c, &a.Ppart, W * p.ppart_stride + kSlack, true));
   TRY_(dev_alloc(c, &a.Ppre, W * p.p_stride + kSlack, true));
   TRY_(dev_alloc(c, &a.Porth, W * p.p_stride + kSlack, true));
   TRY_(dev_alloc(c, &a.orth_part, orth_cells, true));
+  {
+    // Tall factors at rank pads >= 16 exchange whole Gram matrices instead of single columns
+    // (launch_orth decides per call; the same height limits as there).  A caller-provided block
+    // gets the buffers of the form of three launches only, which gives the same bits.
+    const size_t nslice = (size_t)(p.max_rows + 255) / 256, pairs = W * (size_t)std::max(p.L, 1);
+    const size_t ne = (size_t)chol_entries(p.RP);
+    if (ne && nslice >= 8 && nslice <= 64 && pairs * (nslice + 1) * ne * 12 <= ((size_t)1 << 30)) {
+      if (!ext) TRY_(dev_alloc(c, &a.chol_table, pairs * (nslice + 1) * ne, true));
+      TRY_(dev_alloc(c, &a.chol_part, pairs * nslice * ne, true));
+      TRY_(dev_alloc(c, &a.chol_redo, pairs, true));
+    }
+  }
   if (!ext) {
     TRY_(dev_alloc(c, &a.orth_table, orth_cells, true));
     void* hp = nullptr;

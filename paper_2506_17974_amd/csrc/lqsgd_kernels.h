@@ -20,6 +20,10 @@ struct DevArgs {
   float* Porth;                // P_w after Gram-Schmidt
   float* orth_part;            // [2][L*W][ceil(max_rows/256)][RP] slice partials of the many-workgroup Gram-Schmidt
   unsigned long long* orth_table;      // [2][L*W][ceil(max_rows/256)][RP] tagged partials of its one-launch form
+  // Cholesky-QR form of the tall Gram-Schmidt (rank pads >= 16; all three null if the context has none):
+  unsigned long long* chol_table;      // [L*W][ceil(max_rows/256) + 1][NE] tagged Gram matrices of the slices, their total last
+  float* chol_part;            // [L*W][ceil(max_rows/256)][NE] the same matrices in plain memory, for the form of three launches
+  int* chol_redo;              // [L*W] raised for a pair that has to be done column by column
   int* status;                 // pinned host word the kernels raise when a bounded device-side wait expires
   float* Pbar;                 // aggregated P (shared)
   float* Qpart;                // sweep-1 partial products, per worker
@@ -61,9 +65,13 @@ hipError_t launch_add_project(int RP, const DevArgs& a, const Tile* tiles, int n
 struct CoopState {
   unsigned long long epoch = 0;   // launches made so far: makes the tags in `a.orth_table` unique
   int capacity = -1;              // workgroups of that kernel that fit the context's device at once (-1: not asked yet)
+  int chol_capacity = -1;         // the same for the Cholesky-QR kernel
   unsigned max_polls = 0;         // bound of a device-side wait; 0 = the default (about a second)
 };
-// coop: NULL disables the one-launch form.
+// Entries of the r x r Gram matrix that the slices of a factor exchange at rank pad RP (NE above); 0 if
+// the Cholesky-QR form does not exist at that pad.
+int chol_entries(int RP);
+// coop: NULL disables the one-launch forms.
 hipError_t launch_orth(int RP, int max_rows, int max_rank, const DevArgs& a, CoopState* coop, hipStream_t s);
 hipError_t launch_exchange(int mode, int phase, const DevArgs& a, const XTile* tiles, int ntiles, hipStream_t s);
 // Sweep 1 also runs the plain mean of the 1-D tensors (nvtiles extra workgroups).  Layers whose

@@ -754,12 +754,15 @@ __global__ __launch_bounds__(BS) void orth_reg_kernel(DevArgs a) {
 // products of column j with the columns after it.  The grid-wide dependency
 // between columns is the kernel boundary.  Launch 0 sums the sweep-0 partials,
 // launch r finishes with absmax(P_w) through an integer atomic max.
+// only_if (optional): one word per (layer, worker) pair, written by an earlier
+// kernel; the launches skip the pairs whose word is zero.
 // ---------------------------------------------------------------------------
 template <int RP>
-__global__ __launch_bounds__(256) void orth_wide_kernel(DevArgs a, int j, int nslice_max) {
+__global__ __launch_bounds__(256) void orth_wide_kernel(DevArgs a, int j, int nslice_max, const int* only_if) {
   __shared__ float red[4][RP];
   __shared__ float redmax[4];
   const int lw = blockIdx.x / nslice_max, slice = blockIdx.x - lw * nslice_max;
+  if (only_if && only_if[lw] == 0) return;       // this pair was finished by the Cholesky-QR kernels
   const int layer = lw / a.W, worker = lw - layer * a.W;
   const LayerDesc& ld = a.layers[layer];
   const int rows = ld.rows, r = ld.r;
@@ -884,49 +887,14 @@ __device__ __forceinline__ unsigned long long table_load(const unsigned long lon
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// The columns of one slice, all r of them: v holds the slice's rows (one per thread) and leaves
+// orthonormalised.  red [4 RP], tot_s [RP] and gather_s [kCoopMaxSlices RP] are LDS.
 template <int RP>
-__global__ __launch_bounds__(256) void orth_coop_kernel(DevArgs a, int nslice_max, int max_rank,
-                                                        unsigned long long* table, unsigned long long epoch,
-                                                        int* status, unsigned max_polls) {
+__device__ __forceinline__ void coop_columns(float (&v)[RP], int r, int lw, int slice, int nslice, int nslice_max, int max_rank,
+                                             unsigned long long* table, unsigned long long epoch, int* status,
+                                             unsigned max_polls, size_t pstride, float* red, float* tot_s, float* gather_s) {
   constexpr int EPT = (kCoopMaxSlices * RP + 255) / 256;     // table entries a thread collects per column
-  __shared__ float red[4][RP];
-  __shared__ float tot_s[RP];
-  __shared__ float gather_s[kCoopMaxSlices * RP];
-  __shared__ float redmax[4];
-  const int lw = blockIdx.x / nslice_max, slice = blockIdx.x - lw * nslice_max;
-  const int layer = lw / a.W, worker = lw - layer * a.W;
-  const LayerDesc& ld = a.layers[layer];
-  const int rows = ld.rows, r = ld.r;
-  const int nslice = (rows + 255) >> 8;
-  if (slice >= nslice) return;                   // workgroup-uniform
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
-  const int row = slice * 256 + tid;
-  const bool live = row < rows;
-  float* pre = a.Ppre + (size_t)worker * a.p_stride + ld.p_off;
-  float* orth = a.Porth + (size_t)worker * a.p_stride + ld.p_off;
-  const size_t pstride = (size_t)a.L * a.W * nslice_max * RP;   // [2][L*W][nslice_max][RP] entries
-  float v[RP];
-#pragma unroll
-  for (int k = 0; k < RP; ++k) v[k] = 0.0f;
-  // The absmax cell is shared by all slices: zeroed here with a device-scope store, raised with
-  // atomics at the end.  Every slice reads slice 0's first table entry before it gets there.
-  if (slice == 0 && tid == 0 && !a.orth_shared) {
-    __hip_atomic_store(a.scaleP + (size_t)worker * a.L + layer, 0.0f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0): acknowledged before this slice publishes anything
-  }
-  if (live) {
-    const float* Pp = a.Ppart + (size_t)worker * a.ppart_stride + (a.orth_shared ? ld.p_off : ld.ppart_off);
-    const int nseg = a.orth_shared ? 1 : ld.nseg;
-    for (int s = 0; s < nseg; ++s) {
-      const float* src = Pp + (size_t)s * ld.np_pad + (size_t)row * r;
-#pragma unroll
-      for (int k = 0; k < RP; ++k)
-        if (k < r) v[k] += src[k];
-    }
-#pragma unroll
-    for (int k = 0; k < RP; ++k)
-      if (k < r) pre[(size_t)row * r + k] = v[k];
-  }
   const int nent = nslice * RP;
   for (int j = 0; j < r; ++j) {                  // r is the same for every slice of the pair
     const unsigned tag = (unsigned)(epoch * (unsigned long long)max_rank + (unsigned long long)(j + 1));
@@ -939,10 +907,10 @@ __global__ __launch_bounds__(256) void orth_coop_kernel(DevArgs a, int nslice_ma
 #pragma unroll
     for (int k = 0; k < RP; ++k) s[k] = vj * v[k];
     transpose_reduce<RP, RP, 32>(s, lane);
-    if ((lane & (kWave / RP - 1)) == 0) red[wave][lane >> (6 - log2c(RP))] = s[0];
+    if ((lane & (kWave / RP - 1)) == 0) red[wave * RP + (lane >> (6 - log2c(RP)))] = s[0];
     __syncthreads();
     if (tid < RP) {
-      const float val = (red[0][tid] + red[1][tid]) + (red[2][tid] + red[3][tid]);
+      const float val = (red[tid] + red[RP + tid]) + (red[2 * RP + tid] + red[3 * RP + tid]);
       __hip_atomic_store(tab + (size_t)slice * RP + tid, ((unsigned long long)tag << 32) | __float_as_uint(val),
                          __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
@@ -987,6 +955,52 @@ __global__ __launch_bounds__(256) void orth_coop_kernel(DevArgs a, int nslice_ma
     }
     __syncthreads();                             // red, gather_s and tot_s are reused by the next column
   }
+}
+
+template <int RP>
+__global__ __launch_bounds__(256) void orth_coop_kernel(DevArgs a, int nslice_max, int max_rank,
+                                                        unsigned long long* table, unsigned long long epoch,
+                                                        int* status, unsigned max_polls) {
+  __shared__ float red[4 * RP];
+  __shared__ float tot_s[RP];
+  __shared__ float gather_s[kCoopMaxSlices * RP];
+  __shared__ float redmax[4];
+  const int lw = blockIdx.x / nslice_max, slice = blockIdx.x - lw * nslice_max;
+  const int layer = lw / a.W, worker = lw - layer * a.W;
+  const LayerDesc& ld = a.layers[layer];
+  const int rows = ld.rows, r = ld.r;
+  const int nslice = (rows + 255) >> 8;
+  if (slice >= nslice) return;                   // workgroup-uniform
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
+  const int row = slice * 256 + tid;
+  const bool live = row < rows;
+  float* pre = a.Ppre + (size_t)worker * a.p_stride + ld.p_off;
+  float* orth = a.Porth + (size_t)worker * a.p_stride + ld.p_off;
+  const size_t pstride = (size_t)a.L * a.W * nslice_max * RP;   // [2][L*W][nslice_max][RP] entries
+  float v[RP];
+#pragma unroll
+  for (int k = 0; k < RP; ++k) v[k] = 0.0f;
+  // The absmax cell is shared by all slices: zeroed here with a device-scope store, raised with
+  // atomics at the end.  Every slice reads slice 0's first table entry before it gets there.
+  if (slice == 0 && tid == 0 && !a.orth_shared) {
+    __hip_atomic_store(a.scaleP + (size_t)worker * a.L + layer, 0.0f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0): acknowledged before this slice publishes anything
+  }
+  if (live) {
+    const float* Pp = a.Ppart + (size_t)worker * a.ppart_stride + (a.orth_shared ? ld.p_off : ld.ppart_off);
+    const int nseg = a.orth_shared ? 1 : ld.nseg;
+    for (int s = 0; s < nseg; ++s) {
+      const float* src = Pp + (size_t)s * ld.np_pad + (size_t)row * r;
+#pragma unroll
+      for (int k = 0; k < RP; ++k)
+        if (k < r) v[k] += src[k];
+    }
+#pragma unroll
+    for (int k = 0; k < RP; ++k)
+      if (k < r) pre[(size_t)row * r + k] = v[k];
+  }
+  coop_columns<RP>(v, r, lw, slice, nslice, nslice_max, max_rank, table, epoch, status, max_polls, pstride, red, tot_s,
+                   gather_s);
   float mx = 0.0f;
   if (live) {
 #pragma unroll
@@ -2401,6 +2415,471 @@ __global__ __launch_bounds__(256) void pad_factor_kernel(DevArgs a, int RP, int 
   }
 }
 
+// ---------------------------------------------------------------------------
+// orth of tall factors at rank pads >= 16: Cholesky-QR, applied twice.
+// The column-by-column form above pays one exchange between the slices of a
+// factor per column (about 10 us each: r = 32 columns cost 0.33 ms on a factor
+// of 8192 rows, where all the arithmetic is a few microseconds).  Here the
+// slices exchange the r x r Gram matrix G = P^T P once per pass instead:
+//   G = R^T R (Cholesky),  P <- P R^-1.
+// In exact arithmetic R is the triangular factor of the QR decomposition of P,
+// so P R^-1 is what Gram-Schmidt (Algorithm 1's Orthogonalize) returns; in
+// float32 one pass loses orthogonality in proportion to cond(P)^2, and a second
+// pass on its result restores it to rounding level (the usual "CholeskyQR2").
+// That only holds while cond(P)^2 stays well below 1/epsilon: if a pivot of
+// either factorisation falls below kCholPivotFloor of its column's squared
+// norm (or a column is zero), the pair is done again from the start by the
+// column-by-column form, whose result does not depend on conditioning in that
+// way.  Every slice of a pair factorises the same total, so all take the same
+// decision.
+// Steps of a pass, per workgroup (= 256 rows, one per thread, in registers):
+//   * the slice's Gram matrix on the matrix cores (rows are re-read from the
+//     plane this workgroup has just written, in "lane = column" layout), the
+//     four wavefronts' parts added in wavefront order;
+//   * exchange: entry e of the total is owned by slice e / ceil(NE / nslice),
+//     which collects that entry from every slice, adds them up in slice order
+//     and publishes the total; every slice then collects all totals.  Entries
+//     are tagged 64-bit words as in orth_coop_kernel: two round trips per pass
+//     instead of one per column, and no workgroup reads more than 2 NE words;
+//   * wavefront 0 factorises (lane l keeps row l of G in registers; right-
+//     looking elimination with lane broadcasts), every thread then applies
+//     R^-1 to its row by forward substitution, reading R from LDS.
+// phase -1 runs all of it in one cooperative launch.  Without one, phases 0, 1
+// and 2 are three ordinary launches that pass the slices' Gram matrices through
+// plain memory (cpart) and add them up in the same order, so that both forms
+// give the same bits; pairs that need the column-by-column form raise redo[pair]
+// and the guarded orth_wide_kernel launches that follow do them.
+// ---------------------------------------------------------------------------
+constexpr float kCholPivotFloor = 1e-3f;
+
+template <int RP>
+struct CholShape {
+  static_assert(RP == 16 || RP == 32 || RP == 64, "rank pads of the matrix-core sweeps");
+  static constexpr int NB = RP <= 32 ? 1 : 3;                       // 32 x 32 blocks kept: (0,0) or (0,0), (0,1), (1,1)
+  static constexpr int NE = RP <= 32 ? RP * RP : 3 * 1024;          // entries exchanged
+  static constexpr int QN = (NE + 255) / 256;                       // ... per thread
+  static constexpr int GN = (NE + kCoopMaxSlices + 255) / 256;      // entries a thread collects as an owner
+  static constexpr int kPoolA = 4 * NE, kPoolB = (kCoopMaxSlices + 5) * RP;
+  static constexpr int POOL = kPoolA > kPoolB ? kPoolA : kPoolB;    // LDS floats
+};
+
+// Where <column i, column j>, i <= j, sits among the exchanged entries.
+template <int RP>
+__device__ __forceinline__ int chol_entry(int i, int j) {
+  if constexpr (RP <= 32) {
+    return i * RP + j;
+  } else {
+    return j < 32 ? i * 32 + j : (i < 32 ? 1024 + i * 32 + (j - 32) : 2048 + (i - 32) * 32 + (j - 32));
+  }
+}
+
+// The Gram matrix of the slice's 256 rows of `orth`: on return thread t holds entries t, t + 256, ...
+// in gsum.  pool: 4 NE floats of LDS, free again on return.
+template <int RP>
+__device__ __forceinline__ void chol_slice_gram(const float* orth, int rows, int r, int row0, float* pool,
+                                                float (&gsum)[CholShape<RP>::QN]) {
+  using S = CholShape<RP>;
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
+  const int li = lane & 31, h = lane >> 5;
+  v16f acc[S::NB];
+#pragma unroll
+  for (int b = 0; b < S::NB; ++b)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[b][i] = 0.0f;
+  constexpr int U = 16;                           // row pairs loaded ahead of their matrix instructions
+  const int c0 = min(li, r - 1), c1 = min(32 + li, r - 1);
+  const bool ok0 = li < r, ok1 = 32 + li < r;
+#pragma unroll 1
+  for (int b = 0; b < 32 / U; ++b) {
+    float x0[U], x1[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int row = row0 + wave * 64 + 2 * (b * U + u) + h;
+      const float* src = orth + (size_t)min(row, rows - 1) * r;      // every load is in bounds; masked below
+      x0[u] = keep_if(src[c0], ok0 && row < rows);
+      if constexpr (RP == 64) x1[u] = keep_if(src[c1], ok1 && row < rows);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(x0[u], x0[u], acc[0], 0, 0, 0);
+      if constexpr (RP == 64) {
+        acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(x0[u], x1[u], acc[1], 0, 0, 0);
+        acc[2] = __builtin_amdgcn_mfma_f32_32x32x2f32(x1[u], x1[u], acc[2], 0, 0, 0);
+      }
+    }
+  }
+  // D layout: register v of lane (li, h) is element (8 (v / 4) + 4 h + v % 4, li) of the block
+  float* mine = pool + wave * S::NE;
+#pragma unroll
+  for (int b = 0; b < S::NB; ++b)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int m = 8 * (v >> 2) + 4 * h + (v & 3);
+      if constexpr (RP <= 32) {
+        if (m < RP && li < RP) mine[m * RP + li] = acc[b][v];
+      } else {
+        mine[b * 1024 + m * 32 + li] = acc[b][v];
+      }
+    }
+  __syncthreads();
+#pragma unroll
+  for (int q = 0; q < S::QN; ++q) {
+    const int e = tid + 256 * q;
+    gsum[q] = (e < S::NE) ? (pool[e] + pool[S::NE + e]) + (pool[2 * S::NE + e] + pool[3 * S::NE + e]) : 0.0f;
+  }
+  __syncthreads();
+}
+
+__device__ __forceinline__ unsigned long long table_wait(const unsigned long long* p, unsigned long long x, unsigned tag,
+                                                         int* status, unsigned max_polls) {
+  unsigned polls = 0;
+  while ((unsigned)(x >> 32) != tag) {
+    if (++polls >= max_polls) {
+      __hip_atomic_store(status, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+      break;
+    }
+    __builtin_amdgcn_s_sleep(1);
+    x = table_load(p);
+  }
+  return x;
+}
+
+// The slices' Gram matrices -> their total, in LDS at pool + 2 NE, through the tagged table
+// `tab` ([nslice_max + 1][NE]: one plane per slice, the totals in the last one).
+template <int RP>
+__device__ __forceinline__ void chol_exchange(const float (&gsum)[CholShape<RP>::QN], unsigned long long* tab, int slice,
+                                              int nslice, int nslice_max, unsigned tag_part, unsigned tag_total, float* pool,
+                                              int* status, unsigned max_polls) {
+  using S = CholShape<RP>;
+  const int tid = threadIdx.x;
+#pragma unroll
+  for (int q = 0; q < S::QN; ++q) {
+    const int e = tid + 256 * q;
+    if (e < S::NE)
+      __hip_atomic_store(tab + (size_t)slice * S::NE + e, ((unsigned long long)tag_part << 32) | __float_as_uint(gsum[q]),
+                         __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  // the entries this slice owns, from every slice: item = (entry, slice)
+  const int share = (S::NE + nslice - 1) / nslice;
+  const int e0 = slice * share;
+  const int cnt = max(0, min(S::NE - e0, share));
+  const int nitem = cnt * nslice;                  // <= NE + nslice
+  unsigned long long x[S::GN];
+  const unsigned long long* src[S::GN];
+#pragma unroll
+  for (int i = 0; i < S::GN; ++i) {
+    const int it = tid + 256 * i;
+    const int el = it / nslice, sl = it - el * nslice;
+    src[i] = tab + (size_t)sl * S::NE + e0 + el;
+    x[i] = (it < nitem) ? table_load(src[i]) : ((unsigned long long)tag_part << 32);
+  }
+#pragma unroll
+  for (int i = 0; i < S::GN; ++i) {
+    const int it = tid + 256 * i;
+    if (it < nitem) {
+      x[i] = table_wait(src[i], x[i], tag_part, status, max_polls);
+      pool[it] = __uint_as_float((unsigned)x[i]);
+    }
+  }
+  __syncthreads();
+  unsigned long long* totals = tab + (size_t)nslice_max * S::NE;
+  for (int el = tid; el < cnt; el += 256) {
+    float t = 0.0f;
+    for (int sl = 0; sl < nslice; ++sl) t += pool[el * nslice + sl];
+    __hip_atomic_store(totals + e0 + el, ((unsigned long long)tag_total << 32) | __float_as_uint(t), __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_AGENT);
+  }
+  unsigned long long y[S::QN];
+#pragma unroll
+  for (int q = 0; q < S::QN; ++q) {
+    const int e = tid + 256 * q;
+    y[q] = (e < S::NE) ? table_load(totals + e) : ((unsigned long long)tag_total << 32);
+  }
+#pragma unroll
+  for (int q = 0; q < S::QN; ++q) {
+    const int e = tid + 256 * q;
+    if (e < S::NE) {
+      y[q] = table_wait(totals + e, y[q], tag_total, status, max_polls);
+      pool[2 * S::NE + e] = __uint_as_float((unsigned)y[q]);
+    }
+  }
+  __syncthreads();
+}
+
+// The same total from the slices' matrices in plain memory (written by an earlier launch).
+template <int RP>
+__device__ __forceinline__ void chol_sum_parts(const float* parts, int nslice, float* pool) {
+  using S = CholShape<RP>;
+  const int tid = threadIdx.x;
+#pragma unroll
+  for (int q = 0; q < S::QN; ++q) {
+    const int e = tid + 256 * q;
+    if (e < S::NE) {
+      float t = 0.0f;
+      for (int sl = 0; sl < nslice; ++sl) t += parts[(size_t)sl * S::NE + e];
+      pool[2 * S::NE + e] = t;
+    }
+  }
+  __syncthreads();
+}
+
+__device__ __forceinline__ float lane_value(float x, int l) {
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), l));
+}
+
+// One wavefront: G (total, at T) = L L^T.  Lane l works on row l.  Leaves L at Ls ([RP][RP], row
+// major, lower triangle; the diagonal holds 1 / L_jj; rows and columns >= r are those of the
+// identity) and returns whether every pivot stayed above the floor -- the same in every lane.
+template <int RP>
+__device__ __forceinline__ bool chol_factor(const float* T, float* Ls, int r, int lane) {
+  const int l = min(lane, RP - 1);
+  float g[RP];
+#pragma unroll
+  for (int k = 0; k < RP; ++k) g[k] = T[chol_entry<RP>(min(k, l), max(k, l))];
+  float diag0 = 0.0f;
+#pragma unroll
+  for (int k = 0; k < RP; ++k)
+    if (k == l) diag0 = g[k];
+  bool ok = true;
+  static_for<RP>([&](auto J) {
+    constexpr int j = decltype(J)::value;
+    if (j < r) {
+      const float d = lane_value(g[j], j), d0 = lane_value(diag0, j);
+      ok = ok && (d0 > FLT_MIN) && (d > kCholPivotFloor * d0);        // false for NaN as well
+      const float rinv = 1.0f / sqrtf(d);
+      const float lj = (lane >= j) ? g[j] * rinv : 0.0f;               // column j of L
+#pragma unroll
+      for (int k = j + 1; k < RP; ++k) g[k] = fmaf(-lj, lane_value(lj, k), g[k]);
+      g[j] = (lane == j) ? rinv : lj;
+    } else {
+      g[j] = (lane == j) ? 1.0f : 0.0f;
+    }
+  });
+  if (lane < RP) {
+#pragma unroll
+    for (int k = 0; k < RP; ++k) Ls[lane * RP + k] = g[k];
+  }
+  return ok;
+}
+
+// p <- p R^-1 with R = L^T: forward substitution along the row.
+template <int RP>
+__device__ __forceinline__ void chol_solve_row(float (&p)[RP], const float* Ls, int r) {
+  static_for<RP>([&](auto J) {
+    constexpr int j = decltype(J)::value;
+    if (j < r) {                                   // p[j] is zero beyond the rank and stays so
+      float acc = p[j];
+#pragma unroll
+      for (int i = 0; i < j; ++i) acc = fmaf(-p[i], Ls[j * RP + i], acc);
+      p[j] = acc * Ls[j * RP + j];
+    }
+  });
+}
+
+// The slice's block of P_w = the sum of the sweep-0 planes, written to `pre` and `orth`.  The block is
+// one contiguous run of nflt floats in every plane and in both outputs, so the threads walk it in
+// 16-byte pieces, fully coalesced (a thread per row would touch 64 cache lines per load).
+template <int RP>
+__device__ __forceinline__ void chol_sum_planes(const float* planes, int nseg, size_t plane_stride, float* pre_s, float* orth_s,
+                                                int nflt) {
+  const int tid = threadIdx.x;
+  const bool vec = (((reinterpret_cast<uintptr_t>(planes) | reinterpret_cast<uintptr_t>(pre_s) |
+                      reinterpret_cast<uintptr_t>(orth_s)) & 15) == 0) && (plane_stride & 3) == 0;
+  if (vec) {
+    constexpr int NI = RP / 4;
+    float4 acc[NI];
+#pragma unroll
+    for (int i = 0; i < NI; ++i) acc[i] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    for (int sg = 0; sg < nseg; ++sg) {
+      const float* src = planes + (size_t)sg * plane_stride;
+#pragma unroll
+      for (int i = 0; i < NI; ++i) {
+        const int f = 4 * (tid + 256 * i);
+        if (f + 4 <= nflt) {
+          const float4 t = *reinterpret_cast<const float4*>(src + f);
+          acc[i].x += t.x; acc[i].y += t.y; acc[i].z += t.z; acc[i].w += t.w;
+        }
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      const int f = 4 * (tid + 256 * i);
+      if (f + 4 <= nflt) {
+        *reinterpret_cast<float4*>(pre_s + f) = acc[i];
+        *reinterpret_cast<float4*>(orth_s + f) = acc[i];
+      }
+    }
+    const int f = (nflt & ~3) + tid;               // what is left of a block whose length is no multiple of 4
+    if (tid < (nflt & 3)) {
+      float t = 0.0f;
+      for (int sg = 0; sg < nseg; ++sg) t += planes[(size_t)sg * plane_stride + f];
+      pre_s[f] = t;
+      orth_s[f] = t;
+    }
+  } else {
+    float acc[RP];
+#pragma unroll
+    for (int i = 0; i < RP; ++i) acc[i] = 0.0f;
+    for (int sg = 0; sg < nseg; ++sg) {
+      const float* src = planes + (size_t)sg * plane_stride;
+#pragma unroll
+      for (int i = 0; i < RP; ++i) {
+        const int f = tid + 256 * i;
+        if (f < nflt) acc[i] += src[f];
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < RP; ++i) {
+      const int f = tid + 256 * i;
+      if (f < nflt) {
+        pre_s[f] = acc[i];
+        orth_s[f] = acc[i];
+      }
+    }
+  }
+}
+
+// Row `row` of a rows x r factor (zero beyond r and for a thread without a row): whole-row loads that may
+// run into what follows the row, as in load_slice.
+template <int RP>
+__device__ __forceinline__ void chol_load_row(const float* F, int row, int rows, int r, float (&v)[RP]) {
+  load_row<RP>(F, min(row, rows - 1), r, r == RP, v);
+  const bool live = row < rows;
+#pragma unroll
+  for (int k = 0; k < RP; ++k) v[k] = keep_if(v[k], live);
+}
+
+template <int RP>
+__device__ __forceinline__ void chol_store_row(float* F, int row, int rows, int r, const float (&v)[RP]) {
+  if (row >= rows) return;
+  if (r == RP) {
+    float* b = F + (size_t)row * RP;
+#pragma unroll
+    for (int k = 0; k < RP; k += 4) *reinterpret_cast<float4*>(b + k) = make_float4(v[k], v[k + 1], v[k + 2], v[k + 3]);
+  } else if ((r & 1) == 0) {
+    float* b = F + (size_t)row * r;
+#pragma unroll
+    for (int k = 0; k < RP; k += 2)
+      if (k < r) *reinterpret_cast<float2*>(b + k) = make_float2(v[k], v[k + 1]);
+  } else {
+    float* b = F + (size_t)row * r;
+#pragma unroll
+    for (int k = 0; k < RP; ++k)
+      if (k < r) b[k] = v[k];
+  }
+}
+
+template <int RP>
+__global__ __launch_bounds__(256, 2) void orth_chol_kernel(DevArgs a, int nslice_max, int max_rank, int phase,
+                                                        unsigned long long* ctable, float* cpart, int* redo,
+                                                        unsigned long long epoch, unsigned max_polls) {
+  using S = CholShape<RP>;
+  __shared__ __attribute__((aligned(16))) float pool[S::POOL];
+  __shared__ float redmax[4];
+  __shared__ int flag;
+  const int lw = blockIdx.x / nslice_max, slice = blockIdx.x - lw * nslice_max;
+  const int layer = lw / a.W, worker = lw - layer * a.W;
+  const LayerDesc& ld = a.layers[layer];
+  const int rows = ld.rows, r = ld.r;
+  const int nslice = (rows + 255) >> 8;
+  if (slice >= nslice) return;                   // workgroup-uniform
+  if (phase == 2 && redo[lw] != 0) return;       // raised in phase 1, or by a faster slice just now: the pair is done again anyway
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
+  const int row = slice * 256 + tid;
+  const bool live = row < rows;
+  float* pre = a.Ppre + (size_t)worker * a.p_stride + ld.p_off;
+  float* orth = a.Porth + (size_t)worker * a.p_stride + ld.p_off;
+  float* scale = a.scaleP + (size_t)worker * a.L + layer;
+  unsigned long long* tab = ctable + (size_t)lw * (nslice_max + 1) * S::NE;
+  float* parts = cpart + (size_t)lw * nslice_max * S::NE;
+  float* Ls = pool;                              // [RP][RP], once the total has been read out of pool + 2 NE
+  float v[RP];
+#pragma unroll
+  for (int k = 0; k < RP; ++k) v[k] = 0.0f;
+  if (phase <= 0) {
+    if (slice == 0 && tid == 0) {
+      if (phase == 0) {
+        redo[lw] = 0;
+        if (!a.orth_shared) *scale = 0.0f;
+      } else if (!a.orth_shared) {
+        // shared by all slices, raised with atomics at the end; every slice reads an entry that
+        // slice 0 publishes after this store before it gets there
+        __hip_atomic_store(scale, 0.0f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0)
+      }
+    }
+    {
+      const float* Pp = a.Ppart + (size_t)worker * a.ppart_stride + (a.orth_shared ? ld.p_off : ld.ppart_off);
+      const size_t base = (size_t)slice * 256 * r;
+      chol_sum_planes<RP>(Pp + base, a.orth_shared ? 1 : ld.nseg, (size_t)ld.np_pad, pre + base, orth + base,
+                          min(256, rows - slice * 256) * r);
+    }
+  }
+  float gsum[S::QN];
+  bool good = true;
+  if (phase == 0) {
+    __syncthreads();                             // the rows above, for the loads in "lane = column" layout
+    chol_slice_gram<RP>(orth, rows, r, slice * 256, pool, gsum);
+  } else {
+    const int first = phase < 0 ? 0 : phase - 1, last = phase < 0 ? 1 : phase - 1;
+    for (int pass = first; pass <= last; ++pass) {
+      if (phase < 0) {
+        __syncthreads();
+        chol_slice_gram<RP>(orth, rows, r, slice * 256, pool, gsum);
+        const unsigned tag = (unsigned)(epoch * 4ull) + 2u * (unsigned)pass;
+        chol_exchange<RP>(gsum, tab, slice, nslice, nslice_max, tag + 1u, tag + 2u, pool, a.status, max_polls);
+      } else {
+        chol_sum_parts<RP>(parts, nslice, pool);
+      }
+      if (wave == 0) {
+        const bool ok = chol_factor<RP>(pool + 2 * S::NE, Ls, r, lane);
+        if (lane == 0) flag = ok ? 1 : 0;
+      }
+      __syncthreads();
+      good = flag != 0;
+      if (!good) break;
+      // the thread's row as the previous step left it in memory (not kept in registers across the
+      // factorisation, which needs them)
+      chol_load_row<RP>(orth, row, rows, r, v);
+      chol_solve_row<RP>(v, Ls, r);
+      chol_store_row<RP>(orth, row, rows, r, v);
+      __syncthreads();                           // Ls and flag are written again by the next pass
+    }
+    if (phase == 1 && good) chol_slice_gram<RP>(orth, rows, r, slice * 256, pool, gsum);
+  }
+  if (phase == 0 || (phase == 1 && good)) {
+#pragma unroll
+    for (int q = 0; q < S::QN; ++q) {
+      const int e = tid + 256 * q;
+      if (e < S::NE) parts[(size_t)slice * S::NE + e] = gsum[q];
+    }
+    return;
+  }
+  if (!good) {
+    if (phase > 0) {
+      if (slice == 0 && tid == 0) redo[lw] = 1;
+      return;
+    }
+    // one launch: column by column from the sum of the planes, as orth_coop_kernel does
+    chol_load_row<RP>(pre, row, rows, r, v);
+    const size_t pstride = (size_t)a.L * a.W * nslice_max * RP;
+    coop_columns<RP>(v, r, lw, slice, nslice, nslice_max, max_rank, a.orth_table, epoch, a.status, max_polls, pstride,
+                     pool + kCoopMaxSlices * RP, pool + (kCoopMaxSlices + 4) * RP, pool);
+    chol_store_row<RP>(orth, row, rows, r, v);
+  }
+  float mx = 0.0f;
+#pragma unroll
+  for (int k = 0; k < RP; ++k)
+    if (k < r) mx = fmaxf(mx, fabsf(v[k]));
+  mx = wave_max(mx);
+  if (lane == 0) redmax[wave] = mx;
+  __syncthreads();
+  if (tid == 0 && !a.orth_shared) {
+    const float m = fmaxf(fmaxf(redmax[0], redmax[1]), fmaxf(redmax[2], redmax[3]));
+    atomicMax(reinterpret_cast<unsigned int*>(scale), __float_as_uint(m));
+  }
+}
+
 }  // namespace
 
 // ---------------------------------------------------------------------------
@@ -2529,6 +3008,72 @@ bool launch_orth_coop(int rp, int nslice, int max_rank, const DevArgs& a, int nb
   }
 }
 
+// The Cholesky-QR form in one cooperative launch; false (nothing launched) if the grid cannot be
+// resident at once or the stream is being captured.
+template <int RP>
+bool try_orth_chol_coop(int nslice, int max_rank, const DevArgs& a, int nblocks, CoopState* cs, hipStream_t s) {
+  if (cs->chol_capacity < 0) {
+    int dev = 0, coop = 0, cus = 0, per_cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&coop, hipDeviceAttributeCooperativeLaunch, dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, orth_chol_kernel<RP>, 256, 0) != hipSuccess) {
+      (void)hipGetLastError();
+      cs->chol_capacity = 0;
+    } else {
+      cs->chol_capacity = coop ? cus * per_cu : 0;
+    }
+  }
+  if (nblocks > cs->chol_capacity) return false;
+  DevArgs args = a;
+  int phase = -1;
+  unsigned long long* table = a.chol_table;
+  float* part = a.chol_part;
+  int* redo = a.chol_redo;
+  unsigned long long n = cs->epoch;
+  unsigned max_polls = cs->max_polls ? cs->max_polls : kTablePolls;
+  void* params[] = {&args, &nslice, &max_rank, &phase, &table, &part, &redo, &n, &max_polls};
+  const hipError_t e = hipLaunchCooperativeKernel(reinterpret_cast<void*>(orth_chol_kernel<RP>), dim3(nblocks), dim3(256),
+                                                  params, 0, s);
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    return false;
+  }
+  cs->epoch += 1;                                // tags of this launch: 4 epoch + 1 .. + 4, and the columns' as above
+  note_kernel("orth_chol_kernel<%d>", RP);
+  return true;
+}
+
+bool launch_orth_chol_coop(int rp, int nslice, int max_rank, const DevArgs& a, int nblocks, CoopState* cs, hipStream_t s) {
+  if (!cs || !a.chol_table || !a.orth_table || !a.status || nslice > kCoopMaxSlices) return false;
+  hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(s, &cap) != hipSuccess) {
+    (void)hipGetLastError();
+    return false;
+  }
+  if (cap != hipStreamCaptureStatusNone) return false;      // a replay would repeat this launch's tags
+  switch (rp) {
+    case 16: return try_orth_chol_coop<16>(nslice, max_rank, a, nblocks, cs, s);
+    case 32: return try_orth_chol_coop<32>(nslice, max_rank, a, nblocks, cs, s);
+    case 64: return try_orth_chol_coop<64>(nslice, max_rank, a, nblocks, cs, s);
+    default: return false;
+  }
+}
+
+// Three launches of the Cholesky-QR kernel, then the column-by-column launches for the pairs that raised their word.
+template <int RP>
+void launch_orth_chol_split(int nslice, int max_rank, const DevArgs& a, int nblocks, hipStream_t s) {
+  for (int phase = 0; phase < 3; ++phase)
+    orth_chol_kernel<RP><<<dim3(nblocks), dim3(256), 0, s>>>(a, nslice, max_rank, phase, nullptr, a.chol_part, a.chol_redo, 0ull, 0u);
+  for (int j = 0; j <= max_rank; ++j)
+    orth_wide_kernel<RP><<<dim3(nblocks), dim3(256), 0, s>>>(a, j, nslice, a.chol_redo);
+  note_kernel("orth_chol_kernel<%d> x 3 launches", RP);
+}
+
+int chol_entries(int rp) {
+  return rp == 16 ? CholShape<16>::NE : rp == 32 ? CholShape<32>::NE : rp == 64 ? CholShape<64>::NE : 0;
+}
+
 hipError_t launch_orth(int rp, int max_rows, int max_rank, const DevArgs& a, CoopState* coop, hipStream_t s) {
   if (a.L <= 0) return hipSuccess;
   const dim3 grid(a.L * a.W);
@@ -2538,9 +3083,21 @@ hipError_t launch_orth(int rp, int max_rows, int max_rank, const DevArgs& a, Coo
   const bool reg_fits = (max_rows <= 512 && rp * 2 <= 128) || (max_rows <= 2048 && rp * 8 <= 64) ||
                         (max_rows <= 4096 && rp * 4 <= 48) || (max_rows <= 11264 && rp * 11 <= 48);
   if (a.orth_part && nslice >= 8 && ((int)grid.x < 128 || !reg_fits)) {
+#ifdef LQSGD_TUNING
+    static const bool chol = [] { const char* e = std::getenv("LQSGD_ORTH_CHOL"); return !(e && e[0] == '0'); }();
+#else
+    constexpr bool chol = true;
+#endif
+    if (chol && rp >= 16 && a.chol_part && a.chol_redo) {
+      if (launch_orth_chol_coop(rp, nslice, max_rank, a, (int)grid.x * nslice, coop, s)) return hipSuccess;
+      if (rp == 16) launch_orth_chol_split<16>(nslice, max_rank, a, (int)grid.x * nslice, s);
+      else if (rp == 32) launch_orth_chol_split<32>(nslice, max_rank, a, (int)grid.x * nslice, s);
+      else launch_orth_chol_split<64>(nslice, max_rank, a, (int)grid.x * nslice, s);
+      return hipGetLastError();
+    }
     if (launch_orth_coop(rp, nslice, max_rank, a, (int)grid.x * nslice, coop, s)) return hipSuccess;
     for (int j = 0; j <= max_rank; ++j) {
-      LQSGD_RP_SWITCH_ORTH(rp, (orth_wide_kernel<RP><<<dim3(grid.x * nslice), dim3(256), 0, s>>>(a, j, nslice)));
+      LQSGD_RP_SWITCH_ORTH(rp, (orth_wide_kernel<RP><<<dim3(grid.x * nslice), dim3(256), 0, s>>>(a, j, nslice, nullptr)));
     }
     note_kernel("orth_wide_kernel<%d> x %d launches", rp, max_rank + 1);
     return hipGetLastError();

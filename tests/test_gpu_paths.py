@@ -221,3 +221,63 @@ def test_gram_schmidt_with_nearly_dependent_columns(layers, rank, eps):
             assert np.all(np.isfinite(p))
     _say("  ", rep)
     comp.close()
+
+
+# ---------------------------------------------------------------------------
+# Tall factors at rank pads >= 16: Orthogonalize (Algorithm 1) through two rounds of Cholesky-QR
+# instead of column by column.  Every stage is held against the oracle's Gram-Schmidt; the one
+# cooperative launch and the form of three launches must agree bit for bit; pairs whose pivots fall
+# below the floor (nearly dependent columns, an all-zero gradient) are done column by column, again
+# with the same bits in both forms.
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("layers,rank,W,special", [
+    ([(4096, 300)], 16, 4, None),
+    ([(2600, 36), (3000, 64)], 32, 2, None),
+    ([(8192, 128)], 50, 2, None),
+    ([(2304, 200), (300, 40)], 20, 3, None),          # rank below its pad; a short layer in the same launch
+    ([(4096, 300)], 16, 2, 4e-3),                     # two nearly parallel columns: a pivot below the floor
+    ([(5000, 96)], 50, 2, 4e-3),
+    ([(2600, 72)], 32, 2, 0.3),                       # columns at an angle the factorisation still takes
+    ([(4096, 300)], 16, 3, "zero"),                   # one worker's gradient is zero: P_w = 0
+])
+def test_tall_gram_schmidt_by_cholesky_qr(layers, rank, W, special):
+    _say("case: tall Gram-Schmidt, Cholesky-QR", layers, rank, W, special)
+    rng = np.random.default_rng(rank + W)
+    Q0 = []
+    for rows, cols in layers:
+        q = rng.standard_normal((cols, min(rank, rows, cols))).astype(f32)
+        if isinstance(special, float):
+            q[:, 3] = q[:, 1] + special * rng.standard_normal(cols).astype(f32)
+        Q0.append(q)
+    G = _random_inputs(rng, layers, W)
+    if special == "zero":
+        G[W - 1][0][:] = 0.0
+    Gd = pu.to_device(G)
+    rp = 16 if rank <= 16 else 32 if rank <= 32 else 64
+    got = {}
+    for flags, name in ((0, "orth_chol_kernel<%d>" % rp), (B.FLAG_NO_COOPERATIVE_LAUNCH, "orth_chol_kernel<%d> x 3 launches" % rp)):
+        comp, ml = _make(layers, (), rank, 8, 8, W, flags=flags)
+        for l in ml:
+            comp.set_q(l, Q0[l])
+        E = [[np.zeros(s, f32) for s in layers] for _ in range(W)]
+        rep = pu.StageReport()
+        pu.staged_iteration(comp, G, Gd, E, Q0, ml, rep)
+        assert comp.launched_kernel(B.KERNEL_ORTH) == name, comp.launched_kernel(B.KERNEL_ORTH)
+        facs = []
+        for l in ml:
+            for k in range(W):
+                p = comp.get_factor(B.FACTOR_P_ORTH, l, k)
+                assert np.all(np.isfinite(p))
+                ok = pu._well_defined_columns(comp.get_factor(B.FACTOR_P_PRE, l, k))
+                if special == "zero" and l == 0 and k == W - 1:
+                    assert not p.any()
+                else:
+                    p64 = p[:, ok].astype(f64)
+                    assert np.abs(p64.T @ p64 - np.eye(int(ok.sum()))).max() <= 2e-4, "columns not orthonormal"
+                facs.append(p)
+            facs.append(comp.get_factor(B.FACTOR_Q_BAR, l))
+        got[flags] = facs
+        _say("  ", name, rep)
+        comp.close()
+    for x, y in zip(got[0], got[B.FLAG_NO_COOPERATIVE_LAUNCH]):
+        assert np.array_equal(x, y), "the one-launch and the three-launch form differ"
