@@ -65,7 +65,7 @@ def main():
     ap.add_argument("--update", type=float, default=None, metavar="ETA",
                     help="apply w <- w - ETA G-hat to synthetic parameters inside the step instead of storing G-hat")
     ap.add_argument("--no-cooperative-launch", action="store_true",
-                    help="the Gram-Schmidt of tall factors takes its one-launch-per-column form instead of one "
+                    help="the Gram-Schmidt of tall factors takes its form of several ordinary launches instead of one "
                          "cooperative launch (for runs under rocprofv3, whose exit handler crashes after a cooperative launch)")
     ap.add_argument("--graph", action="store_true",
                     help="record one step into a HIP graph and time replays of it (for the small, launch-bound sets)")

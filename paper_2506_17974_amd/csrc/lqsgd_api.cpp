@@ -424,7 +424,7 @@ namespace {
 // Fills c->args and uploads the tables of c->plan.  Device memory comes from hipMalloc or, when
 // c->arena is set, from that block: then the residual slabs and the warm-start Q are not allocated
 // (the caller's buffers are bound per call), and the one-launch Gram-Schmidt of tall factors, which
-// needs a pinned status word and a table that starts from zero, is off (its per-column form runs).
+// needs a pinned status word and a table that starts from zero, is off (its forms of several launches run).
 // On failure the caller releases c->allocs / c->status.
 int setup_device(lqsgd_ctx* c, uint32_t flags) {
   int rc;
