@@ -480,12 +480,13 @@ int setup_device(lqsgd_ctx* c, uint32_t flags) {
   TRY_(dev_alloc(c, &a.orth_part, orth_cells, true));
   {
     // Tall factors at rank pads >= 16 exchange whole Gram matrices instead of single columns
-    // (launch_orth decides per call; the same height limits as there).  A caller-provided block
-    // gets the buffers of the form of three launches only, which gives the same bits.
+    // (launch_orth decides per call; the same lower height limit as there).  A caller-provided block
+    // and factors of more than 64 slices get the buffers of the form of three launches only, which
+    // gives the same bits.
     const size_t nslice = (size_t)(p.max_rows + 255) / 256, pairs = W * (size_t)std::max(p.L, 1);
     const size_t ne = (size_t)chol_entries(p.RP);
-    if (ne && nslice >= 8 && nslice <= 64 && pairs * (nslice + 1) * ne * 12 <= ((size_t)1 << 30)) {
-      if (!ext) TRY_(dev_alloc(c, &a.chol_table, pairs * (nslice + 1) * ne, true));
+    if (ne && nslice >= 8 && pairs * (nslice + 1) * ne * 12 <= ((size_t)1 << 30)) {
+      if (!ext && nslice <= 64) TRY_(dev_alloc(c, &a.chol_table, pairs * (nslice + 1) * ne, true));   // the one-launch form's limit
       TRY_(dev_alloc(c, &a.chol_part, pairs * nslice * ne, true));
       TRY_(dev_alloc(c, &a.chol_redo, pairs, true));
     }

@@ -133,7 +133,8 @@ EDGE_CASES = [
     ([(33, 70)], 4, 8, 4, 9, 255.0),                       # a ragged last pass of worker slots
     ([(3, 70000)], 2, 8, 8, 2, 255.0),                     # very wide: 69 column segments
     ([(70000, 12)], 4, 8, 8, 2, 255.0),                    # very tall: 274 slices, Gram-Schmidt one launch per column
-    ([(20000, 16)], 16, 8, 8, 3, 255.0),                   # tall, rank 16: a larger table of the one-launch Gram-Schmidt
+    ([(20000, 16)], 16, 8, 8, 3, 255.0),                   # tall, rank 16, 79 slices: Cholesky-QR in its form of three launches
+    ([(17000, 40)], 32, 8, 8, 2, 255.0),                   # the same at rank pad 32 (67 slices)
 ]
 
 
@@ -353,7 +354,8 @@ def test_resnet18_free_run_matches_oracle_and_is_deterministic():
     ([(200, 1100), (10, 512), (64, 27)], 32, 3),      # narrow matrix-core sweep 0, padded operand copies
     ([(129, 1028), (70, 27)], 16, 2),
     ([(100, 1100), (70, 200)], 50, 2),                 # rank pad 64
-    ([(20000, 16)], 16, 3),                            # tall factor: Gram-Schmidt in 79 slices, one launch
+    ([(20000, 16)], 16, 3),                            # tall factor: Gram-Schmidt in 79 slices (Cholesky-QR, three launches)
+    ([(8192, 96)], 32, 2),                             # tall factor, 32 slices: the one-launch form
 ])
 def test_three_steps_twice_give_the_same_bits(layers, rank, W):
     import torch
