@@ -1563,31 +1563,46 @@ __global__ __launch_bounds__(256) void reduce_q_kernel(DevArgs a, const RTile* _
   const int layer = tl.lw / a.W, worker = tl.lw - layer * a.W;
   const LayerDesc& ld = a.layers[layer];
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
-  const int e = tl.el0 + tid * 4;
   float mx = 0.0f;
   // phase 1: Q_w from the row-block planes; phase 0 (aggregate-first order only): the raw P_w from
   // the column-segment planes, which is then what the P exchange quantises
   const int n_el = phase ? ld.nq_el : ld.np_el;
-  if (e < n_el) {
-    const float* Qp = phase ? a.Qpart + (size_t)worker * a.qpart_stride + ld.qpart_off + e
-                            : a.Ppart + (size_t)worker * a.ppart_stride + ld.ppart_off + e;
-    const int nplanes = phase ? ld.nrb : ld.nseg;
-    const size_t pitch = phase ? ld.nq_pad : ld.np_pad;
+  const float* planes = phase ? a.Qpart + (size_t)worker * a.qpart_stride + ld.qpart_off
+                              : a.Ppart + (size_t)worker * a.ppart_stride + ld.ppart_off;
+  float* out = phase ? a.Qw + (size_t)worker * a.q_stride + ld.q_off : a.Ppre + (size_t)worker * a.p_stride + ld.p_off;
+  const int nplanes = phase ? ld.nrb : ld.nseg;
+  const size_t pitch = phase ? ld.nq_pad : ld.np_pad;
+  for (int off = tid * 4; off < tl.n; off += 1024) {
+    const int e = tl.el0 + off;                    // < n_el, and so are the elements of its float4 that are kept
+    const float* Qp = planes + e;
     float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int rb = 0; rb < nplanes; ++rb) {
+    // planes are added in order; eight loads are in flight at a time
+    int rb = 0;
+    for (; rb + 8 <= nplanes; rb += 8) {
+      float4 t[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) t[i] = *reinterpret_cast<const float4*>(Qp + (size_t)(rb + i) * pitch);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) { s.x += t[i].x; s.y += t[i].y; s.z += t[i].z; s.w += t[i].w; }
+    }
+    for (; rb < nplanes; ++rb) {
       const float4 t = *reinterpret_cast<const float4*>(Qp + (size_t)rb * pitch);
       s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
     }
-    float* dst = phase ? a.Qw + (size_t)worker * a.q_stride + ld.q_off + e
-                       : a.Ppre + (size_t)worker * a.p_stride + ld.p_off + e;
+    float* dst = out + e;
     const int nv = min(4, n_el - e);
-    const float vals[4] = {s.x, s.y, s.z, s.w};
+    if (nv == 4) {
+      *reinterpret_cast<float4*>(dst) = s;
+      mx = fmaxf(mx, fmaxf(fmaxf(fabsf(s.x), fabsf(s.y)), fmaxf(fabsf(s.z), fabsf(s.w))));
+    } else {
+      const float vals[4] = {s.x, s.y, s.z, s.w};
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-      if (i < nv) {
-        dst[i] = vals[i];
-        mx = fmaxf(mx, fabsf(vals[i]));
-      }
+      for (int i = 0; i < 4; ++i)
+        if (i < nv) {
+          dst[i] = vals[i];
+          mx = fmaxf(mx, fabsf(vals[i]));
+        }
+    }
   }
   mx = wave_max(mx);
   if (lane == 0) redmax[wave] = mx;
@@ -2786,7 +2801,6 @@ __global__ __launch_bounds__(256, 2) void orth_chol_kernel(DevArgs a, int nslice
   if (phase == 2 && redo[lw] != 0) return;       // raised in phase 1, or by a faster slice just now: the pair is done again anyway
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
   const int row = slice * 256 + tid;
-  const bool live = row < rows;
   float* pre = a.Ppre + (size_t)worker * a.p_stride + ld.p_off;
   float* orth = a.Porth + (size_t)worker * a.p_stride + ld.p_off;
   float* scale = a.scaleP + (size_t)worker * a.L + layer;

@@ -146,6 +146,14 @@ int Plan::build(const lqsgd_config* c, const lqsgd_layer* ls, int32_t n_layers) 
   int64_t ppd_acc = 0, qpd_acc = 0;
   padded = false;
   wire_bytes = 0;
+  // the reduce passes: items of 1024 .. 8192 elements, as large as still leaves about 512 of them
+  // (one atomic maximum per item on a cell per (layer, worker); several loads in flight per thread)
+  auto reduce_chunk = [&](bool q) {
+    int64_t total = 0;
+    for (const LayerDesc& d : layers) total += q ? d.nq_el : d.np_el;
+    return (int32_t)(1024 * std::min<int64_t>(8, std::max<int64_t>(1, total * W / (1024 * 512))));
+  };
+  const int32_t rq_chunk = reduce_chunk(true), rp_chunk = reduce_chunk(false);
   for (int li = 0; li < L; ++li) {
     LayerDesc& d = layers[li];
     const int cw = kWave * d.vec;
@@ -223,9 +231,9 @@ int Plan::build(const lqsgd_config* c, const lqsgd_layer* ls, int32_t n_layers) 
           for (int32_t cg = 0; cg < (d.cols + kMfmaCols - 1) / kMfmaCols; ++cg)
             tilesBM.push_back(Tile{lw, rb * d.rbb, std::min(d.rbb, d.rows - rb * d.rbb), cg});
       if (!d.direct_q)
-        for (int32_t e = 0; e < d.nq_el; e += 1024) tilesRQ.push_back(RTile{lw, e});
+        for (int32_t e = 0; e < d.nq_el; e += rq_chunk) tilesRQ.push_back(RTile{lw, e, std::min(rq_chunk, d.nq_el - e)});
       if (agg_first)
-        for (int32_t e = 0; e < d.np_el; e += 1024) tilesRP.push_back(RTile{lw, e});
+        for (int32_t e = 0; e < d.np_el; e += rp_chunk) tilesRP.push_back(RTile{lw, e, std::min(rp_chunk, d.np_el - e)});
     }
     for (int32_t g = 0; g < gp; g += kXBlockGroups) tilesXP.push_back(XTile{li, g});
     for (int32_t g = 0; g < gq; g += kXBlockGroups) tilesXQ.push_back(XTile{li, g});

@@ -52,8 +52,8 @@ struct Tile {
 struct XTile {   // exchange kernels: kXBlockGroups groups of 8 elements starting at group grp0 of `layer`
   int32_t layer, grp0;
 };
-struct RTile {   // reduce_q: 1024 elements of (layer, worker) starting at el0
-  int32_t lw, el0;
+struct RTile {   // reduce_q: n elements of (layer, worker) starting at el0 (n <= 8192, el0 a multiple of 1024)
+  int32_t lw, el0, n;
 };
 struct VTile {   // vector_mean: 1024 elements of vector `vec` starting at el0
   int32_t vec, el0;
