@@ -781,13 +781,21 @@ __global__ __launch_bounds__(256) void orth_wide_kernel(DevArgs a, int j, int ns
   if (j == 0) {
     if (slice == 0 && tid == 0 && !a.orth_shared) a.scaleP[(size_t)worker * a.L + layer] = 0.0f;
     if (live) {
-      const float* Pp = a.Ppart + (size_t)worker * a.ppart_stride + (a.orth_shared ? ld.p_off : ld.ppart_off);
-      const int nseg = a.orth_shared ? 1 : ld.nseg;
-      for (int s = 0; s < nseg; ++s) {
-        const float* src = Pp + (size_t)s * ld.np_pad + (size_t)row * r;
+      if (only_if) {
+        // The Cholesky-QR kernels have left the sum of the planes in `pre`, and where Gram-Schmidt
+        // runs in place (the plane is the output) they have overwritten the plane itself.
 #pragma unroll
         for (int k = 0; k < RP; ++k)
-          if (k < r) v[k] += src[k];
+          if (k < r) v[k] = pre[(size_t)row * r + k];
+      } else {
+        const float* Pp = a.Ppart + (size_t)worker * a.ppart_stride + (a.orth_shared ? ld.p_off : ld.ppart_off);
+        const int nseg = a.orth_shared ? 1 : ld.nseg;
+        for (int s = 0; s < nseg; ++s) {
+          const float* src = Pp + (size_t)s * ld.np_pad + (size_t)row * r;
+#pragma unroll
+          for (int k = 0; k < RP; ++k)
+            if (k < r) v[k] += src[k];
+        }
       }
 #pragma unroll
       for (int k = 0; k < RP; ++k)

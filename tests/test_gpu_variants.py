@@ -63,6 +63,38 @@ def test_aggregate_first_staged(case):
     _say("  ", rep)
 
 
+# Aggregate-first on a tall factor at rank pad >= 16: Gram-Schmidt of the aggregate runs in place on
+# P-bar, through Cholesky-QR; with two nearly parallel columns its pivot test fails and the factor is
+# done column by column from the copy of the aggregate kept aside.  Both launch forms, same bits.
+@pytest.mark.parametrize("layers,rank,eps", [([(4608, 64)], 32, 4e-3), ([(2560, 200)], 16, 4e-3), ([(2560, 200)], 16, None)])
+def test_aggregate_first_tall_factor_with_nearly_dependent_columns(layers, rank, eps):
+    _say("case: aggregate-first, tall, Cholesky-QR", layers, rank, eps)
+    W = 2
+    rng = np.random.default_rng(rank)
+    ml = list(range(len(layers)))
+    Q = []
+    for r_, c_ in layers:
+        q = rng.standard_normal((c_, min(rank, r_, c_))).astype(f32)
+        if eps:
+            q[:, 3] = q[:, 1] + eps * rng.standard_normal(c_).astype(f32)
+        Q.append(q)
+    G = _inputs(rng, layers, W)
+    Gd = pu.to_device(G)
+    got = {}
+    for flags in (0, B.FLAG_NO_COOPERATIVE_LAUNCH):
+        comp = B.Compressor(B.layer_list(layers, ()), rank, 8, 8, W, 255.0, B.FLAG_AGGREGATE_FIRST | flags)
+        for l in ml:
+            comp.set_q(l, Q[l])
+        E = [[np.zeros(s, f32) for s in layers] for _ in range(W)]
+        rep = pu.StageReport()
+        pu.staged_iteration(comp, G, Gd, E, Q, ml, rep, aggregate_first=True)
+        got[flags] = [comp.get_factor(B.FACTOR_P_BAR, l) for l in ml] + [comp.get_factor(B.FACTOR_Q_BAR, l) for l in ml]
+        _say("  ", comp.launched_kernel(B.KERNEL_ORTH), rep)
+        comp.close()
+    for x, y in zip(got[0], got[B.FLAG_NO_COOPERATIVE_LAUNCH]):
+        assert np.array_equal(x, y), "the one-launch and the three-launch form differ"
+
+
 def test_p_mean_needs_the_flag():
     comp = B.Compressor(B.layer_list([(16, 8)], ()), 2, 8, 8, 2)
     with pytest.raises(B.LqsgdError) as ei:
