@@ -242,14 +242,15 @@ def test_model_update(layers, rank, bits, W, flags):
     a.close(); b.close()
 
 
-def test_expired_device_wait_is_reported(monkeypatch):
-    """The one-launch Gram-Schmidt for tall factors waits for other workgroups with
+@pytest.mark.parametrize("rank", [8, 32])     # column by column (orth_coop_kernel) / Cholesky-QR (orth_chol_kernel)
+def test_expired_device_wait_is_reported(monkeypatch, rank):
+    """The one-launch Gram-Schmidt kernels for tall factors wait for other workgroups with
     a bounded number of polls.  With the bound forced to one poll from the host the
     waits expire (the kernel still runs to its end), the context raises its status
     word, and every synchronising call reports it instead of returning bad data."""
     import torch
-    _say("case: expired device-side wait")
-    rows, cols, W, rank = 8192, 64, 4, 8
+    _say("case: expired device-side wait, rank", rank)
+    rows, cols, W = 8192, 64, 4
     rng = np.random.default_rng(3)
     G = [[torch.from_numpy((rng.standard_normal((rows, cols)) * 1e-3).astype(f32)).cuda()] for _ in range(W)]
     q0 = rng.standard_normal((cols, rank)).astype(f32)
