@@ -59,6 +59,9 @@ typedef const float __attribute__((address_space(4)))* const_fp;
 #ifndef LQSGD_RT           // rows a wavefront carries through one column pass of sweep 0 (rank <= 8)
 #define LQSGD_RT 8
 #endif
+#ifndef LQSGD_BM_U2
+#define LQSGD_BM_U2 4  // the same for the form with two blocks of 32 ranks (rank pad 64)
+#endif
 #ifndef LQSGD_BM_U
 #define LQSGD_BM_U 8   // pairs of rows per step of the matrix-core sweep 1 (4: 829 us, 8: 750 us, 16: 833 us at 8192^2 x 16)
 #endif
@@ -1377,6 +1380,10 @@ __device__ __forceinline__ void back_project_mfma_tile(const DevArgs& a, const L
           an[u] = ldrow<4, LQSGD_NT_M != 0>(reinterpret_cast<const char*>(M + (size_t)row * cols), (unsigned)cl * 4u);
           bn[u] = Pb[(size_t)row * r + lic];
         }
+        // the requests above stay ahead of the arithmetic below (left to itself the compiler moves the
+        // P-bar loads down to their first use, and every group of matrix instructions then waits for
+        // its operand and, requests completing in order, for the whole prefetch in front of it)
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int u = 0; u < UI; ++u)
 #pragma unroll
@@ -1445,37 +1452,39 @@ __device__ __forceinline__ void back_project_mfma_tile_nb(const DevArgs& a, cons
     for (int s = 0; s < 4; ++s)
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[nb][s][i] = 0.0f;
-  constexpr int U = 4;
+  constexpr int UI = LQSGD_BM_U2;  // pairs of rows per step on interior strips
+  constexpr int U = 4;             // ... and on the bounds-tested path
   int rb = tl.row0;
   if constexpr (VEC4) {
     // interior strips: as in the one-block form, whole groups of rows without bounds tests and the
     // next group's loads ahead of this group's matrix instructions; ranks beyond r are read from a
     // clamped index and masked
-    if (c0 + 128 <= cols && rend - rb >= 2 * U) {
-      const int last = rb + ((rend - rb) / (2 * U) - 1) * (2 * U);
-      Pk<4> am[U], an[U];
-      float bp[NB][U], bn[NB][U];
+    if (c0 + 128 <= cols && rend - rb >= 2 * UI) {
+      const int last = rb + ((rend - rb) / (2 * UI) - 1) * (2 * UI);
+      Pk<4> am[UI], an[UI];
+      float bp[NB][UI], bn[NB][UI];
       int rkc[NB];
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb) rkc[nb] = min(32 * nb + li, r - 1);
 #pragma unroll
-      for (int u = 0; u < U; ++u) {
+      for (int u = 0; u < UI; ++u) {
         const int row = rb + 2 * u + h;
         am[u] = ldrow<4, LQSGD_NT_M != 0>(reinterpret_cast<const char*>(M + (size_t)row * cols), (unsigned)cl * 4u);
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) bp[nb][u] = Pb[(size_t)row * r + rkc[nb]];
       }
-      for (; rb <= last; rb += 2 * U) {
-        const int nxt = min(rb + 2 * U, last);
+      for (; rb <= last; rb += 2 * UI) {
+        const int nxt = min(rb + 2 * UI, last);
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
+        for (int u = 0; u < UI; ++u) {
           const int row = nxt + 2 * u + h;
           an[u] = ldrow<4, LQSGD_NT_M != 0>(reinterpret_cast<const char*>(M + (size_t)row * cols), (unsigned)cl * 4u);
 #pragma unroll
           for (int nb = 0; nb < NB; ++nb) bn[nb][u] = Pb[(size_t)row * r + rkc[nb]];
         }
+        __builtin_amdgcn_sched_barrier(0);   // as in the one-block form: the requests stay ahead of the arithmetic
 #pragma unroll
-        for (int u = 0; u < U; ++u)
+        for (int u = 0; u < UI; ++u)
 #pragma unroll
           for (int nb = 0; nb < NB; ++nb) {
             const float bv = keep_if(bp[nb][u], rankok[nb]);
@@ -1484,7 +1493,7 @@ __device__ __forceinline__ void back_project_mfma_tile_nb(const DevArgs& a, cons
               acc[nb][s] = __builtin_amdgcn_mfma_f32_32x32x2f32(am[u].v[s], bv, acc[nb][s], 0, 0, 0);
           }
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
+        for (int u = 0; u < UI; ++u) {
           am[u] = an[u];
 #pragma unroll
           for (int nb = 0; nb < NB; ++nb) bp[nb][u] = bn[nb][u];
