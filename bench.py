@@ -268,14 +268,14 @@ def _rank_sweep(B, wl, torch):
             w = wl.scaled(base, rank=r, bits=b)
             comp = B.Compressor(B.layer_list(w.layers, w.vectors), r, b, b, W, w.alpha)
             comp.set_q(0, wl.initial_q(w, 0))
-            for _ in range(2):
+            for _ in range(3):
                 comp.step(grads, ghat)
             torch.cuda.synchronize()
             t0 = time.perf_counter()
-            for _ in range(5):
+            for _ in range(20):
                 comp.step(grads, ghat)
             torch.cuda.synchronize()
-            ms = (time.perf_counter() - t0) * 1e3 / 5
+            ms = (time.perf_counter() - t0) * 1e3 / 20
             comp.timing_enable(True)
             for _ in range(5):
                 comp.step(grads, ghat)
