@@ -238,6 +238,8 @@ def test_gram_schmidt_with_nearly_dependent_columns(layers, rank, eps):
     ([(4096, 300)], 16, 2, 4e-3),                     # two nearly parallel columns: a pivot below the floor
     ([(5000, 96)], 50, 2, 4e-3),
     ([(2600, 72)], 32, 2, 0.3),                       # columns at an angle the factorisation still takes
+    ([(8192, 96)], 32, 2, 0.03),                      # ... and close to its pivot floor (ratio about 5e-4)
+    ([(4096, 300)], 50, 2, 0.03),
     ([(4096, 300)], 16, 3, "zero"),                   # one worker's gradient is zero: P_w = 0
 ])
 def test_tall_gram_schmidt_by_cholesky_qr(layers, rank, W, special):
