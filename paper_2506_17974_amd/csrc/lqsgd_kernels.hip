@@ -2448,7 +2448,7 @@ __global__ __launch_bounds__(256) void pad_factor_kernel(DevArgs a, int RP, int 
 }
 
 // ---------------------------------------------------------------------------
-// orth of tall factors at rank pads >= 16: Cholesky-QR, applied twice.
+// orth of tall factors at rank pads >= 8: Cholesky-QR, applied twice.
 // The column-by-column form above pays one exchange between the slices of a
 // factor per column (about 10 us each: r = 32 columns cost 0.33 ms on a factor
 // of 8192 rows, where all the arithmetic is a few microseconds).  Here the
@@ -2489,7 +2489,7 @@ constexpr float kCholPivotFloor = 1e-4f;
 
 template <int RP>
 struct CholShape {
-  static_assert(RP == 16 || RP == 32 || RP == 64, "rank pads of the matrix-core sweeps");
+  static_assert(RP == 8 || RP == 16 || RP == 32 || RP == 64, "rank pads with a Cholesky-QR form");
   static constexpr int NB = RP <= 32 ? 1 : 3;                       // 32 x 32 blocks kept: (0,0) or (0,0), (0,1), (1,1)
   static constexpr int NE = RP <= 32 ? RP * RP : 3 * 1024;          // entries exchanged
   static constexpr int QN = (NE + 255) / 256;                       // ... per thread
@@ -3087,6 +3087,7 @@ bool launch_orth_chol_coop(int rp, int nslice, int max_rank, const DevArgs& a, i
   }
   if (cap != hipStreamCaptureStatusNone) return false;      // a replay would repeat this launch's tags
   switch (rp) {
+    case 8: return try_orth_chol_coop<8>(nslice, max_rank, a, nblocks, cs, s);
     case 16: return try_orth_chol_coop<16>(nslice, max_rank, a, nblocks, cs, s);
     case 32: return try_orth_chol_coop<32>(nslice, max_rank, a, nblocks, cs, s);
     case 64: return try_orth_chol_coop<64>(nslice, max_rank, a, nblocks, cs, s);
@@ -3105,7 +3106,7 @@ void launch_orth_chol_split(int nslice, int max_rank, const DevArgs& a, int nblo
 }
 
 int chol_entries(int rp) {
-  return rp == 16 ? CholShape<16>::NE : rp == 32 ? CholShape<32>::NE : rp == 64 ? CholShape<64>::NE : 0;
+  return rp == 8 ? CholShape<8>::NE : rp == 16 ? CholShape<16>::NE : rp == 32 ? CholShape<32>::NE : rp == 64 ? CholShape<64>::NE : 0;
 }
 
 hipError_t launch_orth(int rp, int max_rows, int max_rank, const DevArgs& a, CoopState* coop, hipStream_t s) {
@@ -3122,9 +3123,10 @@ hipError_t launch_orth(int rp, int max_rows, int max_rank, const DevArgs& a, Coo
 #else
     constexpr bool chol = true;
 #endif
-    if (chol && rp >= 16 && a.chol_part && a.chol_redo) {
+    if (chol && rp >= 8 && a.chol_part && a.chol_redo) {
       if (launch_orth_chol_coop(rp, nslice, max_rank, a, (int)grid.x * nslice, coop, s)) return hipSuccess;
-      if (rp == 16) launch_orth_chol_split<16>(nslice, max_rank, a, (int)grid.x * nslice, s);
+      if (rp == 8) launch_orth_chol_split<8>(nslice, max_rank, a, (int)grid.x * nslice, s);
+      else if (rp == 16) launch_orth_chol_split<16>(nslice, max_rank, a, (int)grid.x * nslice, s);
       else if (rp == 32) launch_orth_chol_split<32>(nslice, max_rank, a, (int)grid.x * nslice, s);
       else launch_orth_chol_split<64>(nslice, max_rank, a, (int)grid.x * nslice, s);
       return hipGetLastError();
