@@ -224,7 +224,7 @@ def test_gram_schmidt_with_nearly_dependent_columns(layers, rank, eps):
 
 
 # ---------------------------------------------------------------------------
-# Tall factors at rank pads >= 16: Orthogonalize (Algorithm 1) through two rounds of Cholesky-QR
+# Tall factors at rank pads >= 8: Orthogonalize (Algorithm 1) through two rounds of Cholesky-QR
 # instead of column by column.  Every stage is held against the oracle's Gram-Schmidt; the one
 # cooperative launch and the form of three launches must agree bit for bit; pairs whose pivots fall
 # below the floor (nearly dependent columns, an all-zero gradient) are done column by column, again
@@ -232,6 +232,8 @@ def test_gram_schmidt_with_nearly_dependent_columns(layers, rank, eps):
 # ---------------------------------------------------------------------------
 @pytest.mark.parametrize("layers,rank,W,special", [
     ([(4096, 300)], 16, 4, None),
+    ([(4096, 300)], 8, 3, None),                      # rank pad 8
+    ([(2304, 200)], 7, 2, 4e-3),
     ([(2600, 36), (3000, 64)], 32, 2, None),
     ([(8192, 128)], 50, 2, None),
     ([(2304, 200), (300, 40)], 20, 3, None),          # rank below its pad; a short layer in the same launch
@@ -255,7 +257,7 @@ def test_tall_gram_schmidt_by_cholesky_qr(layers, rank, W, special):
     if special == "zero":
         G[W - 1][0][:] = 0.0
     Gd = pu.to_device(G)
-    rp = 16 if rank <= 16 else 32 if rank <= 32 else 64
+    rp = 8 if rank <= 8 else 16 if rank <= 16 else 32 if rank <= 32 else 64
     got = {}
     for flags, name in ((0, "orth_chol_kernel<%d>" % rp), (B.FLAG_NO_COOPERATIVE_LAUNCH, "orth_chol_kernel<%d> x 3 launches" % rp)):
         comp, ml = _make(layers, (), rank, 8, 8, W, flags=flags)
