@@ -2482,7 +2482,7 @@ __global__ __launch_bounds__(256) void pad_factor_kernel(DevArgs a, int RP, int 
 // give the same bits; pairs that need the column-by-column form raise redo[pair]
 // and the guarded orth_wide_kernel launches that follow do them.
 // ---------------------------------------------------------------------------
-// On the CPU, in float32, two rounds stay as close to the float64 Gram-Schmidt as float32 Gram-Schmidt
+// On the CPU, in float32, two passes stay as close to the float64 Gram-Schmidt as float32 Gram-Schmidt
 // itself down to pivot ratios of about 1e-6 (both 1e-6 .. 1e-5 away at ratios 2e-4 .. 1e-5); the floor
 // keeps two orders of magnitude from where the factorisation starts to break down.
 constexpr float kCholPivotFloor = 1e-4f;

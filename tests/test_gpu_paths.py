@@ -224,7 +224,7 @@ def test_gram_schmidt_with_nearly_dependent_columns(layers, rank, eps):
 
 
 # ---------------------------------------------------------------------------
-# Tall factors at rank pads >= 8: Orthogonalize (Algorithm 1) through two rounds of Cholesky-QR
+# Tall factors at rank pads >= 8: Orthogonalize (Algorithm 1) through two passes of Cholesky-QR
 # instead of column by column.  Every stage is held against the oracle's Gram-Schmidt; the one
 # cooperative launch and the form of three launches must agree bit for bit; pairs whose pivots fall
 # below the floor (nearly dependent columns, an all-zero gradient) are done column by column, again
