@@ -237,6 +237,7 @@ def test_gram_schmidt_with_nearly_dependent_columns(layers, rank, eps):
     ([(2600, 36), (3000, 64)], 32, 2, None),
     ([(8192, 128)], 50, 2, None),
     ([(2304, 200), (300, 40)], 20, 3, None),          # rank below its pad; a short layer in the same launch
+    ([(4096, 300), (2600, 12), (2305, 9)], 16, 2, None),   # layers whose own rank is clipped by their width (12, 9); a ragged last slice
     ([(4096, 300)], 16, 2, 4e-3),                     # two nearly parallel columns: a pivot below the floor
     ([(5000, 96)], 50, 2, 4e-3),
     ([(2600, 72)], 32, 2, 0.3),                       # columns at an angle the factorisation still takes
