@@ -286,3 +286,23 @@ def test_tall_gram_schmidt_by_cholesky_qr(layers, rank, W, special):
         comp.close()
     for x, y in zip(got[0], got[B.FLAG_NO_COOPERATIVE_LAUNCH]):
         assert np.array_equal(x, y), "the one-launch and the three-launch form differ"
+
+
+def test_more_tall_factors_than_one_launch_can_hold():
+    """100 (layer, worker) pairs of 16 slices each are more workgroups than fit the chip at once: the
+    Cholesky-QR Gram-Schmidt has to take its three-launch form by itself (no flag), and the sampled
+    layers and workers must still agree with the oracle at every stage."""
+    _say("case: tall factors, one-launch form does not fit")
+    layers, rank, W = [(4096, 256)] * 20, 16, 5
+    rng = np.random.default_rng(5)
+    comp, ml = _make(layers, (), rank, 8, 8, W)
+    Q = [rng.standard_normal((c, rank)).astype(f32) for r, c in layers]
+    for l in ml:
+        comp.set_q(l, Q[l])
+    G = _random_inputs(rng, layers, W)
+    E = [[np.zeros(s, f32) for s in layers] for _ in range(W)]
+    rep = pu.StageReport()
+    pu.staged_iteration(comp, G, pu.to_device(G), E, Q, ml, rep, layers_to_check=[0, 7, 13, 19], workers_to_check=[0, 2, 4])
+    assert comp.launched_kernel(B.KERNEL_ORTH) == "orth_chol_kernel<16> x 3 launches", comp.launched_kernel(B.KERNEL_ORTH)
+    _say("  ", rep)
+    comp.close()
